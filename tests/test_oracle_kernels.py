@@ -1,0 +1,358 @@
+"""Pins for oracle/gd_oracle.c: its fence against the Python model and the
+paper's example, its kernels against textbook NumPy routines on in-bounds
+inputs, and against a per-byte Python retelling plus confinement on tiny pools
+when accesses are out of bounds.  Nothing here calls the HIP library.
+"""
+import math
+import random
+import struct
+
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import host_model as hm
+from oracle import kernels as ok
+
+KiB = 1024
+BASE = 0x7FA2D0000000            # Section 4.3's example base, 16 MiB aligned
+
+
+def make_pool(sizes, fill=0, pool_base=BASE):
+    table = hm.carve(pool_base, sum(sizes), sizes)
+    pool = ok.SimPool(pool_base, sum(sizes), fill)
+    return pool, table
+
+
+# ---------------------------------------------------------------------------
+# fence
+# ---------------------------------------------------------------------------
+
+def test_c_fence_matches_printed_example(golden):
+    (base, size, end, mask), = golden("section4_3_mask_example.txt")
+    base, size, end = int(base, 16), int(size), int(end, 16)
+    assert ok.fence(base, size, end + 1) == base
+    assert ok.fence(base, size, base - 1) == end
+    assert ok.fence(base, size, base - size + 0xABCDE) == base + 0xABCDE
+    assert ok.fence(base, size, end) == end
+
+
+@pytest.mark.parametrize("width", hm.ACCESS_WIDTHS)
+def test_c_fence_equals_python_model_everywhere_on_tiny_pool(width):
+    sizes = [4 * KiB, 32 * KiB, 8 * KiB, 4 * KiB, 16 * KiB]
+    pool_base, pool_bytes = 0x40000, 64 * KiB
+    table = hm.carve(pool_base, pool_bytes, sizes)
+    addrs = np.arange(pool_base - 2 * pool_bytes, pool_base + 3 * pool_bytes, dtype=np.uint64)
+    for (base, size) in table:
+        got = ok.fence_array(base, size, addrs, width)
+        want = (addrs & np.uint64((size - 1) & ~(width - 1))) | np.uint64(base)
+        assert np.array_equal(got, want)
+        # spot check the vector expression itself against the integer model
+        for a in addrs[::997]:
+            assert ok.fence(base, size, int(a), width) == hm.fence(int(a), base, size, width)
+        assert got.min() >= base and got.max() + width - 1 <= base + size - 1
+
+
+def test_c_fence_modes_on_random_64bit_addresses():
+    rnd = random.Random(5)
+    for _ in range(20000):
+        size = 1 << rnd.randint(12, 40)
+        base = size * rnd.randint(1, 1 << 10)
+        a = rnd.getrandbits(64)
+        w = rnd.choice(hm.ACCESS_WIDTHS)
+        assert ok.fence(base, size, a, w, ok.MODE_BITWISE) == hm.fence(a, base, size, w)
+        assert ok.fence(base, size, a, 1, ok.MODE_MODULO) == hm.fence_modulo(a, base, size)
+        assert ok.fence(base, size, a, 1, ok.MODE_MODULO) == ok.fence(base, size, a, 1, ok.MODE_BITWISE)
+        chk = ok.fence(base, size, a, w, ok.MODE_CHECK)
+        assert (chk == a) == hm.check_access(a, base, size, w)
+        assert chk in (a, hm.U64)
+        assert ok.fence(base, size, a, w, ok.MODE_NONE) == a
+
+
+def test_modulo_mode_accepts_unaligned_odd_sized_partitions():
+    base, size = 1000, 300            # Section 4.4: modulo needs no alignment
+    for a in range(0, 5000):
+        f = ok.fence(base, size, a, 1, ok.MODE_MODULO)
+        assert base <= f < base + size
+        if a >= base:                     # below the base the 64-bit subtraction wraps
+            assert (f - a) % size == 0
+        if base <= a < base + size:
+            assert f == a
+
+
+# ---------------------------------------------------------------------------
+# bfloat16 rounding
+# ---------------------------------------------------------------------------
+
+def test_bf16_rounding_closed_forms_and_library():
+    L = ok.lib()
+    one = 0x3F80
+    assert L.gdo_double_to_bf16(1.0) == one
+    assert L.gdo_double_to_bf16(1.0 + 2.0**-8) == one             # tie -> even (down)
+    assert L.gdo_double_to_bf16(1.0 + 3 * 2.0**-8) == one + 2     # tie -> even (up)
+    assert L.gdo_double_to_bf16(1.0 + 2.0**-8 + 2.0**-40) == one + 1
+    assert L.gdo_double_to_bf16(-2.5) == 0xC020
+    assert L.gdo_double_to_bf16(0.0) == 0 and L.gdo_double_to_bf16(-0.0) == 0x8000
+    assert L.gdo_double_to_bf16(1e40) == 0x7F80 and L.gdo_double_to_bf16(-1e40) == 0xFF80
+    assert L.gdo_double_to_bf16(2.0**-133) == 0x0001               # smallest subnormal
+    assert L.gdo_double_to_bf16(2.0**-134) == 0x0000               # tie to even -> 0
+    assert L.gdo_double_to_bf16(1.5 * 2.0**-134) == 0x0001
+    # float32 inputs: one rounding step either way, so torch's conversion agrees
+    g = np.random.Generator(np.random.PCG64(3))
+    x = np.concatenate([g.standard_normal(20000).astype(np.float32),
+                        (g.standard_normal(2000) * 1e-39).astype(np.float32),
+                        (g.standard_normal(2000) * 1e30).astype(np.float32)])
+    want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = np.array([L.gdo_double_to_bf16(float(v)) for v in x], dtype=np.uint16)
+    assert np.array_equal(got, want)
+    assert np.array_equal(si.f32_to_bf16_bits(x), want)             # the input generator's rounding too
+    for h in (0x0000, 0x3F80, 0xC020, 0x0001, 0x7F7F):
+        f = struct.unpack("<f", struct.pack("<I", h << 16))[0]
+        assert L.gdo_bf16_to_double(h) == f
+
+
+# ---------------------------------------------------------------------------
+# kernels on in-bounds inputs reduce to textbook routines
+# ---------------------------------------------------------------------------
+
+@pytest.fixture()
+def one_tenant():
+    pool, table = make_pool([1 << 20, 1 << 20], fill=0xA5)
+    return pool, table[0], table[1]
+
+
+@pytest.mark.parametrize("mode", [ok.MODE_NONE, ok.MODE_BITWISE, ok.MODE_MODULO, ok.MODE_CHECK])
+def test_streaming_kernels_are_memcpy_and_axpy(one_tenant, mode):
+    pool, row, other = one_tenant
+    n = 50001
+    g = si.rng(0)
+    a, b, c = row[0], row[0] + 256 * KiB, row[0] + 512 * KiB
+    vb, vc = si.uniform_f32(g, n), si.uniform_f32(g, n)
+    pool.view(b, np.float32, n)[:] = vb
+    pool.view(c, np.float32, n)[:] = vc
+    before_other = pool.view(other[0], np.uint8, other[1]).copy()
+    assert pool.run("copy", row, mode, a, b, n) == (0, 0, 0)
+    assert np.array_equal(pool.view(a, np.float32, n), vb)
+    s = -0.37
+    assert pool.run("triad", row, mode, a, b, c, s, n) == (0, 0, 0)
+    want = (vb.astype(np.float64) + s * vc.astype(np.float64)).astype(np.float32)
+    assert np.array_equal(pool.view(a, np.float32, n), want)
+    assert pool.view(a, np.float32, n + 1)[n] != want[-1]          # nothing past n written
+    pool.run("store_tid", row, mode, a, 77, n)
+    assert np.all(pool.view(a, np.uint32, n) == 77)
+    assert np.array_equal(pool.view(other[0], np.uint8, other[1]), before_other)
+
+
+def test_indexed_kernels_are_fancy_indexing(one_tenant):
+    pool, row, _ = one_tenant
+    n = 20000
+    g = si.rng(0, 1)
+    x, y, off, out = (row[0] + k * 128 * KiB for k in range(4))
+    vx, vy = si.uniform_f32(g, n), si.uniform_f32(g, n)
+    perm = g.permutation(n).astype(np.int32)
+    pool.view(x, np.float32, n)[:] = vx
+    pool.view(y, np.float32, n)[:] = vy
+    pool.view(off, np.int32, n)[:] = perm
+    alpha = 0.8125
+    pool.run("saxpy_idx", row, ok.MODE_BITWISE, x, y, off, alpha, n)
+    want = (alpha * vx.astype(np.float64) + vy.astype(np.float64)).astype(np.float32)
+    assert np.array_equal(pool.view(y, np.float32, n), want)       # a permutation touches each once
+
+    # gather, 64-bit and 32-bit indices (duplicates allowed)
+    idx64 = g.integers(0, n, size=n, dtype=np.int64)
+    idxp = row[0] + 512 * KiB
+    pool.view(idxp, np.int64, n)[:] = idx64
+    pool.run("gather32_i64", row, ok.MODE_BITWISE, out, x, idxp, n)
+    assert np.array_equal(pool.view(out, np.float32, n), vx[idx64])
+    pool.view(idxp, np.int32, n)[:] = idx64.astype(np.int32)
+    pool.view(out, np.float32, n)[:] = 0
+    pool.run("gather32_i32", row, ok.MODE_BITWISE, out, x, idxp, n)
+    assert np.array_equal(pool.view(out, np.float32, n), vx[idx64])
+
+    # scatter with unique indices
+    pool.view(idxp, np.int64, n)[:] = perm.astype(np.int64)
+    pool.run("scatter_f32_i64", row, ok.MODE_BITWISE, y, x, idxp, -1.0, n)
+    want = np.empty(n, np.float32)
+    want[perm] = -vx
+    assert np.array_equal(pool.view(y, np.float32, n), want)
+
+
+def test_negative_offsets_and_indices_are_signed(one_tenant):
+    pool, row, _ = one_tenant
+    n = 64
+    x, y, off = row[0] + 4 * KiB, row[0] + 8 * KiB, row[0] + 12 * KiB
+    pool.view(x - 256, np.float32, 128)[:] = np.arange(128, dtype=np.float32)
+    pool.view(y - 256, np.float32, 128)[:] = 1000 + np.arange(128, dtype=np.float32)
+    offs = -np.arange(n, dtype=np.int32)
+    pool.view(off, np.int32, n)[:] = offs
+    pool.run("saxpy_idx", row, ok.MODE_BITWISE, x, y, off, 2.0, n)
+    got = pool.view(y - 256, np.float32, 128)
+    for k in range(128):
+        e = k - 64
+        want = 2.0 * k + 1000 + k if -n < e <= 0 else 1000 + k
+        assert got[k] == want
+
+
+def test_sum_matches_fsum(one_tenant):
+    pool, row, _ = one_tenant
+    n = 100003
+    v = si.uniform_f32(si.rng(0, 2), n, 0.0, 1.0)
+    src, out = row[0], row[0] + 512 * KiB
+    pool.view(src, np.float32, n)[:] = v
+    pool.run("sum_f32", row, ok.MODE_BITWISE, out, src, n)
+    exact = math.fsum(float(t) for t in v)
+    assert pool.view(out, np.float32, 1)[0] == np.float32(exact)
+    assert abs(pool.run("sum_f32_exact", row, ok.MODE_BITWISE, src, n) - exact) <= 1e-12 * exact
+
+
+def test_rmsnorm_matches_formula(one_tenant):
+    pool, row, _ = one_tenant
+    rows, cols, eps = 7, 384, 1e-6
+    g = si.rng(0, 3)
+    xb = si.f32_to_bf16_bits(si.normal_f32(g, rows * cols))
+    gb = si.f32_to_bf16_bits(si.uniform_f32(g, cols, 0.5, 1.5))
+    x, gain, y = row[0], row[0] + 64 * KiB, row[0] + 128 * KiB
+    pool.view(x, np.uint16, rows * cols)[:] = xb
+    pool.view(gain, np.uint16, cols)[:] = gb
+    pool.run("rmsnorm_bf16", row, ok.MODE_BITWISE, y, x, gain, rows, cols, eps)
+    xf = si.bf16_bits_to_f32(xb).astype(np.float64).reshape(rows, cols)
+    gf = si.bf16_bits_to_f32(gb).astype(np.float64)
+    ref = xf / np.sqrt((xf * xf).mean(axis=1, keepdims=True) + eps) * gf
+    got = si.bf16_bits_to_f32(pool.view(y, np.uint16, rows * cols)).astype(np.float64).reshape(rows, cols)
+    # the result is the nearest bfloat16: within half a unit in the last place
+    assert np.all(np.abs(got - ref) <= 2.0**-8 * np.abs(ref) * (1 + 1e-12))
+    # rows of unit gain have unit mean square up to the output rounding
+    pool.view(gain, np.uint16, cols)[:] = 0x3F80
+    pool.run("rmsnorm_bf16", row, ok.MODE_BITWISE, y, x, gain, rows, cols, 0.0)
+    got = si.bf16_bits_to_f32(pool.view(y, np.uint16, rows * cols)).astype(np.float64).reshape(rows, cols)
+    assert np.allclose((got * got).mean(axis=1), 1.0, rtol=5e-3)
+
+
+@pytest.mark.parametrize("b_is_nk", [0, 1])
+def test_gemm_matches_numpy_matmul(one_tenant, b_is_nk):
+    pool, row, _ = one_tenant
+    M, N, K = 13, 22, 37                 # all different: a swapped extent shows
+    g = si.rng(0, 4)
+    Ab = si.f32_to_bf16_bits(si.normal_f32(g, M * K))
+    Bb = si.f32_to_bf16_bits(si.normal_f32(g, K * N))
+    A, B, Cc = row[0], row[0] + 64 * KiB, row[0] + 128 * KiB
+    Af = si.bf16_bits_to_f32(Ab).astype(np.float64).reshape(M, K)
+    Bf = si.bf16_bits_to_f32(Bb).astype(np.float64).reshape(K, N)
+    pool.view(A, np.uint16, M * K)[:] = Ab
+    stored = Bb.reshape(K, N).T.copy().reshape(-1) if b_is_nk else Bb
+    pool.view(B, np.uint16, K * N)[:] = stored
+    pool.run("gemm_bf16", row, ok.MODE_BITWISE, Cc, A, B, M, N, K, b_is_nk, 0, M, 0, N)
+    ref = Af @ Bf
+    got = si.bf16_bits_to_f32(pool.view(Cc, np.uint16, M * N)).astype(np.float64).reshape(M, N)
+    assert np.all(np.abs(got - ref) <= 2.0**-8 * np.abs(ref) + 1e-12)
+    want_bits = torch.from_numpy(ref.astype(np.float32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    # double -> float -> bfloat16 may differ from the single rounding in rare ties only
+    assert np.mean(pool.view(Cc, np.uint16, M * N) != want_bits.reshape(-1)) < 0.01
+    e = pool.run("gemm_bf16_entry", row, ok.MODE_BITWISE, A, B, N, K, b_is_nk, 5, 9)
+    assert abs(e - ref[5, 9]) <= 1e-12 * max(1.0, abs(ref[5, 9]))
+    # a slab request writes only the slab
+    pool.view(Cc, np.uint16, M * N)[:] = 0
+    pool.run("gemm_bf16", row, ok.MODE_BITWISE, Cc, A, B, M, N, K, b_is_nk, 2, 4, 3, 8)
+    nz = pool.view(Cc, np.uint16, M * N).reshape(M, N) != 0
+    assert nz[2:4, 3:8].all() and nz.sum() == 2 * 5
+
+
+# ---------------------------------------------------------------------------
+# out-of-bounds behaviour on tiny pools
+# ---------------------------------------------------------------------------
+
+def py_saxpy_idx(mem, pool_base, base, size, x, y, off, alpha, n):
+    """Per-byte retelling of the indexed saxpy in Python integers (tiny inputs)."""
+    def F(a):
+        return hm.fence(a & hm.U64, base, size, 4) - pool_base
+    for i in range(n):
+        o, = struct.unpack_from("<i", mem, F(off + 4 * i))
+        vx, = struct.unpack_from("<f", mem, F(x + 4 * o))
+        vy, = struct.unpack_from("<f", mem, F(y + 4 * o))
+        r = np.float32(alpha * float(vx) + float(vy))
+        struct.pack_into("<f", mem, F(y + 4 * o), r)
+
+
+def test_out_of_bounds_saxpy_wraps_into_own_partition_only():
+    sizes = [16 * KiB, 16 * KiB, 32 * KiB]
+    pool, table = make_pool(sizes, fill=0xA5, pool_base=1 << 20)
+    g = si.rng(0, 5)
+    for tenant in (0, 1):
+        base, size = table[tenant]
+        n = 1024
+        x, y, off = base, base + 4 * KiB, base + 8 * KiB
+        pool.view(x, np.float32, n)[:] = si.uniform_f32(g, n)
+        pool.view(y, np.float32, n)[:] = si.uniform_f32(g, n)
+        offs, where = si.c1_offsets(g, n, y, base, size, frac=0.05, reach=64 * KiB)
+        pool.view(off, np.int32, n)[:] = offs
+        snapshot = pool.mem.copy()
+        twin = bytearray(snapshot.tobytes())
+        esc, vio, wrapped = pool.run("saxpy_idx", table[tenant], ok.MODE_BITWISE, x, y, off, 0.5, n)
+        assert esc == 0 and vio == 0 and wrapped >= 3 * len(where) - 8
+        py_saxpy_idx(twin, pool.pool_base, base, size, x, y, off, 0.5, n)
+        assert pool.mem.tobytes() == bytes(twin)
+        lo, hi = base - pool.pool_base, base - pool.pool_base + size
+        assert np.array_equal(pool.mem[:lo], snapshot[:lo]) and np.array_equal(pool.mem[hi:], snapshot[hi:])
+        assert not np.array_equal(pool.mem[lo:hi], snapshot[lo:hi])
+
+
+def test_unfenced_out_of_bounds_store_does_corrupt_the_neighbour():
+    # What the fence is for: the same launch without it writes into tenant 1.
+    sizes = [4 * KiB, 4 * KiB]
+    pool, table = make_pool(sizes, fill=0xA5, pool_base=1 << 16)
+    base, size = table[0]
+    n = 2 * size // 4                                   # runs over the end of tenant 0
+    pool.run("store_tid", table[0], ok.MODE_NONE, base, 0x11111111, n)
+    assert np.all(pool.view(table[1][0], np.uint32, size // 4) == 0x11111111)
+    pool.mem[:] = 0xA5
+    esc, vio, wrapped = pool.run("store_tid", table[0], ok.MODE_BITWISE, base, 0x11111111, n)
+    assert wrapped == n // 2 and esc == 0
+    assert np.all(pool.view(table[1][0], np.uint8, size) == 0xA5)
+    assert np.all(pool.view(base, np.uint32, size // 4) == 0x11111111)
+    pool.mem[:] = 0xA5
+    esc, vio, wrapped = pool.run("store_tid", table[0], ok.MODE_CHECK, base, 0x11111111, n)
+    assert vio == n // 2 and wrapped == 0
+    assert np.all(pool.view(table[1][0], np.uint8, size) == 0xA5)
+    # leaving the simulated pool altogether is counted, not performed
+    esc, _, _ = pool.run("store_tid", table[0], ok.MODE_NONE, base + 2 * size - 8, 1, 4)
+    assert esc == 2
+
+
+def test_store_through_foreign_pointer_is_redirected():
+    # A tenant that passes another tenant's buffer as its own pointer reaches
+    # only its own partition, at the same offsets.
+    sizes = [8 * KiB, 8 * KiB]
+    pool, table = make_pool(sizes, fill=0, pool_base=1 << 16)
+    (b0, s0), (b1, s1) = table
+    pool.run("store_tid", table[0], ok.MODE_BITWISE, b1 + 64, 9, 100)
+    assert np.all(pool.view(b1, np.uint8, s1) == 0)
+    assert np.all(pool.view(b0 + 64, np.uint32, 100) == 9)
+
+
+def test_fence_addrs_probe_and_scatter_wrap():
+    sizes = [16 * KiB, 16 * KiB]
+    pool, table = make_pool(sizes, fill=0xA5, pool_base=1 << 20)
+    base, size = table[1]
+    n = 512
+    rnd = random.Random(9)
+    raw = np.array([rnd.getrandbits(64) for _ in range(n)], dtype=np.uint64)
+    src, dst = base, base + 8 * KiB
+    pool.view(src, np.uint64, n)[:] = raw
+    for w in hm.ACCESS_WIDTHS:
+        pool.run("fence_addrs", table[1], ok.MODE_BITWISE, dst, src, w, n)
+        want = [hm.fence(int(a), base, size, w) for a in raw]
+        assert pool.view(dst, np.uint64, n).tolist() == want
+    # scatter with far out-of-range 64-bit indices (only the low bits survive)
+    idx = np.array([rnd.getrandbits(63) for _ in range(64)], dtype=np.int64)
+    vals = np.arange(64, dtype=np.float32) + 1
+    pool.mem[:] = 0
+    idxp, srcp, tab = base + 4 * KiB, base + 8 * KiB, base
+    pool.view(idxp, np.int64, 64)[:] = idx
+    pool.view(srcp, np.float32, 64)[:] = vals
+    snapshot = pool.mem.copy()
+    pool.run("scatter_f32_i64", table[1], ok.MODE_BITWISE, tab, srcp, idxp, 1.0, 64)
+    changed = np.flatnonzero(pool.mem != snapshot)
+    assert changed.size and changed.min() >= base - pool.pool_base
+    images = {hm.fence((tab + 4 * int(k)) & hm.U64, base, size, 4) for k in idx}
+    assert {int(c) // 4 * 4 + pool.pool_base for c in changed} <= images
