@@ -1,0 +1,145 @@
+// extern "C" surface of libguardian (see include/guardian.h) and the kernel
+// registry: kernel id -> {name, size of its argument block, launcher}.  The
+// registry plays the role of the paper's pointerToSymbol map (Section 4.2.3):
+// at launch the manager looks the sandboxed kernel up, extends the parameters
+// by the tenant's base and mask taken from the partition bounds table, and
+// issues it on the tenant's stream; a tenant that runs with protection off
+// gets the native (unfenced) build of the same kernel.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <new>
+
+#include "launchers.hpp"
+#include "pool.hpp"
+
+namespace gd {
+
+static thread_local int g_last_hip_error = 0;
+void note_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
+
+struct KernelEntry {
+    const char *name;
+    size_t args_bytes;
+    Launcher launch;
+};
+
+static const KernelEntry g_registry[GD_K_COUNT] = {
+    /* GD_K_STORE_TID       */ {"store_tid", sizeof(gd_args_store_tid), launch_store_tid},
+    /* GD_K_FENCE_ADDRS     */ {"fence_addrs", sizeof(gd_args_fence_addrs), launch_fence_addrs},
+    /* GD_K_COPY            */ {"copy", sizeof(gd_args_copy), launch_copy},
+    /* GD_K_TRIAD           */ {"triad", sizeof(gd_args_triad), launch_triad},
+    /* GD_K_SAXPY_IDX       */ {"saxpy_idx", sizeof(gd_args_saxpy_idx), launch_saxpy_idx},
+    /* GD_K_GATHER32_I64    */ {"gather32_i64", sizeof(gd_args_gather), launch_gather32_i64},
+    /* GD_K_SCATTER_F32_I64 */ {"scatter_f32_i64", sizeof(gd_args_scatter), launch_scatter_f32_i64},
+    /* GD_K_GATHER32_I32    */ {"gather32_i32", sizeof(gd_args_gather), launch_gather32_i32},
+    /* GD_K_SUM_F32         */ {"sum_f32", sizeof(gd_args_sum), launch_sum_f32},
+    /* GD_K_RMSNORM_BF16    */ {"rmsnorm_bf16", sizeof(gd_args_rmsnorm), launch_rmsnorm_bf16},
+    /* GD_K_GEMM_BF16       */ {"gemm_bf16", sizeof(gd_args_gemm), launch_gemm_bf16},
+};
+
+}  // namespace gd
+
+extern "C" {
+
+int gd_pool_create(uint64_t dev_base, uint64_t dev_bytes, const uint64_t *part_bytes, int n_tenants,
+                   gd_pool **out)
+{
+    gd::Pool *p = nullptr;
+    int rc = gd::pool_create(dev_base, dev_bytes, part_bytes, n_tenants, &p);
+    if (rc == GD_OK) *out = p;
+    return rc;
+}
+
+int gd_pool_destroy(gd_pool *pool)
+{
+    if (!pool) return GD_EINVAL;
+    delete pool;
+    return GD_OK;
+}
+
+int gd_tenant_attach(gd_pool *pool, uint64_t bytes, int *tenant_out) { return gd::tenant_attach(pool, bytes, tenant_out); }
+int gd_tenant_detach(gd_pool *pool, int tenant) { return gd::tenant_detach(pool, tenant); }
+
+int gd_partition_info(const gd_pool *pool, int tenant, uint64_t *base, uint64_t *size, uint64_t *mask)
+{
+    return gd::partition_info(pool, tenant, base, size, mask);
+}
+
+int gd_alloc(gd_pool *pool, int tenant, uint64_t bytes, uint64_t align, uint64_t *dptr_out)
+{
+    return gd::alloc(pool, tenant, bytes, align, dptr_out);
+}
+
+int gd_free(gd_pool *pool, int tenant, uint64_t dptr) { return gd::free_(pool, tenant, dptr); }
+
+int gd_check_copy(const gd_pool *pool, int tenant, uint64_t dptr, uint64_t bytes)
+{
+    return gd::check_copy(pool, tenant, dptr, bytes);
+}
+
+uint64_t gd_fence_host(uint64_t base, uint64_t size, uint64_t addr, uint32_t width, int mode)
+{
+    return gd::fence_host(base, size, addr, width, mode);
+}
+
+int gd_kernel_count(void) { return GD_K_COUNT; }
+
+const char *gd_kernel_name(int id) { return (id >= 0 && id < GD_K_COUNT) ? gd::g_registry[id].name : nullptr; }
+
+size_t gd_kernel_args_bytes(int id) { return (id >= 0 && id < GD_K_COUNT) ? gd::g_registry[id].args_bytes : 0; }
+
+int gd_launch_fenced(gd_pool *pool, int tenant, int kernel_id, const void *args, size_t args_bytes,
+                     const uint32_t grid[3], const uint32_t block[3], void *hip_stream, int mode)
+{
+    if (!pool || !args) return GD_EINVAL;
+    if (kernel_id < 0 || kernel_id >= GD_K_COUNT) return GD_ENOKERNEL;
+    const gd::KernelEntry &k = gd::g_registry[kernel_id];                    // lookup
+    if (args_bytes != k.args_bytes) return GD_EINVAL;
+
+    uint64_t base = 0, size = 0, mask = 0;
+    int rc = gd::partition_info(pool, tenant, &base, &size, &mask);          // bounds table row
+    if (rc != GD_OK) return rc;
+
+    int variant;
+    switch (mode) {
+    case GD_FENCE_NONE:
+        variant = gd::V_NONE;
+        break;
+    case GD_FENCE_BITWISE:
+        // A mask that fits 32 bits lets the kernel fence a 32-bit offset and add
+        // the base in the addressing mode; larger partitions fence the high word.
+        variant = (mask <= 0xffffffffull) ? gd::V_BIT32 : gd::V_BIT64;
+        break;
+    default:
+        return GD_ENOKERNEL;
+    }
+
+    alignas(16) unsigned char copy[64];                                      // parameter augmentation
+    static_assert(sizeof(gd_args_gemm) <= sizeof(copy) && sizeof(gd_args_scatter) <= sizeof(copy), "args copy too small");
+    std::memcpy(copy, args, args_bytes);
+    const gd::FenceArgs extra = {base, mask};
+    const gd::Shape shape = {grid, block};
+    return k.launch(copy, extra, variant, shape, static_cast<hipStream_t>(hip_stream));
+}
+
+const char *gd_strerror(int status)
+{
+    switch (status) {
+    case GD_OK: return "ok";
+    case GD_EINVAL: return "invalid argument";
+    case GD_ENOTPOW2: return "partition size is not a power of two of at least 4096";
+    case GD_ENOMEM: return "out of pool or partition memory";
+    case GD_ERANGE: return "range is not inside the tenant's partition";
+    case GD_ENOTENANT: return "no such tenant";
+    case GD_EBUSY: return "tenant has live allocations";
+    case GD_EHIP: return "HIP call failed";
+    case GD_ENOKERNEL: return "unknown kernel or fence mode";
+    case GD_ESHAPE: return "operand shape not supported by the kernel";
+    default: return "unknown status";
+    }
+}
+
+int gd_last_hip_error(void) { return gd::g_last_hip_error; }
+
+}  // extern "C"

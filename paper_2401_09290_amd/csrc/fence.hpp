@@ -1,0 +1,107 @@
+// Device-side address fence for gfx950 kernels.
+//
+// Paper, Listing 1 and Section 4.3: every sandboxed kernel gets two extra
+// parameters (partition base and mask), keeps them in two registers, and runs
+//     addr = (addr AND mask) OR base
+// on the final effective address in front of every global load and store.
+// Here the two parameters arrive in the kernarg segment, so they live in SGPRs,
+// and the fence is folded into the address arithmetic of each access:
+//
+//   V_BIT32  partition <= 4 GiB.  The fence keeps only address bits below the
+//            mask, so the offset inside the partition is
+//            lo32(addr) & mask32 -- one v_and_b32 -- and the OR with the base
+//            is done by the global_load/store "SGPR base + 32-bit VGPR offset"
+//            addressing mode (base is size-aligned, so OR == ADD).
+//   V_BIT64  partition >= 4 GiB.  Then mask_lo = 0xFFFFFFFF and base_lo = 0, so
+//            only the high word needs the AND/OR (two VALU ops).
+//   V_NONE   native kernel: plain global pointer, no fence (Section 4.2.3).
+//
+// Width rule: an access of W bytes also clears the low log2(W) address bits, so
+// the whole access lies inside the partition (for naturally aligned addresses
+// this is exactly the paper's rule).  The mask with those bits cleared is
+// wave-uniform and is computed on the scalar unit.
+//
+// Rules for kernels using this header:
+//   * every global access of tenant data goes through Fence::ld / Fence::st with
+//     the FINAL address of that access (never index off a fenced pointer);
+//   * a vector access (8/16 bytes) is only issued on an address the kernel has
+//     established to be naturally aligned, so it equals the per-element fence;
+//   * LDS and registers are not fenced (Section 3: not reachable by other
+//     tenants); kernarg loads are not tenant-addressable.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gd {
+
+enum Variant : int { V_NONE = 0, V_BIT32 = 1, V_BIT64 = 2, V_COUNT = 3 };
+
+// The two extra kernel parameters of Listing 1.
+struct FenceArgs {
+    uint64_t base;
+    uint64_t mask;
+};
+
+#define GD_GLOBAL __attribute__((address_space(1)))
+
+template <int V>
+struct Fence {
+    uint64_t base;
+    uint64_t mask;
+
+    __device__ __forceinline__ explicit Fence(const FenceArgs &f) : base(f.base), mask(f.mask) {}
+
+    // The fenced address of a W-byte access to `raw` (what the probe kernel reports).
+    template <int W>
+    __device__ __forceinline__ uint64_t address(uint64_t raw) const
+    {
+        if constexpr (V == V_NONE) {
+            return raw;
+        } else if constexpr (V == V_BIT32) {
+            const uint32_t m = (uint32_t)mask & ~(uint32_t)(W - 1);
+            return base + (uint64_t)((uint32_t)raw & m);
+        } else {
+            const uint32_t lo = (uint32_t)raw & ~(uint32_t)(W - 1);
+            const uint32_t hi = ((uint32_t)(raw >> 32) & (uint32_t)(mask >> 32)) | (uint32_t)(base >> 32);
+            return ((uint64_t)hi << 32) | lo;
+        }
+    }
+
+    template <typename T>
+    __device__ __forceinline__ T ld(uint64_t raw) const
+    {
+        if constexpr (V == V_BIT32) {
+            const uint32_t m = (uint32_t)mask & ~(uint32_t)(sizeof(T) - 1);
+            const uint32_t off = (uint32_t)raw & m;
+            return *(const GD_GLOBAL T *)((const GD_GLOBAL char *)base + off);
+        } else {
+            return *(const GD_GLOBAL T *)address<sizeof(T)>(raw);
+        }
+    }
+
+    template <typename T>
+    __device__ __forceinline__ void st(uint64_t raw, T v) const
+    {
+        if constexpr (V == V_BIT32) {
+            const uint32_t m = (uint32_t)mask & ~(uint32_t)(sizeof(T) - 1);
+            const uint32_t off = (uint32_t)raw & m;
+            *(GD_GLOBAL T *)((GD_GLOBAL char *)base + off) = v;
+        } else {
+            *(GD_GLOBAL T *)address<sizeof(T)>(raw) = v;
+        }
+    }
+};
+
+// Launch helper: instantiate KERNEL for the variant chosen on the host.
+#define GD_LAUNCH_VARIANT(variant, KERNEL, grid, block, stream, ...)                            \
+    do {                                                                                        \
+        switch (variant) {                                                                      \
+        case gd::V_NONE:  hipLaunchKernelGGL((KERNEL<gd::V_NONE>), grid, block, 0, stream, __VA_ARGS__); break;  \
+        case gd::V_BIT32: hipLaunchKernelGGL((KERNEL<gd::V_BIT32>), grid, block, 0, stream, __VA_ARGS__); break; \
+        case gd::V_BIT64: hipLaunchKernelGGL((KERNEL<gd::V_BIT64>), grid, block, 0, stream, __VA_ARGS__); break; \
+        default: return GD_ENOKERNEL;                                                           \
+        }                                                                                       \
+    } while (0)
+
+}  // namespace gd

@@ -1,0 +1,152 @@
+// Indexed kernels: saxpy through int32 element offsets, gather and scatter of
+// 4-byte values through int64 or int32 indices.  The index/offset stream and the
+// contiguous side are read or written 16 bytes per lane; the data-dependent side
+// is one 4-byte access per element, each with the fence on its final address
+// (index * 4 added to the tenant's pointer in wrap-around arithmetic, then
+// fenced -- the register+offset rule of Section 4.3).
+#include "launchers.hpp"
+
+namespace gd {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
+
+constexpr int EPT = 4;   // elements per thread on the vector path
+
+// ---- y[o] = alpha*x[o] + y[o], o = off[i] ---------------------------------------
+template <int V>
+__global__ __launch_bounds__(1024) void k_saxpy_idx(gd_args_saxpy_idx p, FenceArgs fa)
+{
+    const Fence<V> F(fa);
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    const uint64_t tid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    uint64_t done = 0;
+    if ((p.off & 15) == 0) {
+        const uint64_t n4 = p.n >> 2;
+        for (uint64_t q = tid; q < n4; q += stride) {
+            const i32x4 o = F.template ld<i32x4>(p.off + 16 * q);
+            float vx[EPT], vy[EPT];
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) {
+                const uint64_t byte_off = (uint64_t)((int64_t)o[e] * 4);
+                vx[e] = F.template ld<float>(p.x + byte_off);
+                vy[e] = F.template ld<float>(p.y + byte_off);
+            }
+#pragma unroll
+            for (int e = 0; e < EPT; ++e)
+                F.template st<float>(p.y + (uint64_t)((int64_t)o[e] * 4), p.alpha * vx[e] + vy[e]);
+        }
+        done = 4 * n4;
+    }
+    for (uint64_t i = done + tid; i < p.n; i += stride) {
+        const int32_t o = F.template ld<int32_t>(p.off + 4 * i);
+        const uint64_t byte_off = (uint64_t)((int64_t)o * 4);
+        const float vx = F.template ld<float>(p.x + byte_off);
+        const float vy = F.template ld<float>(p.y + byte_off);
+        F.template st<float>(p.y + byte_off, p.alpha * vx + vy);
+    }
+}
+
+// ---- out[i] = tab[idx[i]] --------------------------------------------------------
+// IDX64: 1 = int64 indices, 0 = int32 indices (sign-extended).
+template <int V, int IDX64>
+__global__ __launch_bounds__(1024) void k_gather32(gd_args_gather p, FenceArgs fa)
+{
+    const Fence<V> F(fa);
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    const uint64_t tid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    uint64_t done = 0;
+    if (((p.idx | p.out) & 15) == 0) {
+        const uint64_t n4 = p.n >> 2;
+        for (uint64_t q = tid; q < n4; q += stride) {
+            uint64_t k[EPT];
+            if (IDX64) {
+                const u64x2 k01 = F.template ld<u64x2>(p.idx + 32 * q);
+                const u64x2 k23 = F.template ld<u64x2>(p.idx + 32 * q + 16);
+                k[0] = k01[0]; k[1] = k01[1]; k[2] = k23[0]; k[3] = k23[1];
+            } else {
+                const i32x4 k4 = F.template ld<i32x4>(p.idx + 16 * q);
+#pragma unroll
+                for (int e = 0; e < EPT; ++e) k[e] = (uint64_t)(int64_t)k4[e];
+            }
+            u32x4 v;
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) v[e] = F.template ld<uint32_t>(p.tab + 4 * k[e]);
+            F.template st<u32x4>(p.out + 16 * q, v);
+        }
+        done = 4 * n4;
+    }
+    for (uint64_t i = done + tid; i < p.n; i += stride) {
+        const uint64_t k = IDX64 ? F.template ld<uint64_t>(p.idx + 8 * i)
+                                 : (uint64_t)(int64_t)F.template ld<int32_t>(p.idx + 4 * i);
+        F.template st<uint32_t>(p.out + 4 * i, F.template ld<uint32_t>(p.tab + 4 * k));
+    }
+}
+
+// ---- dst[idx[i]] = scale * src[i] -------------------------------------------------
+template <int V>
+__global__ __launch_bounds__(1024) void k_scatter_f32_i64(gd_args_scatter p, FenceArgs fa)
+{
+    const Fence<V> F(fa);
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    const uint64_t tid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    uint64_t done = 0;
+    if (((p.idx | p.src) & 15) == 0) {
+        const uint64_t n4 = p.n >> 2;
+        for (uint64_t q = tid; q < n4; q += stride) {
+            const u64x2 k01 = F.template ld<u64x2>(p.idx + 32 * q);
+            const u64x2 k23 = F.template ld<u64x2>(p.idx + 32 * q + 16);
+            const f32x4 v = F.template ld<f32x4>(p.src + 16 * q);
+            F.template st<float>(p.dst + 4 * k01[0], p.scale * v[0]);
+            F.template st<float>(p.dst + 4 * k01[1], p.scale * v[1]);
+            F.template st<float>(p.dst + 4 * k23[0], p.scale * v[2]);
+            F.template st<float>(p.dst + 4 * k23[1], p.scale * v[3]);
+        }
+        done = 4 * n4;
+    }
+    for (uint64_t i = done + tid; i < p.n; i += stride) {
+        const uint64_t k = F.template ld<uint64_t>(p.idx + 8 * i);
+        const float v = F.template ld<float>(p.src + 4 * i);
+        F.template st<float>(p.dst + 4 * k, p.scale * v);
+    }
+}
+
+// ---- launchers ---------------------------------------------------------------------
+
+static uint64_t blocks_for(uint64_t n, uint32_t block)
+{
+    const uint64_t per_block = (uint64_t)block * EPT;
+    return (n + per_block - 1) / per_block;
+}
+
+#define GD_INDEXED_LAUNCHER(NAME, ARGS_T, KERNEL_EXPR)                                                   \
+    int NAME(const void *args, const FenceArgs &f, int variant, const Shape &shape, hipStream_t stream)  \
+    {                                                                                                    \
+        const ARGS_T &p = *(const ARGS_T *)args;                                                         \
+        const uint32_t b0 = shape.block ? shape.block[0] : 256;                                          \
+        uint32_t grid, block;                                                                            \
+        if (!pick_1d(shape, b0 ? blocks_for(p.n, b0) : 1, 256, &grid, &block)) return GD_EINVAL;         \
+        if (p.n == 0) return GD_OK;                                                                      \
+        switch (variant) {                                                                               \
+        case V_NONE:  hipLaunchKernelGGL((KERNEL_EXPR(V_NONE)), dim3(grid), dim3(block), 0, stream, p, f); break;  \
+        case V_BIT32: hipLaunchKernelGGL((KERNEL_EXPR(V_BIT32)), dim3(grid), dim3(block), 0, stream, p, f); break; \
+        case V_BIT64: hipLaunchKernelGGL((KERNEL_EXPR(V_BIT64)), dim3(grid), dim3(block), 0, stream, p, f); break; \
+        default: return GD_ENOKERNEL;                                                                    \
+        }                                                                                                \
+        GD_CHECK_LAUNCH();                                                                               \
+        return GD_OK;                                                                                    \
+    }
+
+#define K_SAXPY(V) k_saxpy_idx<V>
+#define K_GATHER64(V) k_gather32<V, 1>
+#define K_GATHER32(V) k_gather32<V, 0>
+#define K_SCATTER(V) k_scatter_f32_i64<V>
+
+GD_INDEXED_LAUNCHER(launch_saxpy_idx, gd_args_saxpy_idx, K_SAXPY)
+GD_INDEXED_LAUNCHER(launch_gather32_i64, gd_args_gather, K_GATHER64)
+GD_INDEXED_LAUNCHER(launch_gather32_i32, gd_args_gather, K_GATHER32)
+GD_INDEXED_LAUNCHER(launch_scatter_f32_i64, gd_args_scatter, K_SCATTER)
+
+}  // namespace gd

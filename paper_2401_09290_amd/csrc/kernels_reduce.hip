@@ -1,0 +1,210 @@
+// Reductions: fp32 sum of a contiguous array (two passes: per-workgroup partial
+// sums into the tenant's workspace, then one workgroup adds the partials) and
+// row-wise RMS normalisation of a bf16 matrix (one workgroup per row, the row
+// kept in registers between the sum of squares and the scaling).  Wavefront
+// reductions use cross-lane shuffles, workgroup reductions a few LDS words; LDS
+// is not tenant-addressable and is not fenced.  Every global access, including
+// those to the workspace, carries the fence on its final address.
+#include "launchers.hpp"
+
+namespace gd {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int WG = 256;
+constexpr int WAVES = WG / 64;
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+
+// Sum over the workgroup; the result is valid in every thread.
+template <typename T>
+__device__ __forceinline__ T block_sum(T v, T *lds)
+{
+    v = wave_sum(v);
+    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
+    __syncthreads();
+    T r = lds[0];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) r += lds[w];
+    __syncthreads();
+    return r;
+}
+
+// ---- sum, pass 1: partials[block] = sum of this block's tiles ---------------------
+constexpr int SUM_UNROLL = 4;
+
+template <int V>
+__global__ __launch_bounds__(WG) void k_sum_partial(gd_args_sum p, FenceArgs fa)
+{
+    const Fence<V> F(fa);
+    __shared__ float lds[WAVES];
+    float acc = 0.0f;
+    if ((p.in & 15) == 0) {
+        const uint64_t n4 = p.n >> 2;
+        const uint64_t tile = (uint64_t)WG * SUM_UNROLL;
+        f32x4 a4 = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (uint64_t t0 = blockIdx.x * tile; t0 < n4; t0 += gridDim.x * tile) {
+            const uint64_t i0 = t0 + threadIdx.x;
+            if (t0 + tile <= n4) {
+                f32x4 v[SUM_UNROLL];
+#pragma unroll
+                for (int u = 0; u < SUM_UNROLL; ++u) v[u] = F.template ld<f32x4>(p.in + 16 * (i0 + (uint64_t)u * WG));
+#pragma unroll
+                for (int u = 0; u < SUM_UNROLL; ++u) a4 += v[u];
+            } else {
+#pragma unroll
+                for (int u = 0; u < SUM_UNROLL; ++u) {
+                    const uint64_t i = i0 + (uint64_t)u * WG;
+                    if (i < n4) a4 += F.template ld<f32x4>(p.in + 16 * i);
+                }
+            }
+        }
+        acc = (a4[0] + a4[1]) + (a4[2] + a4[3]);
+        if (blockIdx.x == 0 && threadIdx.x < (p.n & 3)) acc += F.template ld<float>(p.in + 4 * (4 * n4 + threadIdx.x));
+    } else {
+        const uint64_t stride = (uint64_t)gridDim.x * WG;
+        for (uint64_t i = (uint64_t)blockIdx.x * WG + threadIdx.x; i < p.n; i += stride)
+            acc += F.template ld<float>(p.in + 4 * i);
+    }
+    const float total = block_sum(acc, lds);
+    if (threadIdx.x == 0) F.template st<float>(p.partials + 4 * (uint64_t)blockIdx.x, total);
+}
+
+// ---- sum, pass 2: out[0] = sum of the partials (added in fp64) ---------------------
+template <int V>
+__global__ __launch_bounds__(WG) void k_sum_final(gd_args_sum p, uint32_t n_partials, FenceArgs fa)
+{
+    const Fence<V> F(fa);
+    __shared__ double lds[WAVES];
+    double acc = 0.0;
+    for (uint32_t i = threadIdx.x; i < n_partials; i += WG)
+        acc += (double)F.template ld<float>(p.partials + 4 * (uint64_t)i);
+    const double total = block_sum(acc, lds);
+    if (threadIdx.x == 0) F.template st<float>(p.out, (float)total);
+}
+
+// ---- RMSNorm -------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// Nearest bfloat16, ties to even.
+__device__ __forceinline__ uint32_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;          // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    return f32_to_bf16(lo) | (f32_to_bf16(hi) << 16);
+}
+
+constexpr int RMS_MAX_CHUNKS = 4;   // 16-byte chunks (8 values) per thread held in registers
+
+template <int V>
+__global__ __launch_bounds__(WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, FenceArgs fa)
+{
+    const Fence<V> F(fa);
+    __shared__ float lds[WAVES];
+    const uint64_t row = blockIdx.x;
+    const uint64_t xrow = p.x + 2 * row * p.cols;
+    const uint64_t yrow = p.y + 2 * row * p.cols;
+    const float inv_cols = 1.0f / (float)p.cols;
+
+    const bool vec = ((p.x | p.y | p.g) & 15) == 0 && (p.cols & 7) == 0 &&
+                     p.cols <= (uint32_t)(WG * 8 * RMS_MAX_CHUNKS);
+    if (vec) {
+        const uint32_t chunks = p.cols >> 3;
+        u32x4 xv[RMS_MAX_CHUNKS];
+        float ss = 0.0f;
+#pragma unroll
+        for (int c = 0; c < RMS_MAX_CHUNKS; ++c) {
+            const uint32_t q = threadIdx.x + c * WG;
+            if (q < chunks) {
+                xv[c] = F.template ld<u32x4>(xrow + 16 * (uint64_t)q);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float a = bf16_lo(xv[c][e]), b = bf16_hi(xv[c][e]);
+                    ss += a * a;
+                    ss += b * b;
+                }
+            }
+        }
+        ss = block_sum(ss, lds);
+        const float inv = 1.0f / sqrtf(ss * inv_cols + p.eps);
+#pragma unroll
+        for (int c = 0; c < RMS_MAX_CHUNKS; ++c) {
+            const uint32_t q = threadIdx.x + c * WG;
+            if (q < chunks) {
+                const u32x4 gv = F.template ld<u32x4>(p.g + 16 * (uint64_t)q);
+                u32x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    o[e] = pack_bf16(bf16_lo(xv[c][e]) * inv * bf16_lo(gv[e]),
+                                     bf16_hi(xv[c][e]) * inv * bf16_hi(gv[e]));
+                F.template st<u32x4>(yrow + 16 * (uint64_t)q, o);
+            }
+        }
+    } else {
+        float ss = 0.0f;
+        for (uint32_t j = threadIdx.x; j < p.cols; j += WG) {
+            const float a = bf16_lo(F.template ld<uint16_t>(xrow + 2 * (uint64_t)j));
+            ss += a * a;
+        }
+        ss = block_sum(ss, lds);
+        const float inv = 1.0f / sqrtf(ss * inv_cols + p.eps);
+        for (uint32_t j = threadIdx.x; j < p.cols; j += WG) {
+            const float a = bf16_lo(F.template ld<uint16_t>(xrow + 2 * (uint64_t)j));
+            const float g = bf16_lo(F.template ld<uint16_t>(p.g + 2 * (uint64_t)j));
+            F.template st<uint16_t>(yrow + 2 * (uint64_t)j, (uint16_t)f32_to_bf16(a * inv * g));
+        }
+    }
+}
+
+// ---- launchers -------------------------------------------------------------------------
+
+constexpr uint32_t SUM_MAX_BLOCKS = 2048;
+static_assert(SUM_MAX_BLOCKS * 4 <= GD_SUM_WORKSPACE, "workspace too small for the partial sums");
+
+int launch_sum_f32(const void *args, const FenceArgs &f, int variant, const Shape &shape, hipStream_t stream)
+{
+    const gd_args_sum &p = *(const gd_args_sum *)args;
+    if (shape.grid || shape.block) return GD_EINVAL;
+    const uint64_t tile = (uint64_t)WG * SUM_UNROLL * 4;                 // elements per tile
+    uint64_t blocks = (p.n + tile - 1) / tile;
+    if (blocks == 0) blocks = 1;
+    if (blocks > SUM_MAX_BLOCKS) blocks = SUM_MAX_BLOCKS;
+    GD_LAUNCH_VARIANT(variant, k_sum_partial, dim3((uint32_t)blocks), dim3(WG), stream, p, f);
+    GD_CHECK_LAUNCH();
+    GD_LAUNCH_VARIANT(variant, k_sum_final, dim3(1), dim3(WG), stream, p, (uint32_t)blocks, f);
+    GD_CHECK_LAUNCH();
+    return GD_OK;
+}
+
+int launch_rmsnorm_bf16(const void *args, const FenceArgs &f, int variant, const Shape &shape,
+                        hipStream_t stream)
+{
+    const gd_args_rmsnorm &p = *(const gd_args_rmsnorm *)args;
+    if (shape.grid || shape.block) return GD_EINVAL;
+    if (p.cols == 0 || p.rows > 0x7fffffffu) return GD_ESHAPE;
+    if (p.rows == 0) return GD_OK;
+    GD_LAUNCH_VARIANT(variant, k_rmsnorm_bf16, dim3(p.rows), dim3(WG), stream, p, f);
+    GD_CHECK_LAUNCH();
+    return GD_OK;
+}
+
+}  // namespace gd

@@ -1,0 +1,165 @@
+// Contiguous element-wise kernels: Listing 1's sample store, the fence probe,
+// STREAM copy and STREAM triad.  HBM-bound: 16 bytes per lane per access, all
+// loads of a tile issued before its stores, one tile of UNROLL * blockDim.x
+// vectors per loop trip.  The fence (fence.hpp) is applied to the final address
+// of every access; kernels are identical for every variant apart from it.
+#include "launchers.hpp"
+
+namespace gd {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int UNROLL = 4;
+
+// ---- store_tid: A[i] = j (paper Listing 1 / Section 4.3) -----------------------
+template <int V>
+__global__ __launch_bounds__(1024) void k_store_tid(gd_args_store_tid p, FenceArgs fa)
+{
+    const Fence<V> F(fa);
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < p.n; i += stride)
+        F.template st<uint32_t>(p.A + 4 * i, p.j);
+}
+
+// ---- fence probe: out[i] = fence_width(in[i]) ----------------------------------
+template <int V>
+__global__ __launch_bounds__(1024) void k_fence_addrs(gd_args_fence_addrs p, FenceArgs fa)
+{
+    const Fence<V> F(fa);
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < p.n; i += stride) {
+        const uint64_t a = F.template ld<uint64_t>(p.in + 8 * i);
+        uint64_t f;
+        switch (p.width) {
+        case 1: f = F.template address<1>(a); break;
+        case 2: f = F.template address<2>(a); break;
+        case 4: f = F.template address<4>(a); break;
+        case 8: f = F.template address<8>(a); break;
+        default: f = F.template address<16>(a); break;
+        }
+        F.template st<uint64_t>(p.out + 8 * i, f);
+    }
+}
+
+// ---- copy / triad ------------------------------------------------------------------
+// OP 0: a = b.  OP 1: a = b + s*c (one fused multiply-add per element).
+// Vector path when all pointers are 16-byte aligned (then a 16-byte access equals
+// four fenced 4-byte accesses); otherwise every element is accessed on its own.
+template <int V, int OP>
+__global__ __launch_bounds__(1024) void k_stream(uint64_t pa, uint64_t pb, uint64_t pc, uint64_t n,
+                                                 float s, FenceArgs fa)
+{
+    const Fence<V> F(fa);
+    const uint64_t ptr_bits = OP ? (pa | pb | pc) : (pa | pb);
+    if ((ptr_bits & 15) == 0) {
+        const uint64_t n4 = n >> 2;
+        const uint64_t tile = (uint64_t)blockDim.x * UNROLL;
+        for (uint64_t t0 = blockIdx.x * tile; t0 < n4; t0 += gridDim.x * tile) {
+            const uint64_t i0 = t0 + threadIdx.x;
+            f32x4 vb[UNROLL], vc[UNROLL];
+            if (t0 + tile <= n4) {
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    const uint64_t i = i0 + (uint64_t)u * blockDim.x;
+                    vb[u] = F.template ld<f32x4>(pb + 16 * i);
+                    if (OP) vc[u] = F.template ld<f32x4>(pc + 16 * i);
+                }
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    const uint64_t i = i0 + (uint64_t)u * blockDim.x;
+                    F.template st<f32x4>(pa + 16 * i, OP ? vb[u] + s * vc[u] : vb[u]);
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    const uint64_t i = i0 + (uint64_t)u * blockDim.x;
+                    if (i < n4) {
+                        vb[u] = F.template ld<f32x4>(pb + 16 * i);
+                        if (OP) vc[u] = F.template ld<f32x4>(pc + 16 * i);
+                        F.template st<f32x4>(pa + 16 * i, OP ? vb[u] + s * vc[u] : vb[u]);
+                    }
+                }
+            }
+        }
+        if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {          // at most three elements left
+            const uint64_t i = 4 * n4 + threadIdx.x;
+            float r = F.template ld<float>(pb + 4 * i);
+            if (OP) r = r + s * F.template ld<float>(pc + 4 * i);
+            F.template st<float>(pa + 4 * i, r);
+        }
+    } else {
+        const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+        for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+            float r = F.template ld<float>(pb + 4 * i);
+            if (OP) r = r + s * F.template ld<float>(pc + 4 * i);
+            F.template st<float>(pa + 4 * i, r);
+        }
+    }
+}
+
+// ---- launchers -------------------------------------------------------------------
+
+int launch_store_tid(const void *args, const FenceArgs &f, int variant, const Shape &shape,
+                     hipStream_t stream)
+{
+    const gd_args_store_tid &p = *(const gd_args_store_tid *)args;
+    uint32_t grid, block;
+    if (!pick_1d(shape, (p.n + 255) / 256, 256, &grid, &block)) return GD_EINVAL;
+    if (p.n == 0) return GD_OK;
+    GD_LAUNCH_VARIANT(variant, k_store_tid, dim3(grid), dim3(block), stream, p, f);
+    GD_CHECK_LAUNCH();
+    return GD_OK;
+}
+
+int launch_fence_addrs(const void *args, const FenceArgs &f, int variant, const Shape &shape,
+                       hipStream_t stream)
+{
+    const gd_args_fence_addrs &p = *(const gd_args_fence_addrs *)args;
+    if (!(p.width == 1 || p.width == 2 || p.width == 4 || p.width == 8 || p.width == 16))
+        return GD_ESHAPE;
+    uint32_t grid, block;
+    if (!pick_1d(shape, (p.n + 255) / 256, 256, &grid, &block)) return GD_EINVAL;
+    if (p.n == 0) return GD_OK;
+    GD_LAUNCH_VARIANT(variant, k_fence_addrs, dim3(grid), dim3(block), stream, p, f);
+    GD_CHECK_LAUNCH();
+    return GD_OK;
+}
+
+#define GD_STREAM_LAUNCH(variant, OP, grid, block, stream, ...)                                         \
+    do {                                                                                                \
+        switch (variant) {                                                                              \
+        case V_NONE:  hipLaunchKernelGGL((k_stream<V_NONE, OP>), grid, block, 0, stream, __VA_ARGS__); break;  \
+        case V_BIT32: hipLaunchKernelGGL((k_stream<V_BIT32, OP>), grid, block, 0, stream, __VA_ARGS__); break; \
+        case V_BIT64: hipLaunchKernelGGL((k_stream<V_BIT64, OP>), grid, block, 0, stream, __VA_ARGS__); break; \
+        default: return GD_ENOKERNEL;                                                                   \
+        }                                                                                               \
+    } while (0)
+
+static uint64_t stream_tiles(uint64_t n, uint32_t block) { return ((n >> 2) + (uint64_t)block * UNROLL - 1) / ((uint64_t)block * UNROLL); }
+
+int launch_copy(const void *args, const FenceArgs &f, int variant, const Shape &shape, hipStream_t stream)
+{
+    const gd_args_copy &p = *(const gd_args_copy *)args;
+    const uint32_t b0 = shape.block ? shape.block[0] : 256;
+    uint32_t grid, block;
+    if (!pick_1d(shape, b0 ? stream_tiles(p.n, b0) : 1, 256, &grid, &block)) return GD_EINVAL;
+    if (p.n == 0) return GD_OK;
+    GD_STREAM_LAUNCH(variant, 0, dim3(grid), dim3(block), stream, p.a, p.b, (uint64_t)0, p.n, 0.0f, f);
+    GD_CHECK_LAUNCH();
+    return GD_OK;
+}
+
+int launch_triad(const void *args, const FenceArgs &f, int variant, const Shape &shape, hipStream_t stream)
+{
+    const gd_args_triad &p = *(const gd_args_triad *)args;
+    const uint32_t b0 = shape.block ? shape.block[0] : 256;
+    uint32_t grid, block;
+    if (!pick_1d(shape, b0 ? stream_tiles(p.n, b0) : 1, 256, &grid, &block)) return GD_EINVAL;
+    if (p.n == 0) return GD_OK;
+    GD_STREAM_LAUNCH(variant, 1, dim3(grid), dim3(block), stream, p.a, p.b, p.c, p.n, p.s, f);
+    GD_CHECK_LAUNCH();
+    return GD_OK;
+}
+
+}  // namespace gd

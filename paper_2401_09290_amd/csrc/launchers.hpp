@@ -1,0 +1,65 @@
+// Per-kernel launchers: each validates the shape on the host, picks the launch
+// geometry, and launches the template instance for the requested fence variant.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "../../include/guardian.h"
+#include "fence.hpp"
+
+namespace gd {
+
+// Launch geometry requested by the caller: grid/block may be null (library default).
+struct Shape {
+    const uint32_t *grid;
+    const uint32_t *block;
+};
+
+using Launcher = int (*)(const void *args, const FenceArgs &f, int variant, const Shape &shape,
+                         hipStream_t stream);
+
+int launch_store_tid(const void *, const FenceArgs &, int, const Shape &, hipStream_t);
+int launch_fence_addrs(const void *, const FenceArgs &, int, const Shape &, hipStream_t);
+int launch_copy(const void *, const FenceArgs &, int, const Shape &, hipStream_t);
+int launch_triad(const void *, const FenceArgs &, int, const Shape &, hipStream_t);
+int launch_saxpy_idx(const void *, const FenceArgs &, int, const Shape &, hipStream_t);
+int launch_gather32_i64(const void *, const FenceArgs &, int, const Shape &, hipStream_t);
+int launch_scatter_f32_i64(const void *, const FenceArgs &, int, const Shape &, hipStream_t);
+int launch_gather32_i32(const void *, const FenceArgs &, int, const Shape &, hipStream_t);
+int launch_sum_f32(const void *, const FenceArgs &, int, const Shape &, hipStream_t);
+int launch_rmsnorm_bf16(const void *, const FenceArgs &, int, const Shape &, hipStream_t);
+int launch_gemm_bf16(const void *, const FenceArgs &, int, const Shape &, hipStream_t);
+
+// 1-D launch shape of an element-wise kernel that loops over `tiles` tiles.
+// Returns false if the caller's shape is unusable.
+inline bool pick_1d(const Shape &s, uint64_t tiles, uint32_t default_block, uint32_t *grid,
+                    uint32_t *block)
+{
+    uint32_t b = default_block;
+    uint64_t g = tiles ? tiles : 1;
+    if (s.block) {
+        b = s.block[0];
+        if (b == 0 || b > 1024 || (b % 64) != 0 || s.block[1] > 1 || s.block[2] > 1) return false;
+    }
+    if (s.grid) {
+        if (s.grid[0] == 0 || s.grid[1] > 1 || s.grid[2] > 1) return false;
+        g = s.grid[0];
+    }
+    if (g > 0x7fffffffull) g = 0x7fffffffull;
+    *grid = (uint32_t)g;
+    *block = b;
+    return true;
+}
+
+// Last HIP error seen by a launcher on this thread (0 = hipSuccess).
+void note_hip_error(hipError_t e);
+#define GD_CHECK_LAUNCH()                                  \
+    do {                                                   \
+        hipError_t e_ = hipGetLastError();                 \
+        if (e_ != hipSuccess) {                            \
+            gd::note_hip_error(e_);                        \
+            return GD_EHIP;                                \
+        }                                                  \
+    } while (0)
+
+}  // namespace gd

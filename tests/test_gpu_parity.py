@@ -1,0 +1,537 @@
+"""GPU parity: every kernel of the library, launched through the C ABI, against
+the CPU oracle on the same seeded inputs at the same device addresses.
+
+Bars.  Integer, byte and index results and the whole memory image outside
+floating-point outputs: bit-exact.  fp32 outputs: relative Frobenius error
+<= 1e-5 against the oracle's fp64 arithmetic.  bf16 outputs: <= 1e-3 against the
+oracle's result rounded to bf16.  Fenced output is bit-identical to unfenced
+output on in-bounds inputs.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2401_09290_amd as gd
+import synth_inputs as si
+from harness import GiB, KiB, MiB, Rig, rel_frobenius
+from oracle import kernels as ok
+
+pytestmark = pytest.mark.gpu
+
+FP32_TOL = 1e-5
+BF16_TOL = 1e-3
+
+
+@pytest.fixture()
+def rig2():
+    r = Rig([4 * MiB, 4 * MiB])
+    yield r
+    r.close()
+
+
+# ---------------------------------------------------------------------------
+# Listing 1's kernel and the fence probe
+# ---------------------------------------------------------------------------
+
+def test_store_tid_in_bounds_overrun_and_foreign_pointer(rig2):
+    r = rig2
+    (b0, s0), (b1, s1) = r.row(0), r.row(1)
+    cases = [(0, b0 + 4096, 7, 1000),                 # in bounds
+             (0, b0 + s0 - 4096, 8, 5000),            # runs over the end of partition 0: wraps to its start
+             (1, b0 + 64, 9, 777),                    # tenant 1 passes a pointer into partition 0
+             (1, b1 - 4 * 100, 10, 300),              # starts in front of its partition
+             (0, b0 + 2, 11, 5),                      # misaligned pointer: low bits dropped
+             (0, b0, 12, 0)]                          # empty launch
+    for tenant, A, j, n in cases:
+        r.launch(tenant, gd.GD_K_STORE_TID, gd.gd_args_store_tid(A, n, j, 0))
+        r.oracle("store_tid", tenant, A, j, n)
+        r.assert_images_equal(what=f"store_tid tenant {tenant} A={A:#x} n={n}")
+
+
+@pytest.mark.parametrize("width", [1, 2, 4, 8, 16])
+def test_fence_probe_matches_oracle_bit_exactly(rig2, width):
+    r = rig2
+    g = si.rng(0, 10 + width)
+    for tenant in (0, 1):
+        base, size = r.row(tenant)
+        n = 40001
+        raw = g.integers(0, 1 << 63, size=n, dtype=np.uint64) * np.uint64(2) + g.integers(0, 2, size=n, dtype=np.uint64)
+        near = (np.uint64(base) + g.integers(0, 4 * size, size=n // 2, dtype=np.uint64) - np.uint64(2 * size))
+        raw[: n // 2] = near
+        src, dst = r.alloc(tenant, 8 * n), r.alloc(tenant, 8 * n)
+        r.upload(tenant, src, raw)
+        r.launch(tenant, gd.GD_K_FENCE_ADDRS, gd.gd_args_fence_addrs(dst, src, n, width, 0))
+        r.oracle("fence_addrs", tenant, dst, src, width, n)
+        got = r.download(dst, np.uint64, n)
+        assert np.array_equal(got, ok.fence_array(base, size, raw, width))
+        assert got.min() >= base and got.max() + width <= base + size
+        r.assert_images_equal(what="fence probe")
+        # protection off: the probe reports the raw addresses
+        r.launch(tenant, gd.GD_K_FENCE_ADDRS, gd.gd_args_fence_addrs(dst, src, n, width, 0), mode=gd.GD_FENCE_NONE)
+        assert np.array_equal(r.download(dst, np.uint64, n), raw)
+        r.oracle("fence_addrs", tenant, dst, src, width, n, mode=ok.MODE_NONE)
+
+
+def test_fence_probe_on_a_partition_larger_than_4gib():
+    r = Rig([8 * GiB], fill=None, simulate=False)
+    try:
+        base, size = r.row(0)
+        g = si.rng(0, 30)
+        n = 100000
+        raw = g.integers(0, 1 << 63, size=n, dtype=np.uint64) * np.uint64(2) + g.integers(0, 2, size=n, dtype=np.uint64)
+        raw[: n // 2] = np.uint64(base) + g.integers(0, 4 * size, size=n // 2, dtype=np.uint64) - np.uint64(2 * size)
+        # the probe's own arrays sit above the 4 GiB line of the partition
+        r.alloc(0, 5 * GiB)
+        src, dst = r.alloc(0, 8 * n), r.alloc(0, 8 * n)
+        assert src - base > 4 * GiB
+        r.upload(0, src, raw)
+        for width in (1, 4, 16):
+            r.launch(0, gd.GD_K_FENCE_ADDRS, gd.gd_args_fence_addrs(dst, src, n, width, 0))
+            got = r.download(dst, np.uint64, n)
+            assert np.array_equal(got, ok.fence_array(base, size, raw, width))
+        # wrapped pointers: the same launch through aliases one partition size away
+        r.dview(dst, np.uint64, n).zero_()
+        r.launch(0, gd.GD_K_FENCE_ADDRS, gd.gd_args_fence_addrs(dst + size, src - size, n, 8, 0))
+        assert np.array_equal(r.download(dst, np.uint64, n), ok.fence_array(base, size, raw, 8))
+    finally:
+        r.close()
+
+
+# ---------------------------------------------------------------------------
+# copy / triad
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n,shift", [(0, 0), (1, 0), (3, 0), (1023, 0), (4096, 0), (100003, 0), (262144 + 5, 0),
+                                     (100003, 4), (5000, 8)])
+def test_copy_and_triad_against_oracle_and_unfenced(rig2, n, shift):
+    r = rig2
+    g = si.rng(0, 40)
+    a = r.alloc(0, 4 * n + 64) + shift          # shift: pointers that are not 16-byte aligned
+    b = r.alloc(0, 4 * n + 64) + shift
+    c = r.alloc(0, 4 * n + 64) + (shift and 12)
+    vb, vc = si.uniform_f32(g, n), si.uniform_f32(g, n)
+    r.upload(0, b, vb)
+    r.upload(0, c, vc)
+    s = float(np.float32(0.7391))
+    for kid, args, oname, oargs in (
+            (gd.GD_K_COPY, gd.gd_args_copy(a, b, n), "copy", (a, b, n)),
+            (gd.GD_K_TRIAD, gd.gd_args_triad(a, b, c, n, s, 0), "triad", (a, b, c, s, n))):
+        r.launch(0, kid, args)
+        r.oracle(oname, 0, *oargs)
+        fenced = r.download(a, np.float32, n)
+        want = r.sim.view(a, np.float32, n)
+        if oname == "copy":
+            assert np.array_equal(fenced.view(np.uint32), want.view(np.uint32))
+            r.assert_images_equal(what=f"copy n={n}")
+        else:
+            assert rel_frobenius(fenced, want) <= FP32_TOL
+            r.assert_images_equal(skip=[(a, 4 * n)], what=f"triad n={n}")
+        r.dview(a, np.uint8, 4 * n).fill_(0)
+        r.launch(0, kid, args, mode=gd.GD_FENCE_NONE)
+        assert np.array_equal(r.download(a, np.float32, n).view(np.uint32), fenced.view(np.uint32))
+
+
+def test_triad_caller_chosen_launch_shapes(rig2):
+    r = rig2
+    n = 70001
+    g = si.rng(0, 41)
+    a, b, c = (r.alloc(0, 4 * n) for _ in range(3))
+    r.upload(0, b, si.uniform_f32(g, n))
+    r.upload(0, c, si.uniform_f32(g, n))
+    r.oracle("triad", 0, a, b, c, 0.25, n)
+    want = r.sim.view(a, np.float32, n).copy()
+    for grid, block in (((1, 1, 1), (64, 1, 1)), ((7, 1, 1), (1024, 1, 1)), ((1000, 1, 1), (128, 1, 1))):
+        r.dview(a, np.uint8, 4 * n).fill_(0)
+        r.launch(0, gd.GD_K_TRIAD, gd.gd_args_triad(a, b, c, n, 0.25, 0), grid=grid, block=block)
+        assert rel_frobenius(r.download(a, np.float32, n), want) <= FP32_TOL
+    for grid, block in (((0, 1, 1), (64, 1, 1)), ((1, 1, 1), (96, 1, 1)), ((1, 1, 1), (2048, 1, 1)), ((1, 2, 1), (64, 1, 1))):
+        with pytest.raises(gd.GuardianError) as e:
+            r.launch(0, gd.GD_K_TRIAD, gd.gd_args_triad(a, b, c, n, 0.25, 0), grid=grid, block=block)
+        assert e.value.status == gd.GD_EINVAL
+
+
+def test_triad_through_out_of_partition_pointers_wraps_into_own_partition(rig2):
+    # Tenant 1 passes pointers that lie in tenant 0's partition: its kernel reads
+    # and writes the same offsets of its own partition instead.
+    r = rig2
+    (b0, s0), (b1, s1) = r.row(0), r.row(1)
+    n = 50000
+    g = si.rng(0, 42)
+    for t in (0, 1):
+        for k in range(3):
+            p = r.alloc(t, 4 * n)
+            r.upload(t, p, si.uniform_f32(g, n))
+    a0, bb0, c0 = b0, b0 + 4 * n + (-4 * n) % 256, b0 + 2 * (4 * n + (-4 * n) % 256)
+    r.launch(1, gd.GD_K_TRIAD, gd.gd_args_triad(a0, bb0, c0, n, 1.5, 0))
+    r.oracle("triad", 1, a0, bb0, c0, 1.5, n)
+    a1 = a0 - b0 + b1
+    assert rel_frobenius(r.download(a1, np.float32, n), r.sim.view(a1, np.float32, n)) <= FP32_TOL
+    r.assert_images_equal(skip=[(a1, 4 * n)], what="foreign-pointer triad")
+
+
+# ---------------------------------------------------------------------------
+# indexed saxpy (configuration 1 shape) with out-of-range offsets
+# ---------------------------------------------------------------------------
+
+def hazard_free_offsets(g, n, x, y, scratch, scratch_bytes, base, size, frac=0.01, reach=16 * MiB):
+    """Configuration-1 offsets, redrawn (same stream) until every out-of-range
+    element's fenced y-address falls into the scratch region, at a location no
+    other element uses, and its fenced x-address is not written by this launch.
+    Then the final memory image does not depend on the order of the threads."""
+    off, where = si.c1_offsets(g, n, y, base, size, frac, reach)
+    for _ in range(200):
+        o = off[where].astype(np.int64)
+        ya = ok.fence_array(base, size, (np.uint64(y) + (4 * o).astype(np.uint64)), 4)
+        xa = ok.fence_array(base, size, (np.uint64(x) + (4 * o).astype(np.uint64)), 4)
+        in_scratch = (ya >= scratch) & (ya < scratch + scratch_bytes)
+        _, first = np.unique(ya, return_index=True)
+        dup = np.ones(len(ya), bool)
+        dup[first] = False
+        x_written = ((xa >= y) & (xa < y + 4 * n)) | np.isin(xa, ya)
+        bad = ~in_scratch | dup | x_written
+        if not bad.any():
+            return off, where
+        redo, _ = si.c1_offsets(g, n, y, base, size, frac, reach)
+        fresh = redo[redo != np.arange(n)]
+        off[where[bad]] = fresh[: bad.sum()]
+    raise AssertionError("could not draw hazard-free offsets")
+
+
+def test_config1_indexed_saxpy_two_tenants_hazard_free_image_is_bit_exact(rig2):
+    r = rig2
+    n = 262144
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    plan = []
+    for t in (0, 1):
+        base, size = r.row(t)
+        g = si.rng(1, t)
+        x, y, off, scratch = (r.alloc(t, 4 * n) for _ in range(4))
+        r.upload(t, x, si.uniform_f32(g, n))
+        r.upload(t, y, si.uniform_f32(g, n))
+        alpha = float(si.uniform_f32(g, 1)[0])
+        offs, where = hazard_free_offsets(g, n, x, y, scratch, 4 * n, base, size)
+        assert len(where) == 2621
+        r.upload(t, off, offs)
+        plan.append((t, x, y, off, alpha))
+    torch.cuda.synchronize()
+    for (t, x, y, off, alpha), st in zip(plan, streams):
+        r.launch(t, gd.GD_K_SAXPY_IDX, gd.gd_args_saxpy_idx(x, y, off, n, alpha, 0), stream=st.cuda_stream)
+    for (t, x, y, off, alpha) in plan:
+        r.oracle("saxpy_idx", t, x, y, off, alpha, n)
+        assert r.sim.last[0] == 0 and r.sim.last[2] >= 3 * 2621
+    torch.cuda.synchronize()
+    got, want = r.image().view(np.float32), r.sim.mem.view(np.float32)
+    # every 4-byte word of the pool either matches bit for bit or is a saxpy result
+    # that differs in the last place only (fused multiply-add vs fp64 then rounding)
+    differ = np.flatnonzero(got.view(np.uint32) != want.view(np.uint32))
+    assert np.all(np.isfinite(got[differ])) and np.all(np.isfinite(want[differ]))
+    assert np.all(np.abs(got[differ] - want[differ]) <= 2e-7 * np.maximum(1.0, np.abs(want[differ])))
+    assert differ.size < 0.01 * n
+    for (t, x, y, off, alpha) in plan:
+        assert rel_frobenius(r.download(y, np.float32, n), r.sim.view(y, np.float32, n)) <= FP32_TOL
+
+
+def test_config1_literal_offsets_confinement_and_clean_values():
+    # The literal distribution (wrapped stores may hit the tenant's own live data,
+    # which the paper leaves unspecified): neighbours stay byte-identical and every
+    # element not involved in a wrapped access matches the oracle.
+    r = Rig([4 * MiB, 4 * MiB, 4 * MiB])
+    try:
+        n = 262144
+        t = 1
+        base, size = r.row(t)
+        g = si.rng(1, 7)
+        x, y, off = (r.alloc(t, 4 * n) for _ in range(3))
+        r.upload(t, x, si.uniform_f32(g, n))
+        r.upload(t, y, si.uniform_f32(g, n))
+        offs, where = si.c1_offsets(g, n, y, base, size)
+        r.upload(t, off, offs)
+        before = r.image().copy()
+        r.launch(t, gd.GD_K_SAXPY_IDX, gd.gd_args_saxpy_idx(x, y, off, n, 0.5, 0))
+        r.oracle("saxpy_idx", t, x, y, off, 0.5, n)
+        after = r.image()
+        lo, hi = base - r.base, base - r.base + size
+        assert np.array_equal(after[:lo], before[:lo]) and np.array_equal(after[hi:], before[hi:])
+        o = offs[where].astype(np.int64)
+        ya = ok.fence_array(base, size, np.uint64(y) + (4 * o).astype(np.uint64), 4)
+        dirty = np.zeros(n, bool)
+        dirty[where] = True
+        hit_y = ya[(ya >= y) & (ya < y + 4 * n)]
+        dirty[((hit_y - y) // 4).astype(np.int64)] = True
+        hit_x = ya[(ya >= x) & (ya < x + 4 * n)]
+        dirty[((hit_x - x) // 4).astype(np.int64)] = True
+        hit_off = ya[(ya >= off) & (ya < off + 4 * n)]
+        dirty[((hit_off - off) // 4).astype(np.int64)] = True
+        gy, wy = r.download(y, np.float32, n), r.sim.view(y, np.float32, n)
+        clean = ~dirty
+        assert clean.sum() > 0.95 * n
+        # An element whose offset word was overwritten by a wrapped store performs one
+        # rogue store at an order-dependent place: at most that many further elements
+        # may differ; all others must match.
+        close = np.abs(gy - wy) <= 2e-7 * np.maximum(1.0, np.abs(wy))
+        assert (clean & ~close).sum() <= len(hit_off)
+        assert rel_frobenius(gy[clean & close], wy[clean & close]) <= FP32_TOL
+    finally:
+        r.close()
+
+
+# ---------------------------------------------------------------------------
+# gather / scatter
+# ---------------------------------------------------------------------------
+
+def test_gather_scatter_i64_with_out_of_bounds_indices():
+    r = Rig([16 * MiB, 16 * MiB])
+    try:
+        t = 0
+        base, size = r.row(t)
+        tab_n, n = 1 << 19, (1 << 19) + 37
+        g = si.rng(2, 0)
+        tab, idx, out = r.alloc(t, 4 * tab_n), r.alloc(t, 8 * n), r.alloc(t, 4 * n)
+        scratch = r.alloc(t, 1 * MiB)
+        r.upload(t, tab, si.normal_f32(g, tab_n))
+        ix, where = si.c2_indices(g, n, tab_n, frac=0.001, oob_hi=1 << 30)
+        # gather has no wrapped stores; only loads that land on `out` (written by this
+        # launch) are order-dependent: redraw those
+        img = ok.fence_array(base, size, np.uint64(tab) + (4 * ix[where]).astype(np.uint64), 4)
+        clash = (img >= out) & (img < out + 4 * n)
+        ix[where[clash]] = tab_n + 5
+        r.upload(t, idx, ix)
+        r.launch(t, gd.GD_K_GATHER32_I64, gd.gd_args_gather(out, tab, idx, n))
+        r.oracle("gather32_i64", t, out, tab, idx, n)
+        assert r.sim.last[2] >= len(where) - clash.sum()
+        r.assert_images_equal(what="gather i64")
+
+        # scatter back, negated.  Out-of-range targets are steered into the scratch
+        # region, each to its own word, so the image is order-independent.
+        oob_slots = g.choice(MiB // 4, size=len(where), replace=False).astype(np.int64)
+        ix[where] = (scratch - tab) // 4 + oob_slots + (size // 4) * g.integers(1, 1 << 20, size=len(where))
+        r.upload(t, idx, ix)
+        r.launch(t, gd.GD_K_SCATTER_F32_I64, gd.gd_args_scatter(tab, out, idx, n, -1.0, 0))
+        # in-bounds duplicates must all carry the same value for the result to be unique:
+        # out[i] == tab_old[idx[i]] holds for them by construction of the gather
+        r.oracle("scatter_f32_i64", t, tab, out, idx, -1.0, n)
+        r.assert_images_equal(what="scatter i64")
+        # in-bounds indices only: fenced and unfenced gathers are bit-identical
+        ix[where] = 0
+        r.upload(t, idx, ix)
+        r.launch(t, gd.GD_K_GATHER32_I64, gd.gd_args_gather(out, tab, idx, n))
+        a = r.download(out, np.uint32, n).copy()
+        r.dview(out, np.uint8, 4 * n).fill_(0)
+        r.launch(t, gd.GD_K_GATHER32_I64, gd.gd_args_gather(out, tab, idx, n), mode=gd.GD_FENCE_NONE)
+        assert np.array_equal(a, r.download(out, np.uint32, n))
+    finally:
+        r.close()
+
+
+@pytest.mark.parametrize("shift", [0, 4])
+def test_gather_i32_with_out_of_bounds_and_negative_indices(rig2, shift):
+    r = rig2
+    t = 1
+    base, size = r.row(t)
+    tab_n, n = 1 << 18, 200003
+    g = si.rng(5, 3)
+    tab, idx, out = r.alloc(t, 4 * tab_n), r.alloc(t, 4 * n + 64) + shift, r.alloc(t, 4 * n + 64) + shift
+    r.upload(t, tab, g.integers(-2**31, 2**31, size=tab_n, dtype=np.int64).astype(np.int32))
+    ix, where = si.c5_indices_i32(g, n, tab_n)
+    ix[where[::3]] *= -1
+    img = ok.fence_array(base, size, (np.uint64(tab) + (4 * ix[where].astype(np.int64)).astype(np.uint64)), 4)
+    clash = (img >= out - 64) & (img < out + 4 * n + 64)
+    ix[where[clash]] = tab_n
+    r.upload(t, idx, ix)
+    r.launch(t, gd.GD_K_GATHER32_I32, gd.gd_args_gather(out, tab, idx, n))
+    r.oracle("gather32_i32", t, out, tab, idx, n)
+    r.assert_images_equal(what="gather i32")
+    fenced = r.download(out, np.int32, n)
+    ix[where] = 1
+    r.upload(t, idx, ix)
+    r.launch(t, gd.GD_K_GATHER32_I32, gd.gd_args_gather(out, tab, idx, n))
+    a = r.download(out, np.int32, n)
+    r.launch(t, gd.GD_K_GATHER32_I32, gd.gd_args_gather(out, tab, idx, n), mode=gd.GD_FENCE_NONE)
+    assert np.array_equal(a, r.download(out, np.int32, n))
+    keep = np.ones(n, bool)
+    keep[where] = False
+    assert np.array_equal(a[keep], fenced[keep])
+
+
+# ---------------------------------------------------------------------------
+# sum, RMSNorm
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n,shift", [(0, 0), (1, 0), (1000, 0), (4099, 0), (1 << 20, 0), ((1 << 22) + 3, 0), (70001, 4)])
+def test_sum_against_fp64(n, shift):
+    r = Rig([32 * MiB, 4 * MiB])
+    try:
+        g = si.rng(5, 1)
+        src = r.alloc(0, 4 * n + 64) + shift
+        ws, out = r.alloc(0, gd.GD_SUM_WORKSPACE), r.alloc(0, 256)
+        r.upload(0, src, si.uniform_f32(g, n, 0.0, 1.0))
+        r.launch(0, gd.GD_K_SUM_F32, gd.gd_args_sum(out, src, ws, n))
+        exact = r.oracle("sum_f32_exact", 0, src, n)
+        r.oracle("sum_f32", 0, out, src, n)
+        got = float(r.download(out, np.float32, 1)[0])
+        assert abs(got - exact) <= FP32_TOL * max(abs(exact), 1e-30) or (n == 0 and got == 0.0)
+        r.assert_images_equal(skip=[(out, 4), (ws, gd.GD_SUM_WORKSPACE)], what="sum")
+        r.launch(0, gd.GD_K_SUM_F32, gd.gd_args_sum(out + 16, src, ws, n), mode=gd.GD_FENCE_NONE)
+        assert r.download(out + 16, np.float32, 1)[0] == np.float32(got)
+        with pytest.raises(gd.GuardianError):
+            r.launch(0, gd.GD_K_SUM_F32, gd.gd_args_sum(out, src, ws, n), grid=(4, 1, 1))
+    finally:
+        r.close()
+
+
+@pytest.mark.parametrize("rows,cols,shift", [(5, 8192, 0), (33, 4096, 0), (7, 1000, 0), (3, 9000, 0), (4, 8200, 0),
+                                             (6, 257, 0), (9, 512, 2), (0, 64, 0)])
+def test_rmsnorm_against_oracle(rows, cols, shift):
+    r = Rig([4 * MiB, 4 * MiB])
+    try:
+        g = si.rng(5, 2)
+        x = r.alloc(0, 2 * rows * cols + 64) + shift
+        y = r.alloc(0, 2 * rows * cols + 64) + shift
+        gain = r.alloc(0, 2 * cols + 64)
+        r.upload(0, x, si.f32_to_bf16_bits(si.normal_f32(g, rows * cols)))
+        r.upload(0, gain, si.f32_to_bf16_bits(si.uniform_f32(g, cols, 0.5, 1.5)))
+        args = gd.gd_args_rmsnorm(y, x, gain, rows, cols, 1e-6, 0)
+        r.launch(0, gd.GD_K_RMSNORM_BF16, args)
+        r.oracle("rmsnorm_bf16", 0, y, x, gain, rows, cols, 1e-6)
+        got = r.download(y, np.uint16, rows * cols)
+        want = r.sim.view(y, np.uint16, rows * cols)
+        if rows:
+            assert rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want)) <= BF16_TOL
+            assert np.mean(got != want) < 0.02          # only sparse one-unit flips
+        r.assert_images_equal(skip=[(y & ~1, 2 * rows * cols)], what="rmsnorm")
+        if shift == 0:
+            r.dview(y, np.uint8, 2 * rows * cols).fill_(0)
+            r.launch(0, gd.GD_K_RMSNORM_BF16, args, mode=gd.GD_FENCE_NONE)
+            assert np.array_equal(r.download(y, np.uint16, rows * cols), got)
+    finally:
+        r.close()
+
+
+# ---------------------------------------------------------------------------
+# GEMM
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("M,N,K,b_is_nk", [(128, 128, 64, 1), (256, 384, 512, 1), (200, 136, 96, 1), (37, 300, 72, 1),
+                                           (129, 1, 8, 1), (64, 64, 20, 1), (50, 70, 33, 0), (128, 96, 64, 0),
+                                           (16, 16, 0, 1)])
+def test_gemm_against_oracle(M, N, K, b_is_nk):
+    r = Rig([8 * MiB, 4 * MiB])
+    try:
+        g = si.rng(4, M + N + K)
+        A, B, Cc = r.alloc(0, 2 * M * K + 16), r.alloc(0, 2 * K * N + 16), r.alloc(0, 2 * M * N)
+        scale = np.float32(1.0 / np.sqrt(max(K, 1)))
+        r.upload(0, A, si.f32_to_bf16_bits(si.normal_f32(g, M * K) * scale))
+        r.upload(0, B, si.f32_to_bf16_bits(si.normal_f32(g, K * N)))
+        args = gd.gd_args_gemm(Cc, A, B, M, N, K, b_is_nk)
+        r.launch(0, gd.GD_K_GEMM_BF16, args)
+        r.oracle("gemm_bf16", 0, Cc, A, B, M, N, K, b_is_nk, 0, M, 0, N)
+        got = r.download(Cc, np.uint16, M * N)
+        want = r.sim.view(Cc, np.uint16, M * N)
+        assert rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want)) <= BF16_TOL
+        r.assert_images_equal(skip=[(Cc, 2 * M * N)], what="gemm")
+        r.dview(Cc, np.uint8, 2 * M * N).fill_(0)
+        r.launch(0, gd.GD_K_GEMM_BF16, args, mode=gd.GD_FENCE_NONE)
+        assert np.array_equal(r.download(Cc, np.uint16, M * N), got)
+    finally:
+        r.close()
+
+
+def test_gemm_with_wrapping_operand_pointers():
+    # A and B addressed through aliases one partition size below: every tile load
+    # is redirected to the real operands, C lands where the oracle says.
+    r = Rig([8 * MiB, 8 * MiB])
+    try:
+        t = 1
+        base, size = r.row(t)
+        M, N, K = 192, 160, 128
+        g = si.rng(4, 99)
+        A, B, Cc = r.alloc(t, 2 * M * K), r.alloc(t, 2 * K * N), r.alloc(t, 2 * M * N)
+        r.upload(t, A, si.f32_to_bf16_bits(si.normal_f32(g, M * K) * np.float32(K ** -0.5)))
+        r.upload(t, B, si.f32_to_bf16_bits(si.normal_f32(g, K * N)))
+        r.launch(t, gd.GD_K_GEMM_BF16, gd.gd_args_gemm(Cc + size, A - size, B - size, M, N, K, 1))
+        r.oracle("gemm_bf16", t, Cc + size, A - size, B - size, M, N, K, 1, 0, M, 0, N)
+        got, want = r.download(Cc, np.uint16, M * N), r.sim.view(Cc, np.uint16, M * N)
+        assert rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want)) <= BF16_TOL
+        r.assert_images_equal(skip=[(Cc, 2 * M * N)], what="gemm wrapped")
+    finally:
+        r.close()
+
+
+# ---------------------------------------------------------------------------
+# tenants on concurrent streams; re-carving mid-run
+# ---------------------------------------------------------------------------
+
+def test_eight_tenants_on_concurrent_streams_stay_in_their_partitions():
+    sizes = [2 * MiB] * 8
+    r = Rig(sizes)
+    try:
+        n = 150001
+        streams = [torch.cuda.Stream() for _ in sizes]
+        plan = []
+        for t in range(8):
+            g = si.rng(3, t)
+            a, b, c = (r.alloc(t, 4 * n) for _ in range(3))
+            r.upload(t, b, si.uniform_f32(g, n))
+            r.upload(t, c, si.uniform_f32(g, n))
+            plan.append((t, a, b, c, float(si.uniform_f32(g, 1)[0])))
+        torch.cuda.synchronize()
+        for _ in range(3):
+            for (t, a, b, c, s), st in zip(plan, streams):
+                # odd tenants misbehave: their pointers are off by whole partitions
+                k = (t % 2) * (t + 1) * sizes[t]
+                r.launch(t, gd.GD_K_TRIAD, gd.gd_args_triad(a + k, b - k, c + 3 * k, n, s, 0), stream=st.cuda_stream)
+                r.launch(t, gd.GD_K_COPY, gd.gd_args_copy(c - k, a + k, n), stream=st.cuda_stream)
+        for _ in range(3):
+            for (t, a, b, c, s) in plan:
+                k = (t % 2) * (t + 1) * sizes[t]
+                r.oracle("triad", t, a + k, b - k, c + 3 * k, s, n)
+                r.oracle("copy", t, c - k, a + k, n)
+        torch.cuda.synchronize()
+        got, want = r.image().view(np.float32), r.sim.mem.view(np.float32)
+        ok_bits = got.view(np.uint32) == want.view(np.uint32)
+        assert rel_frobenius(got[~ok_bits], want[~ok_bits]) <= FP32_TOL if (~ok_bits).any() else True
+        assert (~ok_bits).sum() < 0.001 * got.size
+    finally:
+        r.close()
+
+
+def test_recarve_mid_run_leaves_other_tenants_untouched():
+    sizes = [1 * MiB, 4 * MiB, 2 * MiB, 1 * MiB]
+    r = Rig(sizes)
+    try:
+        n = 60000
+        g = si.rng(5, 9)
+        bufs = {}
+        for t in range(4):
+            src, dst = r.alloc(t, 4 * n), r.alloc(t, 4 * n)
+            r.upload(t, src, si.uniform_f32(g, n))
+            r.launch(t, gd.GD_K_COPY, gd.gd_args_copy(dst, src, n))
+            r.oracle("copy", t, dst, src, n)
+            bufs[t] = (src, dst)
+        r.assert_images_equal(what="before re-carve")
+        # tenants 0 and 2 leave a 3 MiB hole: a 4 MiB tenant does not fit...
+        for t in (0, 2):
+            for p in bufs.pop(t):
+                r.free(t, p)
+            gd.gd_tenant_detach(r.pool, t)
+            assert r.model.detach(t)
+        with pytest.raises(gd.GuardianError) as e:
+            gd.gd_tenant_attach(r.pool, 4 * MiB)
+        assert e.value.status == gd.GD_ENOMEM and r.model.attach(4 * MiB) is None
+        # ...but two 512 KiB tenants and a 1 MiB tenant fit
+        new = [gd.gd_tenant_attach(r.pool, s) for s in (512 * KiB, 1 * MiB, 512 * KiB)]
+        assert new == [r.model.attach(s) for s in (512 * KiB, 1 * MiB, 512 * KiB)]
+        for t in new:
+            b, s, m = gd.gd_partition_info(r.pool, t)
+            assert (b, s) == r.row(t)
+            src, dst = r.alloc(t, 4 * 30000), r.alloc(t, 4 * 30000)
+            r.upload(t, src, si.uniform_f32(g, 30000))
+            # a write-only launch that overruns its (new, smaller) partition on purpose
+            r.launch(t, gd.GD_K_STORE_TID, gd.gd_args_store_tid(dst, 200000, 100 + t, 0))
+            r.oracle("store_tid", t, dst, 100 + t, 200000)
+        r.assert_images_equal(what="after re-carve")
+        for t in (1, 3):
+            src, dst = bufs[t]
+            assert np.array_equal(r.download(dst, np.float32, n), r.sim.view(src, np.float32, n))
+    finally:
+        r.close()
