@@ -1,0 +1,486 @@
+#!/usr/bin/env python3
+"""Benchmark of the fenced-kernel path on one MI355X.
+
+Headline (`value`): configuration 3 -- 8 tenants, a 16 GiB partition each, one
+HIP stream each, fenced STREAM copy + triad on 2^28 fp32 elements per array.
+One step = one round: every tenant launches copy then triad on its stream
+(16 + 24 = 40 GiB of algorithmic traffic).  All inputs are resident in HBM
+before the timed region.  The other four configurations are measured in the
+same run and reported under "per_config", each fenced and unfenced (same
+kernel, fence off) with the overhead in percent.
+
+Prints ONE JSON line on stdout; progress goes to stderr.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+KiB, MiB, GiB = 1 << 10, 1 << 20, 1 << 30
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--configs", default="c3,c4,c2,c1,c5", help="comma list out of c1..c5 (c3 is the headline)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+# ---------------------------------------------------------------------------------
+# device pool plumbing (torch: memory and streams only)
+# ---------------------------------------------------------------------------------
+
+class DevPool:
+    def __init__(self, torch, gd, sizes, fill=None):
+        self.torch, self.gd = torch, gd
+        self.sizes = list(sizes)
+        biggest, total = max(sizes), sum(sizes)
+        self.buf = torch.empty(total + biggest, dtype=torch.uint8, device="cuda")
+        raw = self.buf.data_ptr()
+        self.base = -(-raw // biggest) * biggest
+        self.total = total
+        self.dev = self.buf[self.base - raw:self.base - raw + total]
+        if fill is not None:
+            self.dev.fill_(fill)
+        self.pool = gd.gd_pool_create(self.base, total, self.sizes)
+
+    def alloc(self, tenant, nbytes, align=256):
+        return self.gd.gd_alloc(self.pool, tenant, nbytes, align)
+
+    def view(self, ptr, nbytes):
+        return self.dev[ptr - self.base:ptr - self.base + nbytes]
+
+    def upload(self, tenant, ptr, arr):
+        """Checked host-to-device copy: the range check, then the copy."""
+        arr = np.ascontiguousarray(arr)
+        if self.gd.gd_check_copy(self.pool, tenant, ptr, arr.nbytes) != self.gd.GD_OK:
+            raise RuntimeError("copy refused by gd_check_copy")
+        self.view(ptr, arr.nbytes).copy_(self.torch.from_numpy(arr.view(np.uint8).reshape(-1)))
+
+    def close(self):
+        self.gd.gd_pool_destroy(self.pool)
+        self.buf = self.dev = None
+        self.torch.cuda.empty_cache()
+
+
+def timed_rounds(torch, streams, launch_round, steps, warmup):
+    """launch_round(i) enqueues one round on every stream.  Returns seconds for
+    `steps` rounds: all streams are released by one event, the clock stops at the
+    last stream's end event; bracketed by synchronize on both sides."""
+    for _ in range(warmup):
+        launch_round()
+    torch.cuda.synchronize()
+    go = torch.cuda.Event(enable_timing=True)
+    ends = [torch.cuda.Event(enable_timing=True) for _ in streams]
+    t0 = time.perf_counter()
+    go.record()
+    for s in streams:
+        s.wait_event(go)
+    for _ in range(steps):
+        launch_round()
+    for s, e in zip(streams, ends):
+        e.record(s)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    dev = max(go.elapsed_time(e) for e in ends) * 1e-3
+    return dev, wall
+
+
+def solo_avg_seconds(torch, stream, launch, reps, warmup=2):
+    """Average duration of one launch, back to back on one stream, by HIP events
+    recorded on that stream."""
+    for _ in range(warmup):
+        launch()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(stream)
+    for _ in range(reps):
+        launch()
+    b.record(stream)
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) * 1e-3 / reps
+
+
+def pct_overhead(fenced_rate, unfenced_rate):
+    return round(100.0 * (unfenced_rate / fenced_rate - 1.0), 2) if fenced_rate else None
+
+
+# ---------------------------------------------------------------------------------
+# configuration 3 (headline): 8 tenants x 16 GiB, copy + triad on 8 streams
+# ---------------------------------------------------------------------------------
+
+def run_c3(torch, gd, si, args):
+    n = 1 << 28
+    tenants = 8
+    log(f"[c3] carving {tenants} x 16 GiB and uploading seeded inputs")
+    dp = DevPool(torch, gd, [16 * GiB] * tenants)
+    streams = [torch.cuda.Stream() for _ in range(tenants)]
+    host = np.empty(n, np.float32)
+    plan = []
+    for t in range(tenants):
+        a, b, c = (dp.alloc(t, 4 * n) for _ in range(3))
+        for part, ptr in ((1, b), (2, c)):
+            si.fill_chunked(host, 3, t + 100 * part, "uniform", threads=16)
+            dp.upload(t, ptr, host)
+        s = float(si.uniform_f32(si.rng(3, t), 1)[0])
+        plan.append((t, a, b, c, s))
+    torch.cuda.synchronize()
+    del host
+
+    def round_of(mode):
+        def go():
+            for (t, a, b, c, s), st in zip(plan, streams):
+                gd.gd_launch_fenced(dp.pool, t, gd.GD_K_COPY, gd.gd_args_copy(a, b, n), stream=st.cuda_stream, mode=mode)
+                gd.gd_launch_fenced(dp.pool, t, gd.GD_K_TRIAD, gd.gd_args_triad(a, b, c, n, s, 0), stream=st.cuda_stream, mode=mode)
+        return go
+
+    bytes_round = tenants * (8 + 12) * n
+    res = {}
+    for name, mode in (("fenced", gd.GD_FENCE_BITWISE), ("unfenced", gd.GD_FENCE_NONE)):
+        dev, wall = timed_rounds(torch, streams, round_of(mode), args.steps, args.warmup)
+        res[name] = {"seconds": dev, "wall_seconds": wall, "GBps": bytes_round * args.steps / dev / 1e9}
+        log(f"[c3] {name}: {res[name]['GBps']:.1f} GB/s aggregate over {tenants} streams ({dev / args.steps * 1e3:.3f} ms/round)")
+
+    # each kernel alone on tenant 0's stream: the per-launch figures of the roofline
+    t, a, b, c, s = plan[0]
+    st = streams[0]
+    solo = {}
+    for kname, kid, kargs, nbytes in (("copy", gd.GD_K_COPY, gd.gd_args_copy(a, b, n), 8 * n),
+                                      ("triad", gd.GD_K_TRIAD, gd.gd_args_triad(a, b, c, n, s, 0), 12 * n)):
+        for name, mode in (("fenced", gd.GD_FENCE_BITWISE), ("unfenced", gd.GD_FENCE_NONE)):
+            sec = solo_avg_seconds(torch, st, lambda: gd.gd_launch_fenced(dp.pool, t, kid, kargs, stream=st.cuda_stream, mode=mode), args.steps)
+            solo[f"{kname}_{name}"] = {"avg_launch_ms": sec * 1e3, "GBps": nbytes / sec / 1e9}
+            log(f"[c3] {kname} {name} alone: {nbytes / sec / 1e9:.1f} GB/s ({sec * 1e3:.3f} ms/launch)")
+    dp.close()
+    return {
+        "workload": "8 tenants x 16 GiB partitions, 8 streams, fp32 copy + triad, 2^28 elements per array",
+        "bytes_per_round": bytes_round,
+        "fenced_GBps": res["fenced"]["GBps"], "unfenced_GBps": res["unfenced"]["GBps"],
+        "overhead_pct": pct_overhead(res["fenced"]["GBps"], res["unfenced"]["GBps"]),
+        "frac_of_hbm_peak": res["fenced"]["GBps"] / HBM_PEAK_GBPS,
+        "ms_per_round_fenced": res["fenced"]["seconds"] / args.steps * 1e3,
+        "wall_seconds_fenced": res["fenced"]["wall_seconds"],
+        "solo": solo,
+        "triad_bytes_per_launch": 12 * n,
+    }
+
+
+# ---------------------------------------------------------------------------------
+# configuration 4: bf16 GEMM 8192^3 in a 4 GiB partition
+# ---------------------------------------------------------------------------------
+
+def run_c4(torch, gd, si, args):
+    M = N = K = 8192
+    log("[c4] GEMM 8192^3 bf16")
+    dp = DevPool(torch, gd, [4 * GiB])
+    A, B, Cc = (dp.alloc(0, 2 * M * K) for _ in range(3))
+    host = np.empty(M * K, np.float32)
+    si.fill_chunked(host, 4, 1, "normal", threads=16)
+    dp.upload(0, A, si.f32_to_bf16_bits(host * np.float32(K ** -0.5)))
+    si.fill_chunked(host, 4, 2, "normal", threads=16)
+    dp.upload(0, B, si.f32_to_bf16_bits(host))
+    del host
+    st = torch.cuda.Stream()
+    kargs = gd.gd_args_gemm(Cc, A, B, M, N, K, 1)
+    flop = 2.0 * M * N * K
+    out = {"workload": "1 tenant, 4 GiB partition, C = A*B, M=N=K=8192, bf16 in/out, fp32 accumulate, B stored N x K", "flop": flop}
+    for name, mode in (("fenced", gd.GD_FENCE_BITWISE), ("unfenced", gd.GD_FENCE_NONE)):
+        sec = solo_avg_seconds(torch, st, lambda: gd.gd_launch_fenced(dp.pool, 0, gd.GD_K_GEMM_BF16, kargs, stream=st.cuda_stream, mode=mode), args.steps)
+        out[f"{name}_TFLOPs"] = flop / sec / 1e12
+        out[f"{name}_ms"] = sec * 1e3
+        log(f"[c4] {name}: {flop / sec / 1e12:.1f} TFLOP/s ({sec * 1e3:.3f} ms)")
+    out["overhead_pct"] = pct_overhead(out["fenced_TFLOPs"], out["unfenced_TFLOPs"])
+    out["frac_of_mfma_peak"] = out["fenced_TFLOPs"] / MFMA_BF16_PEAK_TFLOPS
+    dp.close()
+    return out
+
+
+# ---------------------------------------------------------------------------------
+# configuration 2: gather then scatter, 2^26 elements, 0.1 % of indices out of bounds
+# ---------------------------------------------------------------------------------
+
+def run_c2(torch, gd, si, args):
+    n = tab_n = 1 << 26
+    log("[c2] gather/scatter 2^26")
+    dp = DevPool(torch, gd, [1 * GiB, 1 * GiB])
+    canary = si.address_canary(1 << 20)
+    nb_base, nb_size, _ = gd.gd_partition_info(dp.pool, 1)
+    for k in range(0, nb_size, canary.nbytes):
+        dp.upload(1, nb_base + k, canary)
+    tab, idx, out = dp.alloc(0, 4 * tab_n), dp.alloc(0, 8 * n), dp.alloc(0, 4 * n)
+    host = np.empty(tab_n, np.float32)
+    si.fill_chunked(host, 2, 1, "normal", threads=16)
+    dp.upload(0, tab, host)
+    del host
+    ix, where = si.c2_indices(si.rng(2, 0), n, tab_n)
+    dp.upload(0, idx, ix)
+    st = torch.cuda.Stream()
+    res = {"workload": "1 tenant, 1 GiB partition, fp32 table 2^26, int64 indices 2^26 (0.1 % in [2^26, 2^30)), gather then scatter; neighbour partition holds a canary",
+           "bytes_per_launch": 16 * n}
+    g_args, s_args = gd.gd_args_gather(out, tab, idx, n), gd.gd_args_scatter(tab, out, idx, n, -1.0, 0)
+    for kname, kid, kargs in (("gather", gd.GD_K_GATHER32_I64, g_args), ("scatter", gd.GD_K_SCATTER_F32_I64, s_args)):
+        # the unfenced build may only see in-bounds indices
+        for name, mode in (("fenced", gd.GD_FENCE_BITWISE), ("fenced_inbounds", gd.GD_FENCE_BITWISE), ("unfenced_inbounds", gd.GD_FENCE_NONE)):
+            if name == "fenced_inbounds":
+                ix[where] = ix[(where + 1) % n] % tab_n
+                dp.upload(0, idx, ix)
+            sec = solo_avg_seconds(torch, st, lambda: gd.gd_launch_fenced(dp.pool, 0, kid, kargs, stream=st.cuda_stream, mode=mode), max(3, args.steps // 2))
+            res[f"{kname}_{name}_GBps"] = 16 * n / sec / 1e9
+            log(f"[c2] {kname} {name}: {16 * n / sec / 1e9:.1f} GB/s ({sec * 1e3:.3f} ms)")
+        res[f"{kname}_overhead_pct"] = pct_overhead(res[f"{kname}_fenced_inbounds_GBps"], res[f"{kname}_unfenced_inbounds_GBps"])
+        ix, where = si.c2_indices(si.rng(2, 0), n, tab_n)
+        dp.upload(0, idx, ix)
+    torch.cuda.synchronize()
+    want = torch.from_numpy(canary.view(np.int64)).cuda()
+    got = dp.view(nb_base, nb_size).view(torch.int64).reshape(-1, want.numel())
+    res["canary_intact"] = bool((got == want).all().item())
+    dp.close()
+    return res
+
+
+# ---------------------------------------------------------------------------------
+# configuration 1: two tenants, 4 MiB partitions, indexed saxpy, 1 % offsets out of range
+# ---------------------------------------------------------------------------------
+
+def run_c1(torch, gd, si, args):
+    n = 262144
+    log("[c1] indexed saxpy, 2 tenants")
+    dp = DevPool(torch, gd, [4 * MiB, 4 * MiB], fill=0xA5)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    plans = {}
+    for literal in (True, False):
+        plan = []
+        for t in range(2):
+            base, size, _ = gd.gd_partition_info(dp.pool, t)
+            g = si.rng(1, t)
+            if literal:
+                x, y, off = (dp.alloc(t, 4 * n) for _ in range(3))
+            else:
+                x, y, off = plans[True][t][1:4]
+            offs, where = si.c1_offsets(g, n, y, base, size)
+            if not literal:
+                offs = np.arange(n, dtype=np.int32)
+            plan.append((t, x, y, off, offs, float(si.uniform_f32(g, 1)[0])))
+        plans[literal] = plan
+    launches = 1000
+    res = {"workload": "2 tenants x 4 MiB partitions, 2 streams, fp32 y[o]=a*x[o]+y[o], n=262144, 1 % of offsets out of range",
+           "bytes_per_tenant_launch": 16 * n, "launches_per_stream": launches}
+    for name, literal, mode in (("fenced", True, gd.GD_FENCE_BITWISE), ("fenced_inbounds", False, gd.GD_FENCE_BITWISE),
+                                ("unfenced_inbounds", False, gd.GD_FENCE_NONE)):
+        g = si.rng(1, 50)
+        for (t, x, y, off, offs, alpha) in plans[literal]:
+            dp.upload(t, x, si.uniform_f32(g, n))
+            dp.upload(t, y, np.zeros(n, np.float32))
+            dp.upload(t, off, offs)
+
+        def go():
+            for (t, x, y, off, offs, alpha), st in zip(plans[literal], streams):
+                gd.gd_launch_fenced(dp.pool, t, gd.GD_K_SAXPY_IDX, gd.gd_args_saxpy_idx(x, y, off, n, alpha * 1e-3, 0), stream=st.cuda_stream, mode=mode)
+        dev, _ = timed_rounds(torch, streams, go, launches, 20)
+        res[f"{name}_GBps"] = 2 * 16 * n * launches / dev / 1e9
+        res[f"{name}_us_per_round"] = dev / launches * 1e6
+        log(f"[c1] {name}: {res[f'{name}_GBps']:.1f} GB/s effective ({dev / launches * 1e6:.2f} us per 2-tenant round)")
+    res["overhead_pct"] = pct_overhead(res["fenced_inbounds_GBps"], res["unfenced_inbounds_GBps"])
+    dp.close()
+    return res
+
+
+# ---------------------------------------------------------------------------------
+# configuration 5: 16 tenants, mixed partition sizes, sum / RMSNorm / int32 gather, re-carve
+# ---------------------------------------------------------------------------------
+
+def run_c5(torch, gd, si, args):
+    g = si.rng(5, 0)
+    sizes = si.c5_partition_sizes(g, 16, budget=128 * GiB)
+    log(f"[c5] 16 tenants, sizes (MiB): {[s // MiB for s in sizes]}")
+    dp = DevPool(torch, gd, sizes)
+    streams = [torch.cuda.Stream() for _ in sizes]
+    n_sum, rows, cols, n_g = 1 << 27, 4096, 8192, 1 << 24
+
+    def setup(t, kind):
+        gt = si.rng(5, t + 1)
+        if kind == "sum":
+            src, ws, out = dp.alloc(t, 4 * n_sum), dp.alloc(t, gd.GD_SUM_WORKSPACE), dp.alloc(t, 256)
+            host = np.empty(n_sum, np.float32)
+            si.fill_chunked(host, 5, t + 1, "uniform", 0.0, 1.0, threads=16)
+            dp.upload(t, src, host)
+            return gd.GD_K_SUM_F32, gd.gd_args_sum(out, src, ws, n_sum), 4 * n_sum, [src, ws, out]
+        if kind == "rmsnorm":
+            x, y, gain = dp.alloc(t, 2 * rows * cols), dp.alloc(t, 2 * rows * cols), dp.alloc(t, 2 * cols)
+            dp.upload(t, x, si.f32_to_bf16_bits(si.normal_f32(gt, rows * cols)))
+            dp.upload(t, gain, si.f32_to_bf16_bits(si.uniform_f32(gt, cols, 0.5, 1.5)))
+            return gd.GD_K_RMSNORM_BF16, gd.gd_args_rmsnorm(y, x, gain, rows, cols, 1e-6, 0), 4 * rows * cols, [x, y, gain]
+        tab, idx, out = dp.alloc(t, 4 * n_g), dp.alloc(t, 4 * n_g), dp.alloc(t, 4 * n_g)
+        dp.upload(t, tab, gt.integers(-2**31, 2**31, size=n_g, dtype=np.int64).astype(np.int32))
+        dp.upload(t, idx, si.c5_indices_i32(gt, n_g, n_g)[0])
+        return gd.GD_K_GATHER32_I32, gd.gd_args_gather(out, tab, idx, n_g), 12 * n_g, [tab, idx, out]
+
+    kinds = ["sum", "rmsnorm", "gather"]
+    work = {}
+    k = 0
+    for t, s in enumerate(sizes):
+        kind = kinds[k % 3]
+        if kind == "sum" and s < GiB:
+            kind = "rmsnorm" if (k // 3) % 2 == 0 else "gather"
+        k += 1
+        work[t] = (kind,) + setup(t, kind)
+    if not any(w[0] == "sum" for w in work.values()):
+        raise RuntimeError("no tenant large enough for the reduction")
+    torch.cuda.synchronize()
+
+    res = {"workload": "16 tenants, pow2 partitions in [256 MiB, 8 GiB], 16 streams: fp32 sum 2^27, bf16 RMSNorm 4096x8192, int32 gather 2^24 (0.5 % out of bounds); 4 tenants re-carved mid-run",
+           "partition_MiB": [s // MiB for s in sizes], "assignment": [work[t][0] for t in range(16)]}
+    # each kernel alone
+    for kind in kinds:
+        t = next(t for t in work if work[t][0] == kind)
+        _, kid, kargs, nbytes, _ = work[t]
+        for name, mode in (("fenced", gd.GD_FENCE_BITWISE), ("unfenced", gd.GD_FENCE_NONE)):
+            if kind == "gather" and mode == gd.GD_FENCE_NONE:
+                dp.upload(t, kargs.idx, np.abs(si.c5_indices_i32(si.rng(5, t + 1), n_g, n_g)[0]) % n_g)
+            sec = solo_avg_seconds(torch, streams[t], lambda: gd.gd_launch_fenced(dp.pool, t, kid, kargs, stream=streams[t].cuda_stream, mode=mode), args.steps)
+            res[f"{kind}_{name}_GBps"] = nbytes / sec / 1e9
+            log(f"[c5] {kind} {name} alone: {nbytes / sec / 1e9:.1f} GB/s ({sec * 1e6:.1f} us)")
+        if kind == "gather":
+            sec = solo_avg_seconds(torch, streams[t], lambda: gd.gd_launch_fenced(dp.pool, t, kid, kargs, stream=streams[t].cuda_stream, mode=gd.GD_FENCE_BITWISE), args.steps)
+            res["gather_fenced_inbounds_GBps"] = nbytes / sec / 1e9
+            res["gather_overhead_pct"] = pct_overhead(res["gather_fenced_inbounds_GBps"], res["gather_unfenced_GBps"])
+            dp.upload(t, kargs.idx, si.c5_indices_i32(si.rng(5, t + 1), n_g, n_g)[0])
+        else:
+            res[f"{kind}_overhead_pct"] = pct_overhead(res[f"{kind}_fenced_GBps"], res[f"{kind}_unfenced_GBps"])
+
+    def mixed_round():
+        for t, (kind, kid, kargs, nbytes, _) in work.items():
+            gd.gd_launch_fenced(dp.pool, t, kid, kargs, stream=streams[t].cuda_stream, mode=gd.GD_FENCE_BITWISE)
+
+    bytes_round = sum(w[3] for w in work.values())
+    dev, _ = timed_rounds(torch, streams, mixed_round, args.steps, args.warmup)
+    res["mixed_fenced_GBps_before_recarve"] = bytes_round * args.steps / dev / 1e9
+
+    # re-carve: four tenants free everything, detach, and come back with another size
+    t0 = time.perf_counter()
+    movers = [int(t) for t in g.choice(16, size=4, replace=False)]
+    for t in movers:
+        for p in work[t][4]:
+            gd.gd_free(dp.pool, t, p)
+        gd.gd_tenant_detach(dp.pool, t)
+    resized = sorted(((sizes[t] // 2 if sizes[t] > 512 * MiB else sizes[t] * 2), t) for t in movers)[::-1]
+    for new_size, t in resized:
+        for trial in (new_size, sizes[t], sizes[t] // 2):
+            try:
+                nt = gd.gd_tenant_attach(dp.pool, trial)
+                new_size = trial
+                break
+            except gd.GuardianError as e:
+                if e.status != gd.GD_ENOMEM:
+                    raise
+        else:
+            raise RuntimeError("re-carve: no room for a returning tenant")
+        kind = "rmsnorm" if new_size < GiB or work[t][0] != "sum" else "sum"
+        del work[t]
+        work[nt] = (kind,) + setup(nt, kind)
+    res["recarve_host_ms"] = (time.perf_counter() - t0) * 1e3
+    torch.cuda.synchronize()
+    bytes_round = sum(w[3] for w in work.values())
+    dev, _ = timed_rounds(torch, streams, mixed_round, args.steps, args.warmup)
+    res["mixed_fenced_GBps_after_recarve"] = bytes_round * args.steps / dev / 1e9
+    log(f"[c5] mixed 16-stream rounds: {res['mixed_fenced_GBps_before_recarve']:.1f} GB/s before, {res['mixed_fenced_GBps_after_recarve']:.1f} GB/s after the re-carve")
+    dp.close()
+    return res
+
+
+# ---------------------------------------------------------------------------------
+# CPU baseline: the oracle as it stands, one tenant's share of a round
+# ---------------------------------------------------------------------------------
+
+def cpu_baseline(si):
+    from oracle import kernels as ok
+    n = 1 << 28
+    base, size = 1 << 40, 16 * GiB
+    log("[cpu] timing the oracle (plain C, 1 thread) on copy + triad, 2^28 elements")
+    sim = ok.SimPool(base, 3 * 4 * n, 0)
+    a, b, c = base, base + 4 * n, base + 8 * n
+    si.fill_chunked(sim.view(b, np.float32, n), 3, 101, "uniform", threads=8)
+    si.fill_chunked(sim.view(c, np.float32, n), 3, 201, "uniform", threads=8)
+    t0 = time.perf_counter()
+    sim.run("copy", (base, size), ok.MODE_BITWISE, a, b, n)
+    sim.run("triad", (base, size), ok.MODE_BITWISE, a, b, c, 0.5, n)
+    sec = time.perf_counter() - t0
+    assert sim.last[0] == 0
+    return {"value": (8 + 12) * n / sec / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "fenced copy + triad of one tenant (2^28 fp32 elements per array): 1/8 of a round",
+            "seconds": sec}
+
+
+def read_traffic():
+    """HBM bytes per fenced triad launch from the committed rocprofv3 --pmc summary, if any."""
+    path = os.path.join(ROOT, "profiles", "k_stream_triad_c3_pmc.txt")
+    try:
+        for ln in open(path):
+            if ln.startswith("traffic_bytes_per_launch:"):
+                return float(ln.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (tenants are streams of one context); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2401_09290_amd as gd
+    import synth_inputs as si
+    gd.lib()   # fails loudly if the HIP library has not been built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    runners = {"c1": run_c1, "c2": run_c2, "c3": run_c3, "c4": run_c4, "c5": run_c5}
+    wanted = [c.strip() for c in args.configs.split(",") if c.strip()]
+    per = {}
+    for c in wanted:
+        t0 = time.perf_counter()
+        per[c] = runners[c](torch, gd, si, args)
+        per[c]["bench_seconds"] = round(time.perf_counter() - t0, 1)
+    out = {
+        "metric": "fenced HBM GB/s, 8 tenants on 8 streams (copy + triad); GEMM TFLOP/s and % overhead vs unfenced under per_config",
+        "value": None, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": None, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "configs[2]: 8 tenants x 16 GiB power-of-two partitions on 8 concurrent HIP streams, fenced STREAM copy + triad, fp32, 2^28 elements per array, all accesses in bounds"},
+        "per_config": per,
+    }
+    if "c3" in per:
+        c3 = per["c3"]
+        out["value"] = round(c3["fenced_GBps"], 1)
+        out["ms_per_step"] = round(c3["ms_per_round_fenced"], 4)
+        tri = c3["solo"]["triad_fenced"]
+        out["roofline"] = {"bound": "hbm", "kernel": "k_stream<V_BIT64, triad>", "achieved": round(tri["GBps"], 1),
+                           "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(tri["GBps"] / HBM_PEAK_GBPS, 4),
+                           "avg_launch_ms": round(tri["avg_launch_ms"], 4), "bytes_per_launch": c3["triad_bytes_per_launch"],
+                           "traffic": read_traffic()}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(si)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
