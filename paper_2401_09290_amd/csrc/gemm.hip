@@ -4,6 +4,17 @@
 // 16-byte runs along K -- or row-major K x N (handled by the generic kernel).
 // Tiles of A and B are staged through LDS; every global tile load and every
 // store of C carries the fence on its final address.  LDS is not fenced.
+//
+// Tiled kernel: one workgroup of 4 wavefronts (2 x 2) computes a 256 x 256 tile
+// of C; each wavefront owns 128 x 128 of it as 4 x 4 MFMA tiles (256 fp32
+// accumulators per lane, one wavefront per SIMD).  K advances in steps of 64
+// through two LDS stages of 64 KiB (A 256x64 + B 256x64 bf16 each): while the
+// MFMAs of step t read stage t&1, the tile of step t+1 (already in registers) is
+// written to the other stage and the tile of step t+2 is fetched from global
+// memory, so one barrier per step suffices.  LDS rows are 128 bytes; the eight
+// 16-byte granules of a row are XOR-swizzled with the row number so that the
+// 32 rows a fragment load touches fall into different banks.  The finished tile
+// is converted to bf16, transposed through LDS and stored as 16-byte runs.
 #include "launchers.hpp"
 
 namespace gd {
@@ -40,31 +51,70 @@ __global__ __launch_bounds__(256) void k_gemm_generic(gd_args_gemm p, FenceArgs 
     }
 }
 
-// ---- tiled MFMA kernel: B stored N x K, K % 8 == 0, 16-byte aligned pointers ----------
-// Workgroup tile BM x BN, K step BK, WM x WN wavefronts; each wavefront owns a
-// (BM/WM) x (BN/WN) block of C made of 32x32 MFMA tiles.
-template <int V, int BM, int BN, int BK, int WM, int WN>
-__global__ __launch_bounds__(WM *WN * 64) void k_gemm_nk(gd_args_gemm p, FenceArgs fa)
-{
-    constexpr int NT = WM * WN * 64;
-    constexpr int GPR = BK / 8;                 // 16-byte granules per tile row
-    constexpr int LDS_ROW = BK + 8;             // padded row, in bf16 elements
-    constexpr int A_LOADS = BM * GPR / NT;
-    constexpr int B_LOADS = BN * GPR / NT;
-    constexpr int TM = BM / WM / 32;
-    constexpr int TN = BN / WN / 32;
-    static_assert(BM * GPR % NT == 0 && BN * GPR % NT == 0, "tile loads must divide evenly");
+// ---- tiled MFMA kernel ---------------------------------------------------------------
+// Requirements (checked by the launcher): B stored N x K, K % 8 == 0, A and B
+// 16-byte aligned.  EDGE = 0 additionally assumes M % 256 == 0, N % 256 == 0,
+// K % 64 == 0, C 16-byte aligned: no predicates anywhere.
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int TM = 4, TN = 4;                       // MFMA tiles per wavefront
+constexpr int STAGE_BYTES = (BM + BN) * BK * 2;     // 64 KiB
+constexpr int A_BYTES = BM * BK * 2;                // 32 KiB
+constexpr int LOADS = BM * (BK / 8) / 256;          // 16-byte granules per thread per operand: 8
+constexpr int GROUP_M = 4;                          // tile rows walked together (L2 reuse)
 
+template <int V, bool EDGE>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void k_gemm_nk256(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_n)
+{
     const Fence<V> F(fa);
-    __shared__ __attribute__((aligned(16))) uint16_t As[BM * LDS_ROW];
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[BN * LDS_ROW];
+    __shared__ __attribute__((aligned(16))) uint8_t smem[2 * STAGE_BYTES];
 
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & 63, wave = tid >> 6;
-    const uint32_t wm = wave / WN, wn = wave % WN;
-    const uint32_t tiles_n = (p.N + BN - 1) / BN;
-    const uint32_t m0 = (blockIdx.x / tiles_n) * BM;
-    const uint32_t n0 = (blockIdx.x % tiles_n) * BN;
+    const uint32_t wm = wave >> 1, wn = wave & 1;
+
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): give
+    // every XCD a contiguous run of tiles, walked GROUP_M tile rows at a time.
+    uint32_t lin = blockIdx.x;
+    const uint32_t nblk = gridDim.x;
+    if ((nblk & 7) == 0) lin = (lin & 7) * (nblk >> 3) + (lin >> 3);
+    const uint32_t width = GROUP_M * tiles_n;
+    const uint32_t first_m = (lin / width) * GROUP_M;
+    const uint32_t gsize = (tiles_m - first_m < GROUP_M) ? tiles_m - first_m : GROUP_M;
+    const uint32_t m0 = (first_m + (lin % width) % gsize) * BM;
+    const uint32_t n0 = ((lin % width) / gsize) * BN;
+
+    // global -> register -> LDS mapping: thread = (row t/8 + 32*i, granule t%8)
+    const uint32_t lrow = tid >> 3, lg = tid & 7;
+    const uint64_t a_ptr = p.A + 2 * ((uint64_t)(m0 + lrow) * p.K + lg * 8);
+    const uint64_t b_ptr = p.B + 2 * ((uint64_t)(n0 + lrow) * p.K + lg * 8);
+    const uint64_t row_step = 2 * 32 * (uint64_t)p.K;
+    const uint32_t lds_w = lrow * 128 + ((lg ^ (lrow & 7)) << 4);
+
+    u32x4 ra[LOADS], rb[LOADS];
+    auto gload = [&](uint32_t k0) {
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            if (EDGE) {
+                ra[i] = (u32x4){0, 0, 0, 0};
+                rb[i] = (u32x4){0, 0, 0, 0};
+                const bool kin = k0 + lg * 8 < p.K;
+                if (kin && m0 + lrow + 32 * i < p.M) ra[i] = F.template ld<u32x4>(a_ptr + i * row_step + 2 * (uint64_t)k0);
+                if (kin && n0 + lrow + 32 * i < p.N) rb[i] = F.template ld<u32x4>(b_ptr + i * row_step + 2 * (uint64_t)k0);
+            } else {
+                ra[i] = F.template ld<u32x4>(a_ptr + i * row_step + 2 * (uint64_t)k0);
+                rb[i] = F.template ld<u32x4>(b_ptr + i * row_step + 2 * (uint64_t)k0);
+            }
+        }
+    };
+    auto lstore = [&](uint32_t stage) {
+        uint8_t *sa = smem + stage * STAGE_BYTES + lds_w;
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            *(u32x4 *)(sa + i * 32 * 128) = ra[i];
+            *(u32x4 *)(sa + A_BYTES + i * 32 * 128) = rb[i];
+        }
+    };
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -74,55 +124,33 @@ __global__ __launch_bounds__(WM *WN * 64) void k_gemm_nk(gd_args_gemm p, FenceAr
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    u32x4 ra[A_LOADS], rb[B_LOADS];
-    auto load_tile = [&](uint32_t k0) {
+    // fragment addresses: lane = (row l%32, k half l/32); granule (2*kk + half) ^ (row & 7)
+    const uint32_t frow = lane & 31, fhalf = lane >> 5;
+    const uint32_t a_frag = (wm * 128 + frow) * 128;
+    const uint32_t b_frag = A_BYTES + (wn * 128 + frow) * 128;
+    uint32_t gsw[BK / 16];
 #pragma unroll
-        for (int i = 0; i < A_LOADS; ++i) {
-            const uint32_t q = tid + i * NT, row = q / GPR, g = q % GPR;
-            const uint32_t m = m0 + row, k = k0 + g * 8;
-            ra[i] = (u32x4){0, 0, 0, 0};
-            if (m < p.M && k < p.K) ra[i] = F.template ld<u32x4>(p.A + 2 * ((uint64_t)m * p.K + k));
-        }
-#pragma unroll
-        for (int i = 0; i < B_LOADS; ++i) {
-            const uint32_t q = tid + i * NT, row = q / GPR, g = q % GPR;
-            const uint32_t n = n0 + row, k = k0 + g * 8;
-            rb[i] = (u32x4){0, 0, 0, 0};
-            if (n < p.N && k < p.K) rb[i] = F.template ld<u32x4>(p.B + 2 * ((uint64_t)n * p.K + k));
-        }
-    };
-    auto store_tile = [&]() {
-#pragma unroll
-        for (int i = 0; i < A_LOADS; ++i) {
-            const uint32_t q = tid + i * NT, row = q / GPR, g = q % GPR;
-            *(u32x4 *)&As[row * LDS_ROW + g * 8] = ra[i];
-        }
-#pragma unroll
-        for (int i = 0; i < B_LOADS; ++i) {
-            const uint32_t q = tid + i * NT, row = q / GPR, g = q % GPR;
-            *(u32x4 *)&Bs[row * LDS_ROW + g * 8] = rb[i];
-        }
-    };
+    for (int kk = 0; kk < BK / 16; ++kk) gsw[kk] = ((2 * kk + fhalf) ^ (frow & 7)) << 4;
 
-    load_tile(0);
-    for (uint32_t k0 = 0; k0 < p.K; k0 += BK) {
-        store_tile();
-        __syncthreads();
-        if (k0 + BK < p.K) load_tile(k0 + BK);
+    const uint32_t ksteps = (p.K + BK - 1) / BK;
+    gload(0);
+    lstore(0);
+    if (ksteps > 1) gload(BK);
+    __syncthreads();
+
+    for (uint32_t t = 0; t < ksteps; ++t) {
+        const uint8_t *st = smem + (t & 1) * STAGE_BYTES;
+        if (t + 1 < ksteps) lstore((t + 1) & 1);          // tile t+1: registers -> other stage
+        if (t + 2 < ksteps) gload((t + 2) * BK);          // tile t+2: global -> registers
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             bf16x8 fa_[TM], fb_[TN];
-            const uint32_t kcol = kk * 16 + (lane >> 5) * 8;
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const uint32_t row = wm * (BM / WM) + i * 32 + (lane & 31);
-                fa_[i] = __builtin_bit_cast(bf16x8, *(const u32x4 *)&As[row * LDS_ROW + kcol]);
-            }
+            for (int i = 0; i < TM; ++i)
+                fa_[i] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(st + a_frag + i * 32 * 128 + gsw[kk]));
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const uint32_t row = wn * (BN / WN) + j * 32 + (lane & 31);
-                fb_[j] = __builtin_bit_cast(bf16x8, *(const u32x4 *)&Bs[row * LDS_ROW + kcol]);
-            }
+            for (int j = 0; j < TN; ++j)
+                fb_[j] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(st + b_frag + j * 32 * 128 + gsw[kk]));
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -132,20 +160,43 @@ __global__ __launch_bounds__(WM *WN * 64) void k_gemm_nk(gd_args_gemm p, FenceAr
         __syncthreads();
     }
 
-    // acc[i][j][r] is C[row, col] with row = 8*(r/4) + 4*(lane/32) + r%4, col = lane%32
-    // inside the 32x32 tile.
+    // Epilogue.  acc[i][j][r] is C[row, col] of the wavefront's block with
+    // row = 32*i + 8*(r/4) + 4*(lane/32) + r%4, col = 32*j + lane%32.  Each
+    // wavefront parks its 128 x 128 bf16 block in its own 32 KiB of LDS (rows of
+    // 256 bytes), then streams it out as 16-byte runs: 16 lanes cover one row.
+    uint8_t *park = smem + wave * (128 * 256);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const uint32_t m = m0 + wm * (BM / WM) + i * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r & 3);
-                const uint32_t n = n0 + wn * (BN / WN) + j * 32 + (lane & 31);
-                if (m < p.M && n < p.N)
-                    F.template st<uint16_t>(p.C + 2 * ((uint64_t)m * p.N + n),
-                                            (uint16_t)gemm_f32_to_bf16(acc[i][j][r]));
+                const uint32_t row = 32 * i + 8 * (r / 4) + 4 * fhalf + (r & 3);
+                const uint32_t col = 32 * j + frow;
+                *(uint16_t *)(park + row * 256 + col * 2) = (uint16_t)gemm_f32_to_bf16(acc[i][j][r]);
             }
+    __syncthreads();
+    const uint32_t orow = lane >> 4, og = lane & 15;
+    const bool vec_ok = !EDGE || (((p.C & 15) == 0) && ((p.N & 7) == 0));
+#pragma unroll 4
+    for (int it = 0; it < 32; ++it) {
+        const uint32_t row = orow + 4 * it;
+        const uint32_t m = m0 + wm * 128 + row, n = n0 + wn * 128 + og * 8;
+        const u32x4 v = *(const u32x4 *)(park + row * 256 + og * 16);
+        const uint64_t dst = p.C + 2 * ((uint64_t)m * p.N + n);
+        if (!EDGE) {
+            F.template st<u32x4>(dst, v);
+        } else if (m < p.M && n < p.N) {
+            if (vec_ok && n + 8 <= p.N) {
+                F.template st<u32x4>(dst, v);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (n + e < p.N)
+                        F.template st<uint16_t>(dst + 2 * e, (uint16_t)(v[e >> 1] >> ((e & 1) * 16)));
+            }
+        }
+    }
 }
 
 // ---- launcher ---------------------------------------------------------------------------
@@ -158,17 +209,23 @@ int launch_gemm_bf16(const void *args, const FenceArgs &f, int variant, const Sh
     if (p.M == 0 || p.N == 0) return GD_OK;
     const bool tiled = p.b_is_nk && p.K > 0 && (p.K % 8) == 0 && ((p.A | p.B) & 15) == 0;
     if (tiled) {
-        constexpr int BM = 128, BN = 128, BK = 32;
-        const uint64_t tiles = (uint64_t)((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
+        const uint32_t tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+        const uint64_t tiles = (uint64_t)tiles_m * tiles_n;
         if (tiles > 0x7fffffffull) return GD_ESHAPE;
-#define K_GEMM_NK(V) k_gemm_nk<V, BM, BN, BK, 2, 2>
+        const bool edge = (p.M % BM) || (p.N % BN) || (p.K % BK) || (p.C & 15);
+        const dim3 grid((uint32_t)tiles), block(256);
+#define GD_GEMM_CASE(VAR)                                                                                         \
+    case VAR:                                                                                                     \
+        if (edge) hipLaunchKernelGGL((k_gemm_nk256<VAR, true>), grid, block, 0, stream, p, f, tiles_m, tiles_n);  \
+        else hipLaunchKernelGGL((k_gemm_nk256<VAR, false>), grid, block, 0, stream, p, f, tiles_m, tiles_n);      \
+        break;
         switch (variant) {
-        case V_NONE:  hipLaunchKernelGGL((K_GEMM_NK(V_NONE)), dim3((uint32_t)tiles), dim3(256), 0, stream, p, f); break;
-        case V_BIT32: hipLaunchKernelGGL((K_GEMM_NK(V_BIT32)), dim3((uint32_t)tiles), dim3(256), 0, stream, p, f); break;
-        case V_BIT64: hipLaunchKernelGGL((K_GEMM_NK(V_BIT64)), dim3((uint32_t)tiles), dim3(256), 0, stream, p, f); break;
+            GD_GEMM_CASE(V_NONE)
+            GD_GEMM_CASE(V_BIT32)
+            GD_GEMM_CASE(V_BIT64)
         default: return GD_ENOKERNEL;
         }
-#undef K_GEMM_NK
+#undef GD_GEMM_CASE
     } else {
         const uint64_t total = (uint64_t)p.M * p.N;
         uint64_t blocks = (total + 255) / 256;
