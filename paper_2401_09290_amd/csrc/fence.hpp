@@ -80,6 +80,20 @@ struct Fence {
         }
     }
 
+    // Fenced global -> LDS copy of 16 bytes per lane (global_load_lds_dwordx4): the
+    // global side takes the fenced address, the LDS side (wave-uniform base; lane i
+    // lands at base + 16*i) is not tenant-addressable.
+    __device__ __forceinline__ void ld_to_lds16(uint64_t raw, __attribute__((address_space(3))) void *lds_base) const
+    {
+        if constexpr (V == V_BIT32) {
+            const uint32_t m = (uint32_t)mask & ~15u;
+            const uint32_t off = (uint32_t)raw & m;
+            __builtin_amdgcn_global_load_lds((const GD_GLOBAL void *)((const GD_GLOBAL char *)base + off), lds_base, 16, 0, 0);
+        } else {
+            __builtin_amdgcn_global_load_lds((const GD_GLOBAL void *)address<16>(raw), lds_base, 16, 0, 0);
+        }
+    }
+
     template <typename T>
     __device__ __forceinline__ void st(uint64_t raw, T v) const
     {

@@ -5,16 +5,21 @@
 // Tiles of A and B are staged through LDS; every global tile load and every
 // store of C carries the fence on its final address.  LDS is not fenced.
 //
-// Tiled kernel: one workgroup of 4 wavefronts (2 x 2) computes a 256 x 256 tile
+// Tiled kernels: one workgroup of 4 wavefronts (2 x 2) computes a 256 x 256 tile
 // of C; each wavefront owns 128 x 128 of it as 4 x 4 MFMA tiles (256 fp32
 // accumulators per lane, one wavefront per SIMD).  K advances in steps of 64
-// through two LDS stages of 64 KiB (A 256x64 + B 256x64 bf16 each): while the
-// MFMAs of step t read stage t&1, the tile of step t+1 (already in registers) is
-// written to the other stage and the tile of step t+2 is fetched from global
-// memory, so one barrier per step suffices.  LDS rows are 128 bytes; the eight
-// 16-byte granules of a row are XOR-swizzled with the row number so that the
-// 32 rows a fragment load touches fall into different banks.  The finished tile
-// is converted to bf16, transposed through LDS and stored as 16-byte runs.
+// through two LDS stages of 64 KiB (A 256x64 + B 256x64 bf16 each).  LDS rows
+// are 128 bytes; the eight 16-byte granules of a row are XOR-swizzled with the
+// row number so that the 32 rows a fragment load touches fall into different
+// banks.  The finished tile is converted to bf16, transposed through LDS and
+// stored as 16-byte runs.
+//   k_gemm_dma   (shapes that are multiples of the tile) moves tiles global -> LDS
+//                with global_load_lds_dwordx4: no staging registers, no LDS store
+//                instructions; each lane picks the global granule that belongs in
+//                the LDS slot the hardware assigns to it, which is how the swizzle
+//                is applied.  Fragment loads run one k-substep ahead of the MFMAs.
+//   k_gemm_nk256 (ragged shapes) stages through registers so that out-of-range
+//                rows and the K tail can be zero-filled.
 #include "launchers.hpp"
 
 namespace gd {
@@ -199,6 +204,143 @@ void k_gemm_nk256(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles
     }
 }
 
+
+// ---- tiled MFMA kernel, global -> LDS direct ---------------------------------------------
+// Requirements (checked by the launcher): B stored N x K; M % 256 == 0, N % 256 == 0,
+// K % 64 == 0; A, B, C 16-byte aligned.
+#define GD_LDS __attribute__((address_space(3)))
+
+template <int V>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void k_gemm_dma(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_n)
+{
+    const Fence<V> F(fa);
+    __shared__ __attribute__((aligned(1024))) uint8_t stage0[STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) uint8_t stage1[STAGE_BYTES];
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = tid & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t wm = wave >> 1, wn = wave & 1;
+
+    uint32_t lin = blockIdx.x;
+    const uint32_t nblk = gridDim.x;
+    if ((nblk & 7) == 0) lin = (lin & 7) * (nblk >> 3) + (lin >> 3);
+    const uint32_t width = GROUP_M * tiles_n;
+    const uint32_t first_m = (lin / width) * GROUP_M;
+    const uint32_t gsize = (tiles_m - first_m < GROUP_M) ? tiles_m - first_m : GROUP_M;
+    const uint32_t m0 = (first_m + (lin % width) % gsize) * BM;
+    const uint32_t n0 = ((lin % width) / gsize) * BN;
+
+    // One DMA instruction fills 1 KiB of LDS = 8 tile rows; lane l lands in row l/8,
+    // slot l%8, so it fetches granule (l%8) ^ (l/8) of that row.  Wavefront w moves
+    // rows [64w, 64w+64) of the A tile and of the B tile: 8 + 8 instructions.
+    const uint32_t drow = wave * 64 + (lane >> 3);
+    const uint32_t dgran = (lane & 7) ^ (lane >> 3);
+    const uint64_t a_lane = p.A + 2 * ((uint64_t)(m0 + drow) * p.K + dgran * 8);
+    const uint64_t b_lane = p.B + 2 * ((uint64_t)(n0 + drow) * p.K + dgran * 8);
+    const uint64_t chunk_step = 2 * 8 * (uint64_t)p.K;      // 8 rows further down
+    auto dma_tile = [&](uint8_t *stage, uint32_t k0) {
+        GD_LDS uint8_t *dst = (GD_LDS uint8_t *)stage + wave * (64 * 128);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            F.ld_to_lds16(a_lane + c * chunk_step + 2 * (uint64_t)k0, dst + c * 1024);
+            F.ld_to_lds16(b_lane + c * chunk_step + 2 * (uint64_t)k0, dst + A_BYTES + c * 1024);
+        }
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    const uint32_t frow = lane & 31, fhalf = lane >> 5;
+    const uint32_t a_frag = (wm * 128 + frow) * 128;
+    const uint32_t b_frag = A_BYTES + (wn * 128 + frow) * 128;
+    uint32_t gsw[BK / 16];
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) gsw[kk] = ((2 * kk + fhalf) ^ (frow & 7)) << 4;
+
+    bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+    auto frags = [&](const uint8_t *stage, int kk, bf16x8 (&fa_)[TM], bf16x8 (&fb_)[TN]) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            fa_[i] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(stage + a_frag + i * 32 * 128 + gsw[kk]));
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            fb_[j] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(stage + b_frag + j * 32 * 128 + gsw[kk]));
+    };
+    auto mfmas = [&](const bf16x8 (&fa_)[TM], const bf16x8 (&fb_)[TN]) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa_[i], fb_[j], acc[i][j], 0, 0, 0);
+    };
+    // One K step: MFMAs on `cur` (its substep-0 fragments are already in fa0/fb0),
+    // tile at k_next streams into `nxt` meanwhile; leaves substep 0 of `nxt` in fa0/fb0.
+    auto step = [&](uint8_t *cur, uint8_t *nxt, uint32_t k_next) {
+        dma_tile(nxt, k_next);
+        frags(cur, 1, fa1, fb1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(fa0, fb0);
+        __builtin_amdgcn_sched_barrier(0);
+        frags(cur, 2, fa0, fb0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(fa1, fb1);
+        __builtin_amdgcn_sched_barrier(0);
+        frags(cur, 3, fa1, fb1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(fa0, fb0);
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();                // waits for this wavefront's DMA too: `nxt` is complete, `cur` is free
+        __builtin_amdgcn_sched_barrier(0);
+        frags(nxt, 0, fa0, fb0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(fa1, fb1);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    const uint32_t ksteps = p.K / BK;
+    const uint32_t k_last = p.K - BK;
+    dma_tile(stage0, 0);
+    __syncthreads();
+    frags(stage0, 0, fa0, fb0);
+    uint32_t t = 0;
+    for (; t + 1 < ksteps; t += 2) {
+        uint32_t k1 = (t + 1) * BK, k2 = (t + 2) * BK;
+        step(stage0, stage1, k1);
+        step(stage1, stage0, k2 < k_last ? k2 : k_last);   // past the end: refetch the last tile, unused
+    }
+    if (t < ksteps) step(stage0, stage1, k_last);
+    __syncthreads();
+
+    // Epilogue: see k_gemm_nk256.  Wavefronts 0,1 park in stage0, 2,3 in stage1.
+    uint8_t *park = (wave < 2 ? stage0 : stage1) + (wave & 1) * (128 * 256);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const uint32_t row = 32 * i + 8 * (r / 4) + 4 * fhalf + (r & 3);
+                const uint32_t col = 32 * j + frow;
+                *(uint16_t *)(park + row * 256 + col * 2) = (uint16_t)gemm_f32_to_bf16(acc[i][j][r]);
+            }
+    __syncthreads();
+    const uint32_t orow = lane >> 4, og = lane & 15;
+#pragma unroll 4
+    for (int it = 0; it < 32; ++it) {
+        const uint32_t row = orow + 4 * it;
+        const uint32_t m = m0 + wm * 128 + row, n = n0 + wn * 128 + og * 8;
+        const u32x4 v = *(const u32x4 *)(park + row * 256 + og * 16);
+        F.template st<u32x4>(p.C + 2 * ((uint64_t)m * p.N + n), v);
+    }
+}
+
 // ---- launcher ---------------------------------------------------------------------------
 
 int launch_gemm_bf16(const void *args, const FenceArgs &f, int variant, const Shape &shape,
@@ -217,7 +359,7 @@ int launch_gemm_bf16(const void *args, const FenceArgs &f, int variant, const Sh
 #define GD_GEMM_CASE(VAR)                                                                                         \
     case VAR:                                                                                                     \
         if (edge) hipLaunchKernelGGL((k_gemm_nk256<VAR, true>), grid, block, 0, stream, p, f, tiles_m, tiles_n);  \
-        else hipLaunchKernelGGL((k_gemm_nk256<VAR, false>), grid, block, 0, stream, p, f, tiles_m, tiles_n);      \
+        else hipLaunchKernelGGL((k_gemm_dma<VAR>), grid, block, 0, stream, p, f, tiles_m, tiles_n);               \
         break;
         switch (variant) {
             GD_GEMM_CASE(V_NONE)

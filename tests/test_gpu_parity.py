@@ -411,7 +411,8 @@ def test_rmsnorm_against_oracle(rows, cols, shift):
 # GEMM
 # ---------------------------------------------------------------------------
 
-@pytest.mark.parametrize("M,N,K,b_is_nk", [(128, 128, 64, 1), (256, 384, 512, 1), (200, 136, 96, 1), (37, 300, 72, 1),
+@pytest.mark.parametrize("M,N,K,b_is_nk", [(256, 256, 64, 1), (512, 256, 192, 1), (256, 768, 128, 1), (512, 512, 1024, 1),
+                                           (128, 128, 64, 1), (256, 384, 512, 1), (200, 136, 96, 1), (37, 300, 72, 1),
                                            (129, 1, 8, 1), (64, 64, 20, 1), (50, 70, 33, 0), (128, 96, 64, 0),
                                            (16, 16, 0, 1)])
 def test_gemm_against_oracle(M, N, K, b_is_nk):
