@@ -9,9 +9,9 @@
 // of C; each wavefront owns 128 x 128 of it as 4 x 4 MFMA tiles (256 fp32
 // accumulators per lane, one wavefront per SIMD).  K advances in steps of 64
 // through two LDS stages of 64 KiB (A 256x64 + B 256x64 bf16 each).  LDS rows
-// are 128 bytes; the eight 16-byte granules of a row are XOR-swizzled with the
-// row number so that the 32 rows a fragment load touches fall into different
-// banks.  The finished tile is converted to bf16, transposed through LDS and
+// are 128 bytes; the eight 16-byte granules of a row are XOR-swizzled with half
+// the row number, so that 16 consecutive rows of one granule column (what a
+// fragment load touches per pass) spread over all 64 banks.  The finished tile is converted to bf16, transposed through LDS and
 // stored as 16-byte runs.
 //   k_gemm_dma   (shapes that are multiples of the tile) moves tiles global -> LDS
 //                with global_load_lds_dwordx4: no staging registers, no LDS store
@@ -94,7 +94,7 @@ void k_gemm_nk256(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles
     const uint64_t a_ptr = p.A + 2 * ((uint64_t)(m0 + lrow) * p.K + lg * 8);
     const uint64_t b_ptr = p.B + 2 * ((uint64_t)(n0 + lrow) * p.K + lg * 8);
     const uint64_t row_step = 2 * 32 * (uint64_t)p.K;
-    const uint32_t lds_w = lrow * 128 + ((lg ^ (lrow & 7)) << 4);
+    const uint32_t lds_w = lrow * 128 + ((lg ^ ((lrow >> 1) & 7)) << 4);
 
     u32x4 ra[LOADS], rb[LOADS];
     auto gload = [&](uint32_t k0) {
@@ -129,13 +129,13 @@ void k_gemm_nk256(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    // fragment addresses: lane = (row l%32, k half l/32); granule (2*kk + half) ^ (row & 7)
+    // fragment addresses: lane = (row l%32, k half l/32); granule (2*kk + half) ^ ((row/2) & 7)
     const uint32_t frow = lane & 31, fhalf = lane >> 5;
     const uint32_t a_frag = (wm * 128 + frow) * 128;
     const uint32_t b_frag = A_BYTES + (wn * 128 + frow) * 128;
     uint32_t gsw[BK / 16];
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) gsw[kk] = ((2 * kk + fhalf) ^ (frow & 7)) << 4;
+    for (int kk = 0; kk < BK / 16; ++kk) gsw[kk] = ((2 * kk + fhalf) ^ ((frow >> 1) & 7)) << 4;
 
     const uint32_t ksteps = (p.K + BK - 1) / BK;
     gload(0);
@@ -233,19 +233,24 @@ void k_gemm_dma(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_n
     const uint32_t n0 = ((lin % width) / gsize) * BN;
 
     // One DMA instruction fills 1 KiB of LDS = 8 tile rows; lane l lands in row l/8,
-    // slot l%8, so it fetches granule (l%8) ^ (l/8) of that row.  Wavefront w moves
-    // rows [64w, 64w+64) of the A tile and of the B tile: 8 + 8 instructions.
+    // slot l%8 of chunk c, so it fetches granule (l%8) ^ ((row/2) & 7) of that row,
+    // row = 8c + l/8: the key is (4c + l/16) & 7, one value for even c, one for odd c.
+    // Wavefront w moves rows [64w, 64w+64) of the A tile and of the B tile: 8 + 8
+    // instructions.
     const uint32_t drow = wave * 64 + (lane >> 3);
-    const uint32_t dgran = (lane & 7) ^ (lane >> 3);
-    const uint64_t a_lane = p.A + 2 * ((uint64_t)(m0 + drow) * p.K + dgran * 8);
-    const uint64_t b_lane = p.B + 2 * ((uint64_t)(n0 + drow) * p.K + dgran * 8);
+    const uint32_t dgran[2] = {(lane & 7) ^ (lane >> 4), (lane & 7) ^ (4 + (lane >> 4))};
+    const uint64_t a_row = p.A + 2 * (uint64_t)(m0 + drow) * p.K;
+    const uint64_t b_row = p.B + 2 * (uint64_t)(n0 + drow) * p.K;
+    const uint64_t a_lane[2] = {a_row + 16 * dgran[0], a_row + 16 * dgran[1]};
+    const uint64_t b_lane[2] = {b_row + 16 * dgran[0], b_row + 16 * dgran[1]};
     const uint64_t chunk_step = 2 * 8 * (uint64_t)p.K;      // 8 rows further down
     auto dma_tile = [&](uint8_t *stage, uint32_t k0) {
         GD_LDS uint8_t *dst = (GD_LDS uint8_t *)stage + wave * (64 * 128);
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
-            F.ld_to_lds16(a_lane + c * chunk_step + 2 * (uint64_t)k0, dst + c * 1024);
-            F.ld_to_lds16(b_lane + c * chunk_step + 2 * (uint64_t)k0, dst + A_BYTES + c * 1024);
+            const uint64_t uni = c * chunk_step + 2 * (uint64_t)k0;          // wave-uniform part
+            F.ld_to_lds16(a_lane[c & 1], uni, dst + c * 1024);
+            F.ld_to_lds16(b_lane[c & 1], uni, dst + A_BYTES + c * 1024);
         }
     };
 
@@ -262,7 +267,7 @@ void k_gemm_dma(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_n
     const uint32_t b_frag = A_BYTES + (wn * 128 + frow) * 128;
     uint32_t gsw[BK / 16];
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) gsw[kk] = ((2 * kk + fhalf) ^ (frow & 7)) << 4;
+    for (int kk = 0; kk < BK / 16; ++kk) gsw[kk] = ((2 * kk + fhalf) ^ ((frow >> 1) & 7)) << 4;
 
     bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
     auto frags = [&](const uint8_t *stage, int kk, bf16x8 (&fa_)[TM], bf16x8 (&fb_)[TN]) {
@@ -282,25 +287,47 @@ void k_gemm_dma(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_n
     };
     // One K step: MFMAs on `cur` (its substep-0 fragments are already in fa0/fb0),
     // tile at k_next streams into `nxt` meanwhile; leaves substep 0 of `nxt` in fa0/fb0.
+    // Issue order inside a region: one MFMA, then one fragment load (or two DMA
+    // loads), and so on, so that the matrix pipe never waits for the other units.
+    auto interleave_ds = [&]() {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // 1 MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    // 1 DS read
+        }
+    };
     auto step = [&](uint8_t *cur, uint8_t *nxt, uint32_t k_next) {
-        dma_tile(nxt, k_next);
-        frags(cur, 1, fa1, fb1);
         __builtin_amdgcn_sched_barrier(0);
-        mfmas(fa0, fb0);
-        __builtin_amdgcn_sched_barrier(0);
+        {   // substep 0, written out: per pair of MFMAs one fragment load and two DMA loads
+            GD_LDS uint8_t *dst = (GD_LDS uint8_t *)nxt + wave * (64 * 128);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                if (q < TM)
+                    fa1[q] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(cur + a_frag + q * 32 * 128 + gsw[1]));
+                else
+                    fb1[q - TM] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(cur + b_frag + (q - TM) * 32 * 128 + gsw[1]));
+                const uint64_t uni = q * chunk_step + 2 * (uint64_t)k_next;   // wave-uniform part
+                F.ld_to_lds16(a_lane[q & 1], uni, dst + q * 1024);
+                F.ld_to_lds16(b_lane[q & 1], uni, dst + A_BYTES + q * 1024);
+#pragma unroll
+                for (int e = 2 * q; e < 2 * q + 2; ++e)
+                    acc[e / TN][e % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[e / TN], fb0[e % TN], acc[e / TN][e % TN], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
         frags(cur, 2, fa0, fb0);
-        __builtin_amdgcn_sched_barrier(0);
         mfmas(fa1, fb1);
+        interleave_ds();
         __builtin_amdgcn_sched_barrier(0);
         frags(cur, 3, fa1, fb1);
-        __builtin_amdgcn_sched_barrier(0);
         mfmas(fa0, fb0);
+        interleave_ds();
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();                // waits for this wavefront's DMA too: `nxt` is complete, `cur` is free
         __builtin_amdgcn_sched_barrier(0);
         frags(nxt, 0, fa0, fb0);
-        __builtin_amdgcn_sched_barrier(0);
         mfmas(fa1, fb1);
+        interleave_ds();
         __builtin_amdgcn_sched_barrier(0);
     };
 
