@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--configs", default="c3,c4,c2,c1,c5", help="comma list out of c1..c5 (c3 is the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--prewarm-ms", type=float, default=250.0,
+                    help="untimed launches in front of every measurement until this much GPU time has passed "
+                         "(the shader clock needs tens of milliseconds of load to settle)")
     return ap.parse_args()
 
 
@@ -79,10 +82,23 @@ class DevPool:
         self.torch.cuda.empty_cache()
 
 
+PREWARM_MS = 250.0
+
+
+def prewarm(torch, launch):
+    """Untimed launches until PREWARM_MS of wall time have passed under load."""
+    t0 = time.perf_counter()
+    while (time.perf_counter() - t0) * 1e3 < PREWARM_MS:
+        for _ in range(4):
+            launch()
+        torch.cuda.synchronize()
+
+
 def timed_rounds(torch, streams, launch_round, steps, warmup):
     """launch_round(i) enqueues one round on every stream.  Returns seconds for
     `steps` rounds: all streams are released by one event, the clock stops at the
     last stream's end event; bracketed by synchronize on both sides."""
+    prewarm(torch, launch_round)
     for _ in range(warmup):
         launch_round()
     torch.cuda.synchronize()
@@ -105,6 +121,7 @@ def timed_rounds(torch, streams, launch_round, steps, warmup):
 def solo_avg_seconds(torch, stream, launch, reps, warmup=2):
     """Average duration of one launch, back to back on one stream, by HIP events
     recorded on that stream."""
+    prewarm(torch, launch)
     for _ in range(warmup):
         launch()
     torch.cuda.synchronize()
@@ -440,7 +457,9 @@ def read_traffic():
 
 
 def main():
+    global PREWARM_MS
     args = parse()
+    PREWARM_MS = args.prewarm_ms
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (tenants are streams of one context); "
               f"--gpus {args.gpus} is not supported", file=sys.stderr)

@@ -33,6 +33,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace gd {
 
 enum Variant : int { V_NONE = 0, V_BIT32 = 1, V_BIT64 = 2, V_COUNT = 3 };
@@ -88,6 +90,31 @@ struct Fence {
         } else {
             return *(const GD_GLOBAL T *)address<sizeof(T)>(raw);
         }
+    }
+
+    // A fenced address kept for a later access: the 32-bit offset inside the
+    // partition for V_BIT32, the full address otherwise.  Lets a kernel run the
+    // fence arithmetic a few instructions ahead of the access it belongs to.
+    using Handle = typename std::conditional<V == V_BIT32, uint32_t, uint64_t>::type;
+
+    template <int W>
+    __device__ __forceinline__ Handle fenced(uint64_t lane_part, uint64_t uniform_part) const
+    {
+        if constexpr (V == V_BIT32) {
+            const uint32_t m = (uint32_t)mask & ~(uint32_t)(W - 1);
+            return fence_and32((uint32_t)lane_part + (uint32_t)uniform_part, m);
+        } else {
+            return address<W>(lane_part + uniform_part);
+        }
+    }
+
+    // global -> LDS copy of 16 bytes per lane from an address fenced<16>() produced.
+    __device__ __forceinline__ void dma16(Handle h, __attribute__((address_space(3))) void *lds_base) const
+    {
+        if constexpr (V == V_BIT32)
+            __builtin_amdgcn_global_load_lds((const GD_GLOBAL void *)((const GD_GLOBAL char *)base + h), lds_base, 16, 0, 0);
+        else
+            __builtin_amdgcn_global_load_lds((const GD_GLOBAL void *)h, lds_base, 16, 0, 0);
     }
 
     // Fenced global -> LDS copy of 16 bytes per lane (global_load_lds_dwordx4): the

@@ -368,6 +368,182 @@ void k_gemm_dma(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_n
     }
 }
 
+
+// ---- tiled MFMA kernel, four-stage ring of K=32 slices ---------------------------------------
+// Same 256 x 256 tile and wavefront layout as k_gemm_dma, but K advances in
+// slices of 32 through a ring of four 32 KiB LDS stages (A 256x32 + B 256x32):
+// the slice of step t+3 is requested while step t computes, so a DMA has three
+// steps to land and about 64 KiB per CU stay in flight all the time.  LDS rows
+// are 64 bytes; granule g of row r sits in slot g ^ ((r/4) & 3), which spreads 16
+// consecutive rows of one granule column over all 64 banks.
+// Requirements: as k_gemm_dma, and K % 128 == 0.
+constexpr int RK = 32;                       // K per ring step
+constexpr int RSTAGE = (BM + BN) * RK * 2;   // 32 KiB
+constexpr int RA = BM * RK * 2;              // 16 KiB: offset of the B slice inside a stage
+
+// Workgroup barrier of the ring: wait until at most 16 of this wavefront's DMA
+// loads are still in flight (they complete in order, so everything older has
+// landed in LDS) and all its LDS reads have returned, then meet the other
+// wavefronts.  s_waitcnt immediate: vmcnt = 16, lgkmcnt = 0, expcnt untouched
+// (gfx9 encoding).  The empty asm statements keep the compiler from moving LDS
+// accesses across the barrier.
+#define GD_RING_BARRIER()                       \
+    do {                                        \
+        __builtin_amdgcn_s_waitcnt(0x4070);     \
+        asm volatile("" ::: "memory");          \
+        __builtin_amdgcn_s_barrier();           \
+        asm volatile("" ::: "memory");          \
+    } while (0)
+
+template <int V>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_n)
+{
+    const Fence<V> F(fa);
+    __shared__ __attribute__((aligned(1024))) uint8_t ring0[RSTAGE];
+    __shared__ __attribute__((aligned(1024))) uint8_t ring1[RSTAGE];
+    __shared__ __attribute__((aligned(1024))) uint8_t ring2[RSTAGE];
+    __shared__ __attribute__((aligned(1024))) uint8_t ring3[RSTAGE];
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = tid & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t wm = wave >> 1, wn = wave & 1;
+
+    uint32_t lin = blockIdx.x;
+    const uint32_t nblk = gridDim.x;
+    if ((nblk & 7) == 0) lin = (lin & 7) * (nblk >> 3) + (lin >> 3);
+    const uint32_t width = GROUP_M * tiles_n;
+    const uint32_t first_m = (lin / width) * GROUP_M;
+    const uint32_t gsize = (tiles_m - first_m < GROUP_M) ? tiles_m - first_m : GROUP_M;
+    const uint32_t m0 = (first_m + (lin % width) % gsize) * BM;
+    const uint32_t n0 = ((lin % width) / gsize) * BN;
+
+    // One DMA instruction fills 1 KiB = 16 slice rows; lane l lands in row l/4, slot
+    // l%4, and fetches granule (l%4) ^ ((row/4) & 3) = (l%4) ^ ((l/16) & 3).  Wavefront
+    // w moves rows [64w, 64w+64) of A and of B: 4 + 4 instructions per step.
+    const uint32_t drow = wave * 64 + (lane >> 2);
+    const uint32_t dgran = (lane & 3) ^ ((lane >> 4) & 3);
+    const uint64_t a_lane = p.A + 2 * ((uint64_t)(m0 + drow) * p.K + dgran * 8);
+    const uint64_t b_lane = p.B + 2 * ((uint64_t)(n0 + drow) * p.K + dgran * 8);
+    const uint64_t chunk_step = 2 * 16 * (uint64_t)p.K;      // 16 rows further down
+    typename Fence<V>::Handle pre[8];                      // fenced addresses of the next step's 8 DMAs
+    auto pre_one = [&](uint32_t k0, int c) {
+        const uint64_t uni = (c & 3) * chunk_step + 2 * (uint64_t)k0;
+        pre[c] = F.template fenced<16>(c < 4 ? a_lane : b_lane, uni);
+    };
+    auto dma_one = [&](uint8_t *stage, int c) {
+        GD_LDS uint8_t *dst = (GD_LDS uint8_t *)stage + wave * 4096 + (c & 3) * 1024 + (c < 4 ? 0 : RA);
+        F.dma16(pre[c], dst);
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    const uint32_t frow = lane & 31, fhalf = lane >> 5;
+    const uint32_t a_frag = (wm * 128 + frow) * 64;
+    const uint32_t b_frag = RA + (wn * 128 + frow) * 64;
+    uint32_t gsw[2];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) gsw[kk] = ((2 * kk + fhalf) ^ ((frow >> 2) & 3)) << 4;
+
+    bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+    auto frag_one = [&](const uint8_t *stage, int kk, int q, bf16x8 (&fa_)[TM], bf16x8 (&fb_)[TN]) {
+        if (q < TM)
+            fa_[q] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(stage + a_frag + q * 32 * 64 + gsw[kk]));
+        else
+            fb_[q - TM] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(stage + b_frag + (q - TM) * 32 * 64 + gsw[kk]));
+    };
+    auto mfma_pair = [&](int q, const bf16x8 (&fa_)[TM], const bf16x8 (&fb_)[TN]) {
+#pragma unroll
+        for (int e = 2 * q; e < 2 * q + 2; ++e)
+            acc[e / TN][e % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa_[e / TN], fb_[e % TN], acc[e / TN][e % TN], 0, 0, 0);
+    };
+    // One ring step.  In: substep-0 fragments of `cur` in fa0/fb0.  Out: substep-0
+    // fragments of `nxt` in fa0/fb0.  `refill` is the stage read one step ago.
+    // `k_after` is the slice the FOLLOWING step will request: its fenced addresses are
+    // computed here, in the shadow of MFMAs, so the DMA issue never waits for them.
+    auto step = [&](const uint8_t *cur, const uint8_t *nxt, uint8_t *refill, uint32_t k_after) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {                    // substep 0
+            frag_one(cur, 1, q, fa1, fb1);
+            dma_one(refill, q);
+            mfma_pair(q, fa0, fb0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {                    // substep 1, first half
+            pre_one(k_after, 2 * q);
+            pre_one(k_after, 2 * q + 1);
+            mfma_pair(q, fa1, fb1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        GD_RING_BARRIER();                               // 16 DMAs may stay in flight: `nxt` is older
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int q = 4; q < 8; ++q) {                    // substep 1, second half
+            if (q < 6) {
+#pragma unroll
+                for (int f = 0; f < 4; ++f) frag_one(nxt, 0, 4 * (q - 4) + f, fa0, fb0);
+            }
+            mfma_pair(q, fa1, fb1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    const uint32_t ksteps = p.K / RK;                    // multiple of 4
+    const uint32_t k_last = p.K - RK;
+    auto clamp_k = [&](uint32_t k) { return k < k_last ? k : k_last; };   // past the end: refetch the last slice, unused
+#pragma unroll
+    for (int s3 = 0; s3 < 3; ++s3) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            pre_one(s3 * RK, c);
+            dma_one(s3 == 0 ? ring0 : s3 == 1 ? ring1 : ring2, c);
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < 8; ++c) pre_one(clamp_k(3 * RK), c);
+    GD_RING_BARRIER();
+#pragma unroll
+    for (int q = 0; q < 8; ++q) frag_one(ring0, 0, q, fa0, fb0);
+    for (uint32_t t = 0; t < ksteps; t += 4) {
+        const uint32_t k4 = (t + 4) * RK;
+        step(ring0, ring1, ring3, clamp_k(k4));
+        step(ring1, ring2, ring0, clamp_k(k4 + RK));
+        step(ring2, ring3, ring1, clamp_k(k4 + 2 * RK));
+        step(ring3, ring0, ring2, clamp_k(k4 + 3 * RK));
+    }
+    __syncthreads();                                     // every DMA has landed, every fragment is read
+
+    // Epilogue: see k_gemm_nk256.  Wavefront w parks its 128 x 128 bf16 block in ring stage w.
+    uint8_t *park = wave == 0 ? ring0 : wave == 1 ? ring1 : wave == 2 ? ring2 : ring3;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const uint32_t row = 32 * i + 8 * (r / 4) + 4 * fhalf + (r & 3);
+                const uint32_t col = 32 * j + frow;
+                *(uint16_t *)(park + row * 256 + col * 2) = (uint16_t)gemm_f32_to_bf16(acc[i][j][r]);
+            }
+    __syncthreads();
+    const uint32_t orow = lane >> 4, og = lane & 15;
+#pragma unroll 4
+    for (int it = 0; it < 32; ++it) {
+        const uint32_t row = orow + 4 * it;
+        const uint32_t m = m0 + wm * 128 + row, n = n0 + wn * 128 + og * 8;
+        const u32x4 v = *(const u32x4 *)(park + row * 256 + og * 16);
+        F.template st<u32x4>(p.C + 2 * ((uint64_t)m * p.N + n), v);
+    }
+}
+
 // ---- launcher ---------------------------------------------------------------------------
 
 int launch_gemm_bf16(const void *args, const FenceArgs &f, int variant, const Shape &shape,
@@ -386,6 +562,7 @@ int launch_gemm_bf16(const void *args, const FenceArgs &f, int variant, const Sh
 #define GD_GEMM_CASE(VAR)                                                                                         \
     case VAR:                                                                                                     \
         if (edge) hipLaunchKernelGGL((k_gemm_nk256<VAR, true>), grid, block, 0, stream, p, f, tiles_m, tiles_n);  \
+        else if (p.K % 128 == 0) hipLaunchKernelGGL((k_gemm_ring<VAR>), grid, block, 0, stream, p, f, tiles_m, tiles_n); \
         else hipLaunchKernelGGL((k_gemm_dma<VAR>), grid, block, 0, stream, p, f, tiles_m, tiles_n);               \
         break;
         switch (variant) {
