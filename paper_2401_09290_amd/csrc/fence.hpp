@@ -80,16 +80,21 @@ struct Fence {
         }
     }
 
-    template <typename T>
+    // STREAM = true marks data that is touched once (contiguous streams): the access
+    // carries the nontemporal hint so that it does not displace reusable lines.
+    template <typename T, bool STREAM = false>
     __device__ __forceinline__ T ld(uint64_t raw) const
     {
+        const GD_GLOBAL T *ptr;
         if constexpr (V == V_BIT32) {
             const uint32_t m = (uint32_t)mask & ~(uint32_t)(sizeof(T) - 1);
             const uint32_t off = fence_and32((uint32_t)raw, m);
-            return *(const GD_GLOBAL T *)((const GD_GLOBAL char *)base + off);
+            ptr = (const GD_GLOBAL T *)((const GD_GLOBAL char *)base + off);
         } else {
-            return *(const GD_GLOBAL T *)address<sizeof(T)>(raw);
+            ptr = (const GD_GLOBAL T *)address<sizeof(T)>(raw);
         }
+        if constexpr (STREAM) return __builtin_nontemporal_load(ptr);
+        else return *ptr;
     }
 
     // A fenced address kept for a later access: the 32-bit offset inside the
@@ -135,16 +140,19 @@ struct Fence {
         }
     }
 
-    template <typename T>
+    template <typename T, bool STREAM = false>
     __device__ __forceinline__ void st(uint64_t raw, T v) const
     {
+        GD_GLOBAL T *ptr;
         if constexpr (V == V_BIT32) {
             const uint32_t m = (uint32_t)mask & ~(uint32_t)(sizeof(T) - 1);
             const uint32_t off = fence_and32((uint32_t)raw, m);
-            *(GD_GLOBAL T *)((GD_GLOBAL char *)base + off) = v;
+            ptr = (GD_GLOBAL T *)((GD_GLOBAL char *)base + off);
         } else {
-            *(GD_GLOBAL T *)address<sizeof(T)>(raw) = v;
+            ptr = (GD_GLOBAL T *)address<sizeof(T)>(raw);
         }
+        if constexpr (STREAM) __builtin_nontemporal_store(v, ptr);
+        else *ptr = v;
     }
 };
 

@@ -26,7 +26,7 @@ __global__ __launch_bounds__(1024) void k_saxpy_idx(gd_args_saxpy_idx p, FenceAr
     if ((p.off & 15) == 0) {
         const uint64_t n4 = p.n >> 2;
         for (uint64_t q = tid; q < n4; q += stride) {
-            const i32x4 o = F.template ld<i32x4>(p.off + 16 * q);
+            const i32x4 o = F.template ld<i32x4, true>(p.off + 16 * q);
             float vx[EPT], vy[EPT];
 #pragma unroll
             for (int e = 0; e < EPT; ++e) {
@@ -63,18 +63,18 @@ __global__ __launch_bounds__(1024) void k_gather32(gd_args_gather p, FenceArgs f
         for (uint64_t q = tid; q < n4; q += stride) {
             uint64_t k[EPT];
             if (IDX64) {
-                const u64x2 k01 = F.template ld<u64x2>(p.idx + 32 * q);
-                const u64x2 k23 = F.template ld<u64x2>(p.idx + 32 * q + 16);
+                const u64x2 k01 = F.template ld<u64x2, true>(p.idx + 32 * q);
+                const u64x2 k23 = F.template ld<u64x2, true>(p.idx + 32 * q + 16);
                 k[0] = k01[0]; k[1] = k01[1]; k[2] = k23[0]; k[3] = k23[1];
             } else {
-                const i32x4 k4 = F.template ld<i32x4>(p.idx + 16 * q);
+                const i32x4 k4 = F.template ld<i32x4, true>(p.idx + 16 * q);
 #pragma unroll
                 for (int e = 0; e < EPT; ++e) k[e] = (uint64_t)(int64_t)k4[e];
             }
             u32x4 v;
 #pragma unroll
             for (int e = 0; e < EPT; ++e) v[e] = F.template ld<uint32_t>(p.tab + 4 * k[e]);
-            F.template st<u32x4>(p.out + 16 * q, v);
+            F.template st<u32x4, true>(p.out + 16 * q, v);
         }
         done = 4 * n4;
     }
@@ -96,9 +96,9 @@ __global__ __launch_bounds__(1024) void k_scatter_f32_i64(gd_args_scatter p, Fen
     if (((p.idx | p.src) & 15) == 0) {
         const uint64_t n4 = p.n >> 2;
         for (uint64_t q = tid; q < n4; q += stride) {
-            const u64x2 k01 = F.template ld<u64x2>(p.idx + 32 * q);
-            const u64x2 k23 = F.template ld<u64x2>(p.idx + 32 * q + 16);
-            const f32x4 v = F.template ld<f32x4>(p.src + 16 * q);
+            const u64x2 k01 = F.template ld<u64x2, true>(p.idx + 32 * q);
+            const u64x2 k23 = F.template ld<u64x2, true>(p.idx + 32 * q + 16);
+            const f32x4 v = F.template ld<f32x4>(p.src + 16 * q);   // measured: the hint on this stream slows the scattered stores
             F.template st<float>(p.dst + 4 * k01[0], p.scale * v[0]);
             F.template st<float>(p.dst + 4 * k01[1], p.scale * v[1]);
             F.template st<float>(p.dst + 4 * k23[0], p.scale * v[2]);

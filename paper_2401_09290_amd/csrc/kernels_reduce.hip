@@ -61,14 +61,14 @@ __global__ __launch_bounds__(WG) void k_sum_partial(gd_args_sum p, FenceArgs fa)
             if (t0 + tile <= n4) {
                 f32x4 v[SUM_UNROLL];
 #pragma unroll
-                for (int u = 0; u < SUM_UNROLL; ++u) v[u] = F.template ld<f32x4>(p.in + 16 * (i0 + (uint64_t)u * WG));
+                for (int u = 0; u < SUM_UNROLL; ++u) v[u] = F.template ld<f32x4, true>(p.in + 16 * (i0 + (uint64_t)u * WG));
 #pragma unroll
                 for (int u = 0; u < SUM_UNROLL; ++u) a4 += v[u];
             } else {
 #pragma unroll
                 for (int u = 0; u < SUM_UNROLL; ++u) {
                     const uint64_t i = i0 + (uint64_t)u * WG;
-                    if (i < n4) a4 += F.template ld<f32x4>(p.in + 16 * i);
+                    if (i < n4) a4 += F.template ld<f32x4, true>(p.in + 16 * i);
                 }
             }
         }

@@ -1,7 +1,8 @@
 // Contiguous element-wise kernels: Listing 1's sample store, the fence probe,
-// STREAM copy and STREAM triad.  HBM-bound: 16 bytes per lane per access, all
-// loads of a tile issued before its stores, one tile of UNROLL * blockDim.x
-// vectors per loop trip.  The fence (fence.hpp) is applied to the final address
+// STREAM copy and STREAM triad.  HBM-bound: 16 bytes per lane per access with
+// the nontemporal hint, all loads of a tile issued before its stores, one tile
+// of UNROLL * blockDim.x vectors per loop trip (measured best: one vector per
+// lane and a workgroup per 4 KiB tile).  The fence (fence.hpp) is applied to the final address
 // of every access; kernels are identical for every variant apart from it.
 #include "launchers.hpp"
 
@@ -10,7 +11,7 @@ namespace gd {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int UNROLL = 4;
+constexpr int UNROLL = 1;
 
 // ---- store_tid: A[i] = j (paper Listing 1 / Section 4.3) -----------------------
 template <int V>
@@ -62,22 +63,22 @@ __global__ __launch_bounds__(1024) void k_stream(uint64_t pa, uint64_t pb, uint6
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) {
                     const uint64_t i = i0 + (uint64_t)u * blockDim.x;
-                    vb[u] = F.template ld<f32x4>(pb + 16 * i);
-                    if (OP) vc[u] = F.template ld<f32x4>(pc + 16 * i);
+                    vb[u] = F.template ld<f32x4, true>(pb + 16 * i);
+                    if (OP) vc[u] = F.template ld<f32x4, true>(pc + 16 * i);
                 }
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) {
                     const uint64_t i = i0 + (uint64_t)u * blockDim.x;
-                    F.template st<f32x4>(pa + 16 * i, OP ? vb[u] + s * vc[u] : vb[u]);
+                    F.template st<f32x4, true>(pa + 16 * i, OP ? vb[u] + s * vc[u] : vb[u]);
                 }
             } else {
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) {
                     const uint64_t i = i0 + (uint64_t)u * blockDim.x;
                     if (i < n4) {
-                        vb[u] = F.template ld<f32x4>(pb + 16 * i);
-                        if (OP) vc[u] = F.template ld<f32x4>(pc + 16 * i);
-                        F.template st<f32x4>(pa + 16 * i, OP ? vb[u] + s * vc[u] : vb[u]);
+                        vb[u] = F.template ld<f32x4, true>(pb + 16 * i);
+                        if (OP) vc[u] = F.template ld<f32x4, true>(pc + 16 * i);
+                        F.template st<f32x4, true>(pa + 16 * i, OP ? vb[u] + s * vc[u] : vb[u]);
                     }
                 }
             }
