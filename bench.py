@@ -465,7 +465,7 @@ def cpu_baseline(si):
 
 def read_traffic():
     """HBM bytes per fenced triad launch from the committed rocprofv3 --pmc summary, if any."""
-    path = os.path.join(ROOT, "profiles", "k_stream_triad_c3_pmc.txt")
+    path = os.path.join(ROOT, "profiles", "pmc_fence_overhead_and_traffic.md")
     try:
         for ln in open(path):
             if ln.startswith("traffic_bytes_per_launch:"):
