@@ -27,6 +27,9 @@ namespace gd {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ uint32_t gemm_f32_to_bf16(float f)
 {
@@ -381,6 +384,10 @@ constexpr int RK = 32;                       // K per ring step
 constexpr int RSTAGE = (BM + BN) * RK * 2;   // 32 KiB
 constexpr int RA = BM * RK * 2;              // 16 KiB: offset of the B slice inside a stage
 
+// Fragment loads are issued in the order the MFMAs need them (0..3 = A fragments,
+// 4..7 = B fragments; MFMAs run A-fragment-major): B0 A0 B1 B2 B3 A1 A2 A3.
+__device__ constexpr int FRAG_ORDER[8] = {4, 0, 5, 6, 7, 1, 2, 3};
+
 // Workgroup barrier of the ring: wait until at most 16 of this wavefront's DMA
 // loads are still in flight (they complete in order, so everything older has
 // landed in LDS) and all its LDS reads have returned, then meet the other
@@ -462,7 +469,7 @@ void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_
     auto mfma_pair = [&](int q, const bf16x8 (&fa_)[TM], const bf16x8 (&fb_)[TN]) {
 #pragma unroll
         for (int e = 2 * q; e < 2 * q + 2; ++e)
-            acc[e / TN][e % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa_[e / TN], fb_[e % TN], acc[e / TN][e % TN], 0, 0, 0);
+            acc[e / TN][e % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb_[e % TN], fa_[e / TN], acc[e / TN][e % TN], 0, 0, 0);
     };
     // One ring step.  In: substep-0 fragments of `cur` in fa0/fb0.  Out: substep-0
     // fragments of `nxt` in fa0/fb0.  `refill` is the stage read one step ago.
@@ -471,7 +478,10 @@ void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_
     auto step = [&](const uint8_t *cur, const uint8_t *nxt, uint8_t *refill, uint32_t k_after) {
 #pragma unroll
         for (int q = 0; q < 8; ++q) {                    // substep 0
-            frag_one(cur, 1, q, fa1, fb1);
+            if (q < 4) {
+                frag_one(cur, 1, FRAG_ORDER[2 * q], fa1, fb1);
+                frag_one(cur, 1, FRAG_ORDER[2 * q + 1], fa1, fb1);
+            }
             dma_one(refill, q);
             mfma_pair(q, fa0, fb0);
             __builtin_amdgcn_sched_barrier(0);
@@ -489,7 +499,7 @@ void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_
         for (int q = 4; q < 8; ++q) {                    // substep 1, second half
             if (q < 6) {
 #pragma unroll
-                for (int f = 0; f < 4; ++f) frag_one(nxt, 0, 4 * (q - 4) + f, fa0, fb0);
+                for (int f = 0; f < 4; ++f) frag_one(nxt, 0, FRAG_ORDER[4 * (q - 4) + f], fa0, fb0);
             }
             mfma_pair(q, fa1, fb1);
             __builtin_amdgcn_sched_barrier(0);
@@ -511,7 +521,7 @@ void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_
     for (int c = 0; c < 8; ++c) pre_one(clamp_k(3 * RK), c);
     GD_RING_BARRIER();
 #pragma unroll
-    for (int q = 0; q < 8; ++q) frag_one(ring0, 0, q, fa0, fb0);
+    for (int q = 0; q < 8; ++q) frag_one(ring0, 0, FRAG_ORDER[q], fa0, fb0);
     for (uint32_t t = 0; t < ksteps; t += 4) {
         const uint32_t k4 = (t + 4) * RK;
         step(ring0, ring1, ring3, clamp_k(k4));
@@ -521,17 +531,28 @@ void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_
     }
     __syncthreads();                                     // every DMA has landed, every fragment is read
 
-    // Epilogue: see k_gemm_nk256.  Wavefront w parks its 128 x 128 bf16 block in ring stage w.
+    // Epilogue.  The MFMAs take the B fragment as their row operand, so acc[i][j][r]
+    // is C[row, col] of the wavefront's block with row = 32*i + lane%32 and
+    // col = 32*j + 8*(r/4) + 4*(lane/32) + r%4: four consecutive columns per r/4,
+    // i.e. 8 contiguous bytes of bf16.  Wavefront w parks its 128 x 128 bf16 block
+    // in ring stage w (rows of 256 bytes = 32 units of 8 bytes; unit u of row q is
+    // kept at u ^ (q & 31) so that the 32 rows written together spread over the
+    // banks), then streams it out as 16-byte runs, 16 lanes per row.
     uint8_t *park = wave == 0 ? ring0 : wave == 1 ? ring1 : wave == 2 ? ring2 : ring3;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const uint32_t row = 32 * i + 8 * (r / 4) + 4 * fhalf + (r & 3);
-                const uint32_t col = 32 * j + frow;
-                *(uint16_t *)(park + row * 256 + col * 2) = (uint16_t)gemm_f32_to_bf16(acc[i][j][r]);
+            for (int g = 0; g < 4; ++g) {
+                const f32x2 lo = {acc[i][j][4 * g + 0], acc[i][j][4 * g + 1]};
+                const f32x2 hi = {acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                u32x2 w;
+                w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+                w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
+                const uint32_t row = 32 * i + frow;
+                const uint32_t unit = (8 * j + 2 * g + fhalf) ^ (row & 31);
+                *(u32x2 *)(park + row * 256 + unit * 8) = w;
             }
     __syncthreads();
     const uint32_t orow = lane >> 4, og = lane & 15;
@@ -539,7 +560,9 @@ void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_
     for (int it = 0; it < 32; ++it) {
         const uint32_t row = orow + 4 * it;
         const uint32_t m = m0 + wm * 128 + row, n = n0 + wn * 128 + og * 8;
-        const u32x4 v = *(const u32x4 *)(park + row * 256 + og * 16);
+        // units 2*og and 2*og+1 sit in granule og ^ ((row & 31) / 2), swapped if the row is odd
+        u32x4 v = *(const u32x4 *)(park + row * 256 + ((og ^ ((row & 31) >> 1)) << 4));
+        if (row & 1) v = (u32x4){v[2], v[3], v[0], v[1]};
         F.template st<u32x4>(p.C + 2 * ((uint64_t)m * p.N + n), v);
     }
 }
