@@ -50,8 +50,9 @@ typedef enum {
 typedef enum {
     GD_FENCE_NONE = 0,     /* native kernel: tenant runs alone, protection off (Section 4.2.3) */
     GD_FENCE_BITWISE = 1,  /* AND with mask, OR with base (Listing 1); needs size-aligned pow2 partitions */
-    GD_FENCE_MODULO = 2,   /* base + (addr - base) % size (Section 4.4) */
-    GD_FENCE_CHECK = 3     /* compare against base/end; an offending thread stops (Sections 4.3, 4.4) */
+    GD_FENCE_MODULO = 2,   /* base + (addr - base) % size (Section 4.4); any size, any alignment */
+    GD_FENCE_CHECK = 3     /* compare against base/end; an offending logical thread stops and is counted
+                              (Sections 4.3, 4.4).  Built for kernel ids 0..8; others: GD_ENOKERNEL */
 } gd_fence_mode;
 
 /* ---- pool and partition bounds table (Section 4.2.1) ---------------------- */
@@ -66,6 +67,23 @@ typedef enum {
  * n_tenants may be 0 (part_bytes may then be NULL). */
 int gd_pool_create(uint64_t dev_base, uint64_t dev_bytes, const uint64_t *part_bytes,
                    int n_tenants, gd_pool **out);
+
+/* The same for partitions of ARBITRARY size (Section 4.4: the modulo fence and
+ * address checking need neither power-of-two sizes nor alignment).  Sizes must be
+ * multiples of GD_GRANULE and at least GD_MIN_PARTITION (else GD_ENOTPOW2);
+ * partitions are placed in tenant order, each at the lowest GD_GRANULE-aligned
+ * free address.  Kernels on such a pool can only be launched with
+ * GD_FENCE_MODULO, GD_FENCE_CHECK or GD_FENCE_NONE (GD_FENCE_BITWISE: GD_EINVAL);
+ * gd_tenant_attach on it follows the same placement rule. */
+int gd_pool_create_flex(uint64_t dev_base, uint64_t dev_bytes, const uint64_t *part_bytes,
+                        int n_tenants, gd_pool **out);
+
+/* Address checking reports violations in a per-tenant uint64 counter (one per
+ * tenant number, `slots` of them) at device address `dev_counters`.  The array
+ * is owned by the caller in the manager's role: it must lie outside the pool (else
+ * GD_EINVAL), be 8-byte aligned and zeroed by the caller.  Required before any
+ * GD_FENCE_CHECK launch. */
+int gd_pool_set_fault_counters(gd_pool *pool, uint64_t dev_counters, int slots);
 
 /* Frees host metadata only. */
 int gd_pool_destroy(gd_pool *pool);

@@ -20,7 +20,9 @@
  *                log2(width) bits are cleared too (this build's reading: the
  *                paper fences the start address only, and hardware that allows
  *                unaligned accesses needs the whole access inside)
- *   2  modulo    base + ((addr - base) % size), Section 4.4
+ *   2  modulo    base + ((addr - base) % size), Section 4.4, with the same
+ *                width rule: the low log2(width) bits of the offset are cleared
+ *                (bases and sizes are multiples of every access width)
  *   3  check     Section 4.4: the access proceeds only if it lies inside the
  *                partition; otherwise the logical thread stops (Section 4.3,
  *                last sentence) and the violation is counted
@@ -65,7 +67,7 @@ static int effective(gdo_ctx *c, uint64_t raw, uint32_t width, uint64_t *eff)
         break;
     }
     case 2:
-        *eff = base + ((raw - base) % size);
+        *eff = base + (((raw - base) % size) & ~(uint64_t)(width - 1));
         break;
     case 3:
         if (raw < base || raw + (width - 1) < raw || raw + (width - 1) > base + size - 1) {

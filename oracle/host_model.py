@@ -12,6 +12,7 @@ fence with the modulo definition of Section 4.4.
 U64 = (1 << 64) - 1
 
 ACCESS_WIDTHS = (1, 2, 4, 8, 16)
+GRANULE = 256
 
 
 def is_pow2(v):
@@ -97,10 +98,37 @@ def fence(addr, base, size, width=1):
     return (addr & mask) | base
 
 
-def fence_modulo(addr, base, size):
+def fence_modulo(addr, base, size, width=1):
     """Section 4.4: ``base + ((addr - base) % size)``, subtraction in wrap-around
-    64-bit arithmetic, ``%`` the non-negative remainder.  No alignment needed."""
-    return base + (((addr - base) & U64) % size)
+    64-bit arithmetic, ``%`` the non-negative remainder.  No alignment needed.
+    ``width``: as for the bitwise fence, the low bits of the offset are cleared so
+    that the whole access stays inside (base and size are multiples of the width)."""
+    assert width in ACCESS_WIDTHS
+    return base + ((((addr - base) & U64) % size) & ~(width - 1))
+
+
+def carve_flex(pool_base, pool_bytes, sizes):
+    """Partitions of arbitrary size for the modulo fence and address checking
+    (Section 4.4: no power of two, no alignment to the size): tenants in order,
+    each at the lowest 256-byte aligned address that is still free."""
+    table = []
+    for size in sizes:
+        spot = lowest_free(pool_base, pool_bytes, table, size, GRANULE)
+        if spot is None:
+            return None
+        table.append((spot, size))
+    return table
+
+
+def lowest_free(pool_base, pool_bytes, taken, size, align):
+    pool_end = pool_base + pool_bytes
+    a = -(-pool_base // align) * align
+    while a + size <= pool_end:
+        clash = [b + s for (b, s) in taken if a < b + s and b < a + size]
+        if not clash:
+            return a
+        a = -(-max(clash) // align) * align
+    return None
 
 
 def check_access(addr, base, size, width=1):
@@ -123,9 +151,6 @@ def check_copy(base, size, ptr, nbytes):
 # ---------------------------------------------------------------------------
 # In-partition allocator model (Section 4.2.1; policy is this build's)
 # ---------------------------------------------------------------------------
-
-GRANULE = 256
-
 
 class FirstFit:
     """Address-ordered first fit inside one partition, written the slow way.

@@ -41,6 +41,8 @@ gd_args_gemm = _struct("gd_args_gemm", [("C", _u64), ("A", _u64), ("B", _u64), (
 
 EXPORTS = {
     "gd_pool_create": (C.c_int, [_u64, _u64, C.POINTER(_u64), C.c_int, C.POINTER(C.c_void_p)]),
+    "gd_pool_create_flex": (C.c_int, [_u64, _u64, C.POINTER(_u64), C.c_int, C.POINTER(C.c_void_p)]),
+    "gd_pool_set_fault_counters": (C.c_int, [C.c_void_p, _u64, C.c_int]),
     "gd_pool_destroy": (C.c_int, [C.c_void_p]),
     "gd_tenant_attach": (C.c_int, [C.c_void_p, _u64, C.POINTER(C.c_int)]),
     "gd_tenant_detach": (C.c_int, [C.c_void_p, C.c_int]),
@@ -95,6 +97,17 @@ def gd_pool_create(dev_base, dev_bytes, part_bytes):
     out = C.c_void_p()
     _ok(lib().gd_pool_create(dev_base, dev_bytes, arr, len(part_bytes), C.byref(out)), "gd_pool_create")
     return out
+
+
+def gd_pool_create_flex(dev_base, dev_bytes, part_bytes):
+    arr = (_u64 * len(part_bytes))(*part_bytes) if len(part_bytes) else None
+    out = C.c_void_p()
+    _ok(lib().gd_pool_create_flex(dev_base, dev_bytes, arr, len(part_bytes), C.byref(out)), "gd_pool_create_flex")
+    return out
+
+
+def gd_pool_set_fault_counters(pool, dev_counters, slots):
+    _ok(lib().gd_pool_set_fault_counters(pool, dev_counters, slots), "gd_pool_set_fault_counters")
 
 
 def gd_pool_destroy(pool):

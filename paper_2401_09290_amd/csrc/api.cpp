@@ -46,9 +46,23 @@ int gd_pool_create(uint64_t dev_base, uint64_t dev_bytes, const uint64_t *part_b
                    gd_pool **out)
 {
     gd::Pool *p = nullptr;
-    int rc = gd::pool_create(dev_base, dev_bytes, part_bytes, n_tenants, &p);
+    int rc = gd::pool_create(dev_base, dev_bytes, part_bytes, n_tenants, false, &p);
     if (rc == GD_OK) *out = p;
     return rc;
+}
+
+int gd_pool_create_flex(uint64_t dev_base, uint64_t dev_bytes, const uint64_t *part_bytes, int n_tenants,
+                        gd_pool **out)
+{
+    gd::Pool *p = nullptr;
+    int rc = gd::pool_create(dev_base, dev_bytes, part_bytes, n_tenants, true, &p);
+    if (rc == GD_OK) *out = p;
+    return rc;
+}
+
+int gd_pool_set_fault_counters(gd_pool *pool, uint64_t dev_counters, int slots)
+{
+    return gd::set_fault_counters(pool, dev_counters, slots);
 }
 
 int gd_pool_destroy(gd_pool *pool)
@@ -102,14 +116,35 @@ int gd_launch_fenced(gd_pool *pool, int tenant, int kernel_id, const void *args,
     if (rc != GD_OK) return rc;
 
     int variant;
+    gd::FenceArgs extra = {base, mask, 0, 0, (uint32_t)tenant, 0};
     switch (mode) {
     case GD_FENCE_NONE:
         variant = gd::V_NONE;
         break;
     case GD_FENCE_BITWISE:
+        if (pool->flex) return GD_EINVAL;            // needs power-of-two, size-aligned partitions
         // A mask that fits 32 bits lets the kernel fence a 32-bit offset and add
         // the base in the addressing mode; larger partitions fence the high word.
         variant = (mask <= 0xffffffffull) ? gd::V_BIT32 : gd::V_BIT64;
+        break;
+    case GD_FENCE_MODULO: {
+        // Reciprocal for the exact 64-bit remainder by `size` (division by an
+        // invariant integer, round-up method): shift = ceil(log2 size),
+        // magic = floor(2^64 * (2^shift - size) / size) + 1.
+        variant = gd::V_MOD;
+        uint32_t l = 0;
+        while (l < 64 && ((uint64_t)1 << l) < size) ++l;
+        const unsigned __int128 pow_l = (unsigned __int128)1 << l;
+        extra.mask = size;
+        extra.shift = l;
+        extra.magic = (uint64_t)((((unsigned __int128)1 << 64) * (pow_l - size)) / size) + 1;
+        break;
+    }
+    case GD_FENCE_CHECK:
+        if (!pool->fault_counters || tenant >= pool->fault_slots) return GD_EINVAL;
+        variant = gd::V_CHECK;
+        extra.mask = size;
+        extra.faults = pool->fault_counters;
         break;
     default:
         return GD_ENOKERNEL;
@@ -118,7 +153,6 @@ int gd_launch_fenced(gd_pool *pool, int tenant, int kernel_id, const void *args,
     alignas(16) unsigned char copy[64];                                      // parameter augmentation
     static_assert(sizeof(gd_args_gemm) <= sizeof(copy) && sizeof(gd_args_scatter) <= sizeof(copy), "args copy too small");
     std::memcpy(copy, args, args_bytes);
-    const gd::FenceArgs extra = {base, mask};
     const gd::Shape shape = {grid, block};
     return k.launch(copy, extra, variant, shape, static_cast<hipStream_t>(hip_stream));
 }

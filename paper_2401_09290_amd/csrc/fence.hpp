@@ -15,6 +15,13 @@
 //   V_BIT64  partition >= 4 GiB.  Then mask_lo = 0xFFFFFFFF and base_lo = 0, so
 //            only the high word needs the AND/OR (two VALU ops).
 //   V_NONE   native kernel: plain global pointer, no fence (Section 4.2.3).
+//   V_MOD    Section 4.4's modulo fence, base + (addr - base) % size, for partitions
+//            of any size and alignment: the 64-bit remainder is taken with a
+//            multiply-high by a reciprocal the host precomputes per partition (the
+//            paper's extra parameter holding 1/size), corrected to be exact.
+//   V_CHECK  Section 4.4's address checking: the access proceeds unchanged if it
+//            lies inside [base, base+size), otherwise the logical thread stops and
+//            the tenant's fault counter (manager-owned memory) is incremented.
 //
 // Width rule: an access of W bytes also clears the low log2(W) address bits, so
 // the whole access lies inside the partition (for naturally aligned addresses
@@ -37,12 +44,18 @@
 
 namespace gd {
 
-enum Variant : int { V_NONE = 0, V_BIT32 = 1, V_BIT64 = 2, V_COUNT = 3 };
+enum Variant : int { V_NONE = 0, V_BIT32 = 1, V_BIT64 = 2, V_MOD = 3, V_CHECK = 4, V_COUNT = 5 };
 
-// The two extra kernel parameters of Listing 1.
+// The extra kernel parameters.  Listing 1's two (base, mask) are all the bitwise
+// fence uses; the other rules of Section 4.4 reuse `mask` for the partition size
+// and add the reciprocal (modulo) or the fault counter (checking).
 struct FenceArgs {
     uint64_t base;
-    uint64_t mask;
+    uint64_t mask;      // bitwise: size - 1.  modulo, checking: size in bytes
+    uint64_t magic;     // modulo: floor(2^64 * (2^shift - size) / size) + 1
+    uint32_t shift;     // modulo: ceil(log2(size))
+    uint32_t tenant;    // checking: slot of the launching tenant in the fault counters
+    uint64_t faults;    // checking: device address of the uint64 fault counters, outside the pool
 };
 
 #define GD_GLOBAL __attribute__((address_space(1)))
@@ -61,15 +74,46 @@ template <int V>
 struct Fence {
     uint64_t base;
     uint64_t mask;
+    uint64_t magic;
+    uint32_t shift;
+    uint32_t tenant;
+    uint64_t faults;
 
-    __device__ __forceinline__ explicit Fence(const FenceArgs &f) : base(f.base), mask(f.mask) {}
+    static constexpr bool CHECKED = (V == V_CHECK);
+
+    __device__ __forceinline__ explicit Fence(const FenceArgs &f)
+        : base(f.base), mask(f.mask), magic(f.magic), shift(f.shift), tenant(f.tenant), faults(f.faults) {}
+
+    // Address checking (V_CHECK only; every other rule lets all accesses through, the
+    // fence having made them safe): is the whole W-byte access inside the partition?
+    template <int W>
+    __device__ __forceinline__ bool inside(uint64_t raw) const
+    {
+        if constexpr (V == V_CHECK) return raw - base <= mask - W;     // mask holds the size; wrap-around makes addr < base fail
+        else return true;
+    }
+
+    // One violation: count it for the tenant.  The counter is manager-owned memory.
+    __device__ __forceinline__ void fault() const
+    {
+        if constexpr (V == V_CHECK)
+            atomicAdd((unsigned long long *)(faults + 8 * (uint64_t)tenant), 1ULL);
+    }
 
     // The fenced address of a W-byte access to `raw` (what the probe kernel reports).
     template <int W>
     __device__ __forceinline__ uint64_t address(uint64_t raw) const
     {
-        if constexpr (V == V_NONE) {
+        if constexpr (V == V_NONE || V == V_CHECK) {
             return raw;
+        } else if constexpr (V == V_MOD) {
+            // n mod d for any 64-bit n (Granlund-Montgomery division by an invariant):
+            // q = (t + ((n - t) >> 1)) >> (shift - 1) with t = mulhi(magic, n).
+            const uint64_t n = raw - base, d = mask;
+            const uint64_t t = __umul64hi(magic, n);
+            const uint64_t q = (t + ((n - t) >> 1)) >> (shift - 1);
+            const uint64_t r = n - q * d;
+            return base + (r & ~(uint64_t)(W - 1));
         } else if constexpr (V == V_BIT32) {
             const uint32_t m = (uint32_t)mask & ~(uint32_t)(W - 1);
             return base + (uint64_t)fence_and32((uint32_t)raw, m);
@@ -156,13 +200,27 @@ struct Fence {
     }
 };
 
-// Launch helper: instantiate KERNEL for the variant chosen on the host.
+// Launch helper for kernels built for all five variants.
+#define GD_LAUNCH_VARIANT5(variant, KERNEL, grid, block, stream, ...)                           \
+    do {                                                                                        \
+        switch (variant) {                                                                      \
+        case gd::V_NONE:  hipLaunchKernelGGL((KERNEL<gd::V_NONE>), grid, block, 0, stream, __VA_ARGS__); break;  \
+        case gd::V_BIT32: hipLaunchKernelGGL((KERNEL<gd::V_BIT32>), grid, block, 0, stream, __VA_ARGS__); break; \
+        case gd::V_BIT64: hipLaunchKernelGGL((KERNEL<gd::V_BIT64>), grid, block, 0, stream, __VA_ARGS__); break; \
+        case gd::V_MOD:   hipLaunchKernelGGL((KERNEL<gd::V_MOD>), grid, block, 0, stream, __VA_ARGS__); break;   \
+        case gd::V_CHECK: hipLaunchKernelGGL((KERNEL<gd::V_CHECK>), grid, block, 0, stream, __VA_ARGS__); break; \
+        default: return GD_ENOKERNEL;                                                           \
+        }                                                                                       \
+    } while (0)
+
+// Launch helper: instantiate KERNEL for the variant chosen on the host (no checking build).
 #define GD_LAUNCH_VARIANT(variant, KERNEL, grid, block, stream, ...)                            \
     do {                                                                                        \
         switch (variant) {                                                                      \
         case gd::V_NONE:  hipLaunchKernelGGL((KERNEL<gd::V_NONE>), grid, block, 0, stream, __VA_ARGS__); break;  \
         case gd::V_BIT32: hipLaunchKernelGGL((KERNEL<gd::V_BIT32>), grid, block, 0, stream, __VA_ARGS__); break; \
         case gd::V_BIT64: hipLaunchKernelGGL((KERNEL<gd::V_BIT64>), grid, block, 0, stream, __VA_ARGS__); break; \
+        case gd::V_MOD:   hipLaunchKernelGGL((KERNEL<gd::V_MOD>), grid, block, 0, stream, __VA_ARGS__); break;   \
         default: return GD_ENOKERNEL;                                                           \
         }                                                                                       \
     } while (0)

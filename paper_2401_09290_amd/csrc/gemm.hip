@@ -592,6 +592,7 @@ int launch_gemm_bf16(const void *args, const FenceArgs &f, int variant, const Sh
             GD_GEMM_CASE(V_NONE)
             GD_GEMM_CASE(V_BIT32)
             GD_GEMM_CASE(V_BIT64)
+            GD_GEMM_CASE(V_MOD)
         default: return GD_ENOKERNEL;
         }
 #undef GD_GEMM_CASE

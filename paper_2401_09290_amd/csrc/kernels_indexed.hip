@@ -15,6 +15,9 @@ typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
 
 constexpr int EPT = 4;   // elements per thread on the vector path
 
+// Under address checking (Section 4.4) the kernels take their per-element path,
+// where every access is tested on its own and an offending logical thread stops.
+
 // ---- y[o] = alpha*x[o] + y[o], o = off[i] ---------------------------------------
 template <int V>
 __global__ __launch_bounds__(1024) void k_saxpy_idx(gd_args_saxpy_idx p, FenceArgs fa)
@@ -23,7 +26,7 @@ __global__ __launch_bounds__(1024) void k_saxpy_idx(gd_args_saxpy_idx p, FenceAr
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
     const uint64_t tid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     uint64_t done = 0;
-    if ((p.off & 15) == 0) {
+    if (!F.CHECKED && (p.off & 15) == 0) {
         const uint64_t n4 = p.n >> 2;
         for (uint64_t q = tid; q < n4; q += stride) {
             const i32x4 o = F.template ld<i32x4, true>(p.off + 16 * q);
@@ -41,9 +44,12 @@ __global__ __launch_bounds__(1024) void k_saxpy_idx(gd_args_saxpy_idx p, FenceAr
         done = 4 * n4;
     }
     for (uint64_t i = done + tid; i < p.n; i += stride) {
+        if (!F.template inside<4>(p.off + 4 * i)) { F.fault(); continue; }
         const int32_t o = F.template ld<int32_t>(p.off + 4 * i);
         const uint64_t byte_off = (uint64_t)((int64_t)o * 4);
+        if (!F.template inside<4>(p.x + byte_off)) { F.fault(); continue; }
         const float vx = F.template ld<float>(p.x + byte_off);
+        if (!F.template inside<4>(p.y + byte_off)) { F.fault(); continue; }
         const float vy = F.template ld<float>(p.y + byte_off);
         F.template st<float>(p.y + byte_off, p.alpha * vx + vy);
     }
@@ -58,7 +64,7 @@ __global__ __launch_bounds__(1024) void k_gather32(gd_args_gather p, FenceArgs f
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
     const uint64_t tid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     uint64_t done = 0;
-    if (((p.idx | p.out) & 15) == 0) {
+    if (!F.CHECKED && ((p.idx | p.out) & 15) == 0) {
         const uint64_t n4 = p.n >> 2;
         for (uint64_t q = tid; q < n4; q += stride) {
             uint64_t k[EPT];
@@ -79,9 +85,13 @@ __global__ __launch_bounds__(1024) void k_gather32(gd_args_gather p, FenceArgs f
         done = 4 * n4;
     }
     for (uint64_t i = done + tid; i < p.n; i += stride) {
-        const uint64_t k = IDX64 ? F.template ld<uint64_t>(p.idx + 8 * i)
-                                 : (uint64_t)(int64_t)F.template ld<int32_t>(p.idx + 4 * i);
-        F.template st<uint32_t>(p.out + 4 * i, F.template ld<uint32_t>(p.tab + 4 * k));
+        const uint64_t ia = IDX64 ? p.idx + 8 * i : p.idx + 4 * i;
+        if (!F.template inside<IDX64 ? 8 : 4>(ia)) { F.fault(); continue; }
+        const uint64_t k = IDX64 ? F.template ld<uint64_t>(ia) : (uint64_t)(int64_t)F.template ld<int32_t>(ia);
+        if (!F.template inside<4>(p.tab + 4 * k)) { F.fault(); continue; }
+        const uint32_t v = F.template ld<uint32_t>(p.tab + 4 * k);
+        if (!F.template inside<4>(p.out + 4 * i)) { F.fault(); continue; }
+        F.template st<uint32_t>(p.out + 4 * i, v);
     }
 }
 
@@ -93,7 +103,7 @@ __global__ __launch_bounds__(1024) void k_scatter_f32_i64(gd_args_scatter p, Fen
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
     const uint64_t tid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     uint64_t done = 0;
-    if (((p.idx | p.src) & 15) == 0) {
+    if (!F.CHECKED && ((p.idx | p.src) & 15) == 0) {
         const uint64_t n4 = p.n >> 2;
         for (uint64_t q = tid; q < n4; q += stride) {
             const u64x2 k01 = F.template ld<u64x2, true>(p.idx + 32 * q);
@@ -107,8 +117,11 @@ __global__ __launch_bounds__(1024) void k_scatter_f32_i64(gd_args_scatter p, Fen
         done = 4 * n4;
     }
     for (uint64_t i = done + tid; i < p.n; i += stride) {
+        if (!F.template inside<8>(p.idx + 8 * i)) { F.fault(); continue; }
         const uint64_t k = F.template ld<uint64_t>(p.idx + 8 * i);
+        if (!F.template inside<4>(p.src + 4 * i)) { F.fault(); continue; }
         const float v = F.template ld<float>(p.src + 4 * i);
+        if (!F.template inside<4>(p.dst + 4 * k)) { F.fault(); continue; }
         F.template st<float>(p.dst + 4 * k, p.scale * v);
     }
 }
@@ -133,6 +146,8 @@ static uint64_t blocks_for(uint64_t n, uint32_t block)
         case V_NONE:  hipLaunchKernelGGL((KERNEL_EXPR(V_NONE)), dim3(grid), dim3(block), 0, stream, p, f); break;  \
         case V_BIT32: hipLaunchKernelGGL((KERNEL_EXPR(V_BIT32)), dim3(grid), dim3(block), 0, stream, p, f); break; \
         case V_BIT64: hipLaunchKernelGGL((KERNEL_EXPR(V_BIT64)), dim3(grid), dim3(block), 0, stream, p, f); break; \
+        case V_MOD:   hipLaunchKernelGGL((KERNEL_EXPR(V_MOD)), dim3(grid), dim3(block), 0, stream, p, f); break;   \
+        case V_CHECK: hipLaunchKernelGGL((KERNEL_EXPR(V_CHECK)), dim3(grid), dim3(block), 0, stream, p, f); break; \
         default: return GD_ENOKERNEL;                                                                    \
         }                                                                                                \
         GD_CHECK_LAUNCH();                                                                               \

@@ -58,7 +58,7 @@ __global__ __launch_bounds__(WG) void k_sum_partial(gd_args_sum p, FenceArgs fa)
         f32x4 a4 = {0.0f, 0.0f, 0.0f, 0.0f};
         for (uint64_t t0 = blockIdx.x * tile; t0 < n4; t0 += gridDim.x * tile) {
             const uint64_t i0 = t0 + threadIdx.x;
-            if (t0 + tile <= n4) {
+            if (!F.CHECKED && t0 + tile <= n4) {
                 f32x4 v[SUM_UNROLL];
 #pragma unroll
                 for (int u = 0; u < SUM_UNROLL; ++u) v[u] = F.template ld<f32x4, true>(p.in + 16 * (i0 + (uint64_t)u * WG));
@@ -68,19 +68,38 @@ __global__ __launch_bounds__(WG) void k_sum_partial(gd_args_sum p, FenceArgs fa)
 #pragma unroll
                 for (int u = 0; u < SUM_UNROLL; ++u) {
                     const uint64_t i = i0 + (uint64_t)u * WG;
-                    if (i < n4) a4 += F.template ld<f32x4, true>(p.in + 16 * i);
+                    if (i >= n4) continue;
+                    if (F.template inside<16>(p.in + 16 * i)) {
+                        a4 += F.template ld<f32x4, true>(p.in + 16 * i);
+                    } else {                       // address checking: element by element, offenders contribute nothing
+                        for (int e = 0; e < 4; ++e) {
+                            if (F.template inside<4>(p.in + 16 * i + 4 * e)) a4[e] += F.template ld<float>(p.in + 16 * i + 4 * e);
+                            else F.fault();
+                        }
+                    }
                 }
             }
         }
         acc = (a4[0] + a4[1]) + (a4[2] + a4[3]);
-        if (blockIdx.x == 0 && threadIdx.x < (p.n & 3)) acc += F.template ld<float>(p.in + 4 * (4 * n4 + threadIdx.x));
+        if (blockIdx.x == 0 && threadIdx.x < (p.n & 3)) {
+            const uint64_t a = p.in + 4 * (4 * n4 + threadIdx.x);
+            if (F.template inside<4>(a)) acc += F.template ld<float>(a);
+            else F.fault();
+        }
     } else {
         const uint64_t stride = (uint64_t)gridDim.x * WG;
-        for (uint64_t i = (uint64_t)blockIdx.x * WG + threadIdx.x; i < p.n; i += stride)
-            acc += F.template ld<float>(p.in + 4 * i);
+        for (uint64_t i = (uint64_t)blockIdx.x * WG + threadIdx.x; i < p.n; i += stride) {
+            if (F.template inside<4>(p.in + 4 * i)) acc += F.template ld<float>(p.in + 4 * i);
+            else F.fault();
+        }
     }
     const float total = block_sum(acc, lds);
-    if (threadIdx.x == 0) F.template st<float>(p.partials + 4 * (uint64_t)blockIdx.x, total);
+    // the workspace and the result are tenant memory too; a refused access to them is counted and dropped
+    if (threadIdx.x == 0) {
+        const uint64_t a = p.partials + 4 * (uint64_t)blockIdx.x;
+        if (F.template inside<4>(a)) F.template st<float>(a, total);
+        else F.fault();
+    }
 }
 
 // ---- sum, pass 2: out[0] = sum of the partials (added in fp64) ---------------------
@@ -90,10 +109,16 @@ __global__ __launch_bounds__(WG) void k_sum_final(gd_args_sum p, uint32_t n_part
     const Fence<V> F(fa);
     __shared__ double lds[WAVES];
     double acc = 0.0;
-    for (uint32_t i = threadIdx.x; i < n_partials; i += WG)
-        acc += (double)F.template ld<float>(p.partials + 4 * (uint64_t)i);
+    for (uint32_t i = threadIdx.x; i < n_partials; i += WG) {
+        const uint64_t a = p.partials + 4 * (uint64_t)i;
+        if (F.template inside<4>(a)) acc += (double)F.template ld<float>(a);
+        else F.fault();
+    }
     const double total = block_sum(acc, lds);
-    if (threadIdx.x == 0) F.template st<float>(p.out, (float)total);
+    if (threadIdx.x == 0) {
+        if (F.template inside<4>(p.out)) F.template st<float>(p.out, (float)total);
+        else F.fault();
+    }
 }
 
 // ---- RMSNorm -------------------------------------------------------------------------
@@ -188,9 +213,9 @@ int launch_sum_f32(const void *args, const FenceArgs &f, int variant, const Shap
     uint64_t blocks = (p.n + tile - 1) / tile;
     if (blocks == 0) blocks = 1;
     if (blocks > SUM_MAX_BLOCKS) blocks = SUM_MAX_BLOCKS;
-    GD_LAUNCH_VARIANT(variant, k_sum_partial, dim3((uint32_t)blocks), dim3(WG), stream, p, f);
+    GD_LAUNCH_VARIANT5(variant, k_sum_partial, dim3((uint32_t)blocks), dim3(WG), stream, p, f);
     GD_CHECK_LAUNCH();
-    GD_LAUNCH_VARIANT(variant, k_sum_final, dim3(1), dim3(WG), stream, p, (uint32_t)blocks, f);
+    GD_LAUNCH_VARIANT5(variant, k_sum_final, dim3(1), dim3(WG), stream, p, (uint32_t)blocks, f);
     GD_CHECK_LAUNCH();
     return GD_OK;
 }

@@ -19,26 +19,35 @@ __global__ __launch_bounds__(1024) void k_store_tid(gd_args_store_tid p, FenceAr
 {
     const Fence<V> F(fa);
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < p.n; i += stride)
-        F.template st<uint32_t>(p.A + 4 * i, p.j);
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < p.n; i += stride) {
+        const uint64_t a = p.A + 4 * i;
+        if (!F.template inside<4>(a)) { F.fault(); continue; }
+        F.template st<uint32_t>(a, p.j);
+    }
 }
 
 // ---- fence probe: out[i] = fence_width(in[i]) ----------------------------------
+// Under address checking the probe reports ~0 for an address that is refused (and
+// counts it), like any other refused access.
 template <int V>
 __global__ __launch_bounds__(1024) void k_fence_addrs(gd_args_fence_addrs p, FenceArgs fa)
 {
     const Fence<V> F(fa);
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
     for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < p.n; i += stride) {
+        if (!F.template inside<8>(p.in + 8 * i)) { F.fault(); continue; }
         const uint64_t a = F.template ld<uint64_t>(p.in + 8 * i);
         uint64_t f;
+        bool ok;
         switch (p.width) {
-        case 1: f = F.template address<1>(a); break;
-        case 2: f = F.template address<2>(a); break;
-        case 4: f = F.template address<4>(a); break;
-        case 8: f = F.template address<8>(a); break;
-        default: f = F.template address<16>(a); break;
+        case 1: f = F.template address<1>(a); ok = F.template inside<1>(a); break;
+        case 2: f = F.template address<2>(a); ok = F.template inside<2>(a); break;
+        case 4: f = F.template address<4>(a); ok = F.template inside<4>(a); break;
+        case 8: f = F.template address<8>(a); ok = F.template inside<8>(a); break;
+        default: f = F.template address<16>(a); ok = F.template inside<16>(a); break;
         }
+        if (!ok) { F.fault(); f = ~(uint64_t)0; }
+        if (!F.template inside<8>(p.out + 8 * i)) { F.fault(); continue; }
         F.template st<uint64_t>(p.out + 8 * i, f);
     }
 }
@@ -47,55 +56,57 @@ __global__ __launch_bounds__(1024) void k_fence_addrs(gd_args_fence_addrs p, Fen
 // OP 0: a = b.  OP 1: a = b + s*c (one fused multiply-add per element).
 // Vector path when all pointers are 16-byte aligned (then a 16-byte access equals
 // four fenced 4-byte accesses); otherwise every element is accessed on its own.
+// Under address checking a vector whose three 16-byte accesses are not all inside
+// the partition is redone element by element, so that exactly the offending
+// logical threads stop.
 template <int V, int OP>
 __global__ __launch_bounds__(1024) void k_stream(uint64_t pa, uint64_t pb, uint64_t pc, uint64_t n,
                                                  float s, FenceArgs fa)
 {
     const Fence<V> F(fa);
+    // one logical thread: accesses in the order load b, load c, store a
+    auto element = [&](uint64_t i) {
+        if (!F.template inside<4>(pb + 4 * i)) { F.fault(); return; }
+        float r = F.template ld<float>(pb + 4 * i);
+        if (OP) {
+            if (!F.template inside<4>(pc + 4 * i)) { F.fault(); return; }
+            r = r + s * F.template ld<float>(pc + 4 * i);
+        }
+        if (!F.template inside<4>(pa + 4 * i)) { F.fault(); return; }
+        F.template st<float>(pa + 4 * i, r);
+    };
     const uint64_t ptr_bits = OP ? (pa | pb | pc) : (pa | pb);
     if ((ptr_bits & 15) == 0) {
         const uint64_t n4 = n >> 2;
         const uint64_t tile = (uint64_t)blockDim.x * UNROLL;
         for (uint64_t t0 = blockIdx.x * tile; t0 < n4; t0 += gridDim.x * tile) {
-            const uint64_t i0 = t0 + threadIdx.x;
             f32x4 vb[UNROLL], vc[UNROLL];
-            if (t0 + tile <= n4) {
+            bool vec[UNROLL];
 #pragma unroll
-                for (int u = 0; u < UNROLL; ++u) {
-                    const uint64_t i = i0 + (uint64_t)u * blockDim.x;
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint64_t i = t0 + threadIdx.x + (uint64_t)u * blockDim.x;
+                vec[u] = i < n4;
+                if (F.CHECKED && vec[u] &&
+                    !(F.template inside<16>(pb + 16 * i) && (!OP || F.template inside<16>(pc + 16 * i)) &&
+                      F.template inside<16>(pa + 16 * i))) {
+                    vec[u] = false;
+                    for (int e = 0; e < 4; ++e) element(4 * i + e);
+                }
+                if (vec[u]) {
                     vb[u] = F.template ld<f32x4, true>(pb + 16 * i);
                     if (OP) vc[u] = F.template ld<f32x4, true>(pc + 16 * i);
                 }
+            }
 #pragma unroll
-                for (int u = 0; u < UNROLL; ++u) {
-                    const uint64_t i = i0 + (uint64_t)u * blockDim.x;
-                    F.template st<f32x4, true>(pa + 16 * i, OP ? vb[u] + s * vc[u] : vb[u]);
-                }
-            } else {
-#pragma unroll
-                for (int u = 0; u < UNROLL; ++u) {
-                    const uint64_t i = i0 + (uint64_t)u * blockDim.x;
-                    if (i < n4) {
-                        vb[u] = F.template ld<f32x4, true>(pb + 16 * i);
-                        if (OP) vc[u] = F.template ld<f32x4, true>(pc + 16 * i);
-                        F.template st<f32x4, true>(pa + 16 * i, OP ? vb[u] + s * vc[u] : vb[u]);
-                    }
-                }
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint64_t i = t0 + threadIdx.x + (uint64_t)u * blockDim.x;
+                if (vec[u]) F.template st<f32x4, true>(pa + 16 * i, OP ? vb[u] + s * vc[u] : vb[u]);
             }
         }
-        if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {          // at most three elements left
-            const uint64_t i = 4 * n4 + threadIdx.x;
-            float r = F.template ld<float>(pb + 4 * i);
-            if (OP) r = r + s * F.template ld<float>(pc + 4 * i);
-            F.template st<float>(pa + 4 * i, r);
-        }
+        if (blockIdx.x == 0 && threadIdx.x < (n & 3)) element(4 * n4 + threadIdx.x);   // at most three elements left
     } else {
         const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-        for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
-            float r = F.template ld<float>(pb + 4 * i);
-            if (OP) r = r + s * F.template ld<float>(pc + 4 * i);
-            F.template st<float>(pa + 4 * i, r);
-        }
+        for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) element(i);
     }
 }
 
@@ -108,7 +119,7 @@ int launch_store_tid(const void *args, const FenceArgs &f, int variant, const Sh
     uint32_t grid, block;
     if (!pick_1d(shape, (p.n + 255) / 256, 256, &grid, &block)) return GD_EINVAL;
     if (p.n == 0) return GD_OK;
-    GD_LAUNCH_VARIANT(variant, k_store_tid, dim3(grid), dim3(block), stream, p, f);
+    GD_LAUNCH_VARIANT5(variant, k_store_tid, dim3(grid), dim3(block), stream, p, f);
     GD_CHECK_LAUNCH();
     return GD_OK;
 }
@@ -122,7 +133,7 @@ int launch_fence_addrs(const void *args, const FenceArgs &f, int variant, const 
     uint32_t grid, block;
     if (!pick_1d(shape, (p.n + 255) / 256, 256, &grid, &block)) return GD_EINVAL;
     if (p.n == 0) return GD_OK;
-    GD_LAUNCH_VARIANT(variant, k_fence_addrs, dim3(grid), dim3(block), stream, p, f);
+    GD_LAUNCH_VARIANT5(variant, k_fence_addrs, dim3(grid), dim3(block), stream, p, f);
     GD_CHECK_LAUNCH();
     return GD_OK;
 }
@@ -133,6 +144,8 @@ int launch_fence_addrs(const void *args, const FenceArgs &f, int variant, const 
         case V_NONE:  hipLaunchKernelGGL((k_stream<V_NONE, OP>), grid, block, 0, stream, __VA_ARGS__); break;  \
         case V_BIT32: hipLaunchKernelGGL((k_stream<V_BIT32, OP>), grid, block, 0, stream, __VA_ARGS__); break; \
         case V_BIT64: hipLaunchKernelGGL((k_stream<V_BIT64, OP>), grid, block, 0, stream, __VA_ARGS__); break; \
+        case V_MOD:   hipLaunchKernelGGL((k_stream<V_MOD, OP>), grid, block, 0, stream, __VA_ARGS__); break;   \
+        case V_CHECK: hipLaunchKernelGGL((k_stream<V_CHECK, OP>), grid, block, 0, stream, __VA_ARGS__); break; \
         default: return GD_ENOKERNEL;                                                                   \
         }                                                                                               \
     } while (0)

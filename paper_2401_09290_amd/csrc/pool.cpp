@@ -19,10 +19,18 @@ static inline bool align_up(uint64_t v, uint64_t align, uint64_t *out)
     return true;
 }
 
-// Lowest size-aligned address whose block fits the pool and overlaps no
-// attached partition.  `rows` need not be sorted.
+static inline bool size_ok(const Pool &p, uint64_t bytes)
+{
+    if (bytes < GD_MIN_PARTITION) return false;
+    return p.flex ? (bytes % GD_GRANULE) == 0 : is_pow2(bytes);
+}
+
+// Lowest aligned address whose block fits the pool and overlaps no attached
+// partition; aligned to the size (power-of-two pools) or to the granule (flex
+// pools).  `rows` need not be sorted.
 static bool place(const Pool &p, uint64_t size, uint64_t *where)
 {
+    const uint64_t align = p.flex ? (uint64_t)GD_GRANULE : size;
     std::vector<std::pair<uint64_t, uint64_t>> taken;   // (base, end) sorted by base
     for (const Partition &r : p.rows)
         if (r.attached) taken.emplace_back(r.base, r.base + r.size);
@@ -30,7 +38,7 @@ static bool place(const Pool &p, uint64_t size, uint64_t *where)
 
     const uint64_t pool_end = p.dev_base + p.dev_bytes;   // caller checked: no overflow
     uint64_t a;
-    if (!align_up(p.dev_base, size, &a)) return false;
+    if (!align_up(p.dev_base, align, &a)) return false;
     size_t k = 0;
     while (a <= pool_end && pool_end - a >= size) {
         while (k < taken.size() && taken[k].second <= a) ++k;      // entirely in front of a
@@ -38,29 +46,35 @@ static bool place(const Pool &p, uint64_t size, uint64_t *where)
             *where = a;
             return true;
         }
-        if (!align_up(taken[k].second, size, &a)) return false;    // hop behind the obstacle
+        if (!align_up(taken[k].second, align, &a)) return false;   // hop behind the obstacle
     }
     return false;
 }
 
-int pool_create(uint64_t dev_base, uint64_t dev_bytes, const uint64_t *part_bytes, int n,
+int pool_create(uint64_t dev_base, uint64_t dev_bytes, const uint64_t *part_bytes, int n, bool flex,
                 Pool **out)
 {
     if (!out || n < 0 || (n > 0 && !part_bytes)) return GD_EINVAL;
     if (dev_base + dev_bytes < dev_base) return GD_EINVAL;           // range wraps 2^64
-    for (int i = 0; i < n; ++i)
-        if (!is_pow2(part_bytes[i]) || part_bytes[i] < GD_MIN_PARTITION) return GD_ENOTPOW2;
 
     Pool *p = new (std::nothrow) Pool;
     if (!p) return GD_ENOMEM;
     p->dev_base = dev_base;
     p->dev_bytes = dev_bytes;
+    p->flex = flex;
+    for (int i = 0; i < n; ++i)
+        if (!size_ok(*p, part_bytes[i])) {
+            delete p;
+            return GD_ENOTPOW2;
+        }
     p->rows.resize(n);
 
+    // power-of-two pools: by decreasing size (packs without gaps); flex pools: tenant order
     std::vector<int> order(n);
     for (int i = 0; i < n; ++i) order[i] = i;
-    std::stable_sort(order.begin(), order.end(),
-                     [&](int x, int y) { return part_bytes[x] > part_bytes[y]; });
+    if (!flex)
+        std::stable_sort(order.begin(), order.end(),
+                         [&](int x, int y) { return part_bytes[x] > part_bytes[y]; });
     for (int t : order) {
         uint64_t where;
         if (!place(*p, part_bytes[t], &where)) {
@@ -82,7 +96,7 @@ int pool_create(uint64_t dev_base, uint64_t dev_bytes, const uint64_t *part_byte
 int tenant_attach(Pool *p, uint64_t bytes, int *tenant_out)
 {
     if (!p || !tenant_out) return GD_EINVAL;
-    if (!is_pow2(bytes) || bytes < GD_MIN_PARTITION) return GD_ENOTPOW2;
+    if (!size_ok(*p, bytes)) return GD_ENOTPOW2;
     std::lock_guard<std::mutex> g(p->mu);
     uint64_t where;
     if (!place(*p, bytes, &where)) return GD_ENOMEM;
@@ -97,6 +111,19 @@ int tenant_attach(Pool *p, uint64_t bytes, int *tenant_out)
     r.free_blocks[where] = bytes;
     r.live.clear();
     *tenant_out = (int)slot;
+    return GD_OK;
+}
+
+int set_fault_counters(Pool *p, uint64_t dev_counters, int slots)
+{
+    if (!p || slots < 0 || (dev_counters & 7)) return GD_EINVAL;
+    const uint64_t bytes = 8 * (uint64_t)slots;
+    if (dev_counters + bytes < dev_counters) return GD_EINVAL;
+    // must not overlap the pool: no tenant may be able to address its own counter
+    if (slots > 0 && dev_counters < p->dev_base + p->dev_bytes && p->dev_base < dev_counters + bytes) return GD_EINVAL;
+    std::lock_guard<std::mutex> g(p->mu);
+    p->fault_counters = slots ? dev_counters : 0;
+    p->fault_slots = slots;
     return GD_OK;
 }
 
@@ -204,7 +231,7 @@ uint64_t fence_host(uint64_t base, uint64_t size, uint64_t addr, uint32_t width,
         if (!is_pow2(size) || (base & (size - 1))) return bad;
         return (addr & (size - 1) & ~uint64_t(width - 1)) | base;
     case GD_FENCE_MODULO:
-        return base + (addr - base) % size;
+        return base + (((addr - base) % size) & ~uint64_t(width - 1));
     case GD_FENCE_CHECK: {
         const uint64_t last = addr + (width - 1);
         if (addr < base || last < addr || last > base + (size - 1)) return bad;

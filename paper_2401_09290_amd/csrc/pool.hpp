@@ -26,6 +26,9 @@ struct gd_pool {
     uint64_t dev_base = 0;
     uint64_t dev_bytes = 0;
     std::vector<gd::Partition> rows;         // index = tenant number
+    bool flex = false;                       // arbitrary sizes (modulo fence / checking only)
+    uint64_t fault_counters = 0;             // device address of the per-tenant uint64 counters, 0 = none
+    int fault_slots = 0;
     mutable std::mutex mu;
 };
 
@@ -33,7 +36,8 @@ namespace gd {
 
 using Pool = ::gd_pool;
 
-int pool_create(uint64_t dev_base, uint64_t dev_bytes, const uint64_t *part_bytes, int n, Pool **out);
+int pool_create(uint64_t dev_base, uint64_t dev_bytes, const uint64_t *part_bytes, int n, bool flex, Pool **out);
+int set_fault_counters(Pool *p, uint64_t dev_counters, int slots);
 int tenant_attach(Pool *p, uint64_t bytes, int *tenant_out);
 int tenant_detach(Pool *p, int tenant);
 int partition_info(const Pool *p, int tenant, uint64_t *base, uint64_t *size, uint64_t *mask);

@@ -211,12 +211,73 @@ def test_host_fence_equals_oracle_on_tiny_pool_and_random_addresses(width):
         b = s * rnd.randint(1, 1 << 12)
         a = rnd.getrandbits(64)
         assert gd.gd_fence_host(b, s, a, width, gd.GD_FENCE_BITWISE) == hm.fence(a, b, s, width)
-        assert gd.gd_fence_host(b, s, a, width, gd.GD_FENCE_MODULO) == hm.fence_modulo(a, b, s)
+        assert gd.gd_fence_host(b, s, a, width, gd.GD_FENCE_MODULO) == hm.fence_modulo(a, b, s, width)
         ok = hm.check_access(a, b, s, width)
         assert gd.gd_fence_host(b, s, a, width, gd.GD_FENCE_CHECK) == (a if ok else hm.U64)
         assert gd.gd_fence_host(b, s, a, width, gd.GD_FENCE_NONE) == a
     assert gd.gd_fence_host(4096 + 256, 4096, 0, 4) == hm.U64           # base not size-aligned
     assert gd.gd_fence_host(4096, 4096, 0, 3) == hm.U64                 # not an access width
+
+
+def test_flex_pool_places_odd_sizes_like_the_oracle():
+    rnd = random.Random(31)
+    for _ in range(200):
+        sizes = [256 * rnd.randint(16, 5000) for _ in range(rnd.randint(1, 9))]
+        pool_base = 256 * rnd.randint(1, 1 << 20) + rnd.choice([0, 0, 8, 100])
+        pool_bytes = sum(sizes) + rnd.choice([0, 256, 4096])
+        want = hm.carve_flex(pool_base, pool_bytes, sizes)
+        if want is None:
+            with pytest.raises(gd.GuardianError) as e:
+                gd.gd_pool_create_flex(pool_base, pool_bytes, sizes)
+            assert e.value.status == gd.GD_ENOMEM
+            continue
+        pool = gd.gd_pool_create_flex(pool_base, pool_bytes, sizes)
+        for t, (b, s) in enumerate(want):
+            assert gd.gd_partition_info(pool, t)[:2] == (b, s)
+            assert b % 256 == 0 and pool_base <= b and b + s <= pool_base + pool_bytes
+        spans = sorted(want)
+        for (b0, s0), (b1, _) in zip(spans, spans[1:]):
+            assert b0 + s0 <= b1
+        # the bitwise fence is refused on such a pool (its partitions are not size-aligned powers of two)
+        with pytest.raises(gd.GuardianError) as e:
+            gd.gd_launch_fenced(pool, 0, gd.GD_K_COPY, gd.gd_args_copy(want[0][0], want[0][0] + 1024, 4))
+        assert e.value.status == gd.GD_EINVAL
+        gd.gd_pool_destroy(pool)
+    for bad in ([4096 + 8], [2048], [0]):
+        with pytest.raises(gd.GuardianError) as e:
+            gd.gd_pool_create_flex(1 << 20, 1 << 20, bad)
+        assert e.value.status == gd.GD_ENOTPOW2
+
+
+def test_modulo_host_fence_on_odd_partitions_confines_whole_access():
+    rnd = random.Random(17)
+    for _ in range(20000):
+        size = 256 * rnd.randint(16, 1 << 24)
+        base = 256 * rnd.randint(1, 1 << 30)
+        a = rnd.getrandbits(64)
+        w = rnd.choice(hm.ACCESS_WIDTHS)
+        f = gd.gd_fence_host(base, size, a, w, gd.GD_FENCE_MODULO)
+        assert f == hm.fence_modulo(a, base, size, w)
+        assert base <= f and f + w <= base + size
+        if base <= a and a + w <= base + size and a % w == 0:
+            assert f == a
+
+
+def test_fault_counters_must_lie_outside_the_pool():
+    pool = gd.gd_pool_create(1 << 30, 1 << 20, [1 << 20])
+    for addr in ((1 << 30), (1 << 30) + (1 << 20) - 8, (1 << 30) - 8):
+        with pytest.raises(gd.GuardianError) as e:
+            gd.gd_pool_set_fault_counters(pool, addr, 4)
+        assert e.value.status == gd.GD_EINVAL
+    with pytest.raises(gd.GuardianError):
+        gd.gd_pool_set_fault_counters(pool, (1 << 29) + 4, 1)            # not 8-byte aligned
+    # checking needs the counters
+    with pytest.raises(gd.GuardianError) as e:
+        gd.gd_launch_fenced(pool, 0, gd.GD_K_COPY, gd.gd_args_copy(1 << 30, (1 << 30) + 4096, 4), mode=gd.GD_FENCE_CHECK)
+    assert e.value.status == gd.GD_EINVAL
+    gd.gd_pool_set_fault_counters(pool, (1 << 30) + (1 << 20), 1)        # right behind the pool is fine
+    gd.gd_pool_set_fault_counters(pool, 1 << 29, 4)
+    gd.gd_pool_destroy(pool)
 
 
 def test_launch_argument_errors_need_no_gpu():

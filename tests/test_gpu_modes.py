@@ -1,0 +1,286 @@
+"""GPU parity for the two other bounds-checking rules of Section 4.4: the modulo
+fence (partitions of any size and alignment) and address checking (an offending
+logical thread stops and is counted).  Same bars as test_gpu_parity.py; the
+fault counters must equal the oracle's violation counts exactly.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2401_09290_amd as gd
+import synth_inputs as si
+from harness import KiB, MiB, Rig, rel_frobenius
+from oracle import host_model as hm
+from oracle import kernels as ok
+
+pytestmark = pytest.mark.gpu
+
+
+class FlexRig:
+    """Device pool with partitions of arbitrary size, mirrored by the oracle."""
+
+    def __init__(self, sizes, fill=0xA5, misalign=256 * 3):
+        total = sum(sizes) + 4096
+        self.buf = torch.empty(total + misalign, dtype=torch.uint8, device="cuda")
+        self.base = self.buf.data_ptr() + misalign            # deliberately not aligned to anything large
+        self.bytes = total
+        self.dev = self.buf[misalign:misalign + total]
+        self.dev.fill_(fill)
+        self.pool = gd.gd_pool_create_flex(self.base, total, sizes)
+        self.table = hm.carve_flex(self.base, total, sizes)
+        for t, row in enumerate(self.table):
+            assert gd.gd_partition_info(self.pool, t)[:2] == row
+        self.heaps = [hm.FirstFit(b, s) for (b, s) in self.table]
+        self.sim = ok.SimPool(self.base, total, fill)
+        torch.cuda.synchronize()
+
+    def alloc(self, t, nbytes):
+        p = gd.gd_alloc(self.pool, t, nbytes)
+        assert p == self.heaps[t].alloc(nbytes)
+        return p
+
+    def upload(self, t, ptr, arr):
+        arr = np.ascontiguousarray(arr)
+        assert gd.gd_check_copy(self.pool, t, ptr, arr.nbytes) == gd.GD_OK
+        self.dev[ptr - self.base:ptr - self.base + arr.nbytes].copy_(torch.from_numpy(arr.view(np.uint8).reshape(-1)))
+        self.sim.view(ptr, arr.dtype, arr.size)[:] = arr.reshape(-1)
+
+    def download(self, ptr, dtype, count):
+        n = count * np.dtype(dtype).itemsize
+        return self.dev[ptr - self.base:ptr - self.base + n].cpu().numpy().view(dtype)
+
+    def images_equal(self, skip=()):
+        torch.cuda.synchronize()
+        got, want = self.dev.cpu().numpy().copy(), self.sim.mem.copy()
+        for (p, n) in skip:
+            got[p - self.base:p - self.base + n] = 0
+            want[p - self.base:p - self.base + n] = 0
+        return np.array_equal(got, want)
+
+    def close(self):
+        gd.gd_pool_destroy(self.pool)
+        self.buf = self.dev = self.sim = None
+        torch.cuda.empty_cache()
+
+
+def random_addresses(g, n, base, size):
+    raw = g.integers(0, 1 << 63, size=n, dtype=np.uint64) * np.uint64(2) + g.integers(0, 2, size=n, dtype=np.uint64)
+    raw[: n // 2] = np.uint64(base) + g.integers(0, 4 * size, size=n // 2, dtype=np.uint64) - np.uint64(2 * size)
+    return raw
+
+
+# ---------------------------------------------------------------------------
+# modulo fence
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("width", [1, 4, 16])
+def test_modulo_probe_agrees_with_bitwise_on_aligned_power_of_two_partitions(width):
+    r = Rig([4 * MiB, 4 * MiB])
+    try:
+        g = si.rng(6, width)
+        base, size = r.row(1)
+        n = 30000
+        raw = random_addresses(g, n, base, size)
+        src, dst = r.alloc(1, 8 * n), r.alloc(1, 8 * n)
+        r.upload(1, src, raw)
+        r.launch(1, gd.GD_K_FENCE_ADDRS, gd.gd_args_fence_addrs(dst, src, n, width, 0), mode=gd.GD_FENCE_MODULO)
+        got = r.download(dst, np.uint64, n)
+        assert np.array_equal(got, ok.fence_array(base, size, raw, width, ok.MODE_MODULO))
+        assert np.array_equal(got, ok.fence_array(base, size, raw, width, ok.MODE_BITWISE))
+    finally:
+        r.close()
+
+
+def test_modulo_fence_on_partitions_of_odd_size_and_alignment():
+    sizes = [3 * MiB + 256, 5 * MiB + 768, MiB + 256 * 17]
+    r = FlexRig(sizes)
+    try:
+        g = si.rng(6, 50)
+        for t, (base, size) in enumerate(r.table):
+            assert size & (size - 1) and base % 4096                    # neither a power of two nor page aligned
+            n = 20001
+            raw = random_addresses(g, n, base, size)
+            src, dst = r.alloc(t, 8 * n), r.alloc(t, 8 * n)
+            r.upload(t, src, raw)
+            for width in (1, 2, 4, 8, 16):
+                gd.gd_launch_fenced(r.pool, t, gd.GD_K_FENCE_ADDRS, gd.gd_args_fence_addrs(dst, src, n, width, 0), mode=gd.GD_FENCE_MODULO)
+                r.sim.run("fence_addrs", (base, size), ok.MODE_MODULO, dst, src, width, n)
+                got = r.download(dst, np.uint64, n)
+                assert np.array_equal(got, ok.fence_array(base, size, raw, width, ok.MODE_MODULO))
+                assert got.min() >= base and got.max() + width <= base + size
+            # a store loop twice as long as the partition, from a pointer in front of it: wraps, stays inside
+            gd.gd_launch_fenced(r.pool, t, gd.GD_K_STORE_TID, gd.gd_args_store_tid(base - 1000 * 4, 2 * size // 4, 40 + t, 0), mode=gd.GD_FENCE_MODULO)
+            r.sim.run("store_tid", (base, size), ok.MODE_MODULO, base - 1000 * 4, 40 + t, 2 * size // 4)
+            assert r.images_equal(), f"tenant {t}"
+        # arithmetic kernels through pointers that are off by whole partitions
+        t = 1
+        base, size = r.table[t]
+        n = 100003
+        bufs = [base + k * 512 * KiB for k in range(6)]
+        a, b, c, idx, out = bufs[0], bufs[1], bufs[2], bufs[3], bufs[5]      # idx (8 bytes per element) takes two slots
+        r.upload(t, b, si.uniform_f32(g, n))
+        r.upload(t, c, si.uniform_f32(g, n))
+        gd.gd_launch_fenced(r.pool, t, gd.GD_K_TRIAD, gd.gd_args_triad(a + 3 * size, b - size, c + size, n, 0.75, 0), mode=gd.GD_FENCE_MODULO)
+        r.sim.run("triad", (base, size), ok.MODE_MODULO, a + 3 * size, b - size, c + size, 0.75, n)
+        assert rel_frobenius(r.download(a, np.float32, n), r.sim.view(a, np.float32, n)) <= 1e-5
+        assert r.images_equal(skip=[(a, 4 * n)])
+        r.upload(t, a, r.sim.view(a, np.float32, n).copy())               # wrapped loads below may read `a`: same bits on both sides
+        ix, where = si.c2_indices(g, n, n, frac=0.01, oob_hi=1 << 40)
+        img = ok.fence_array(base, size, np.uint64(b) + (4 * ix[where]).astype(np.uint64), 4, ok.MODE_MODULO)
+        ix[where[(img >= out) & (img < out + 4 * n)]] = 5                 # loads that would race with this launch's stores
+        r.upload(t, idx, ix)
+        gd.gd_launch_fenced(r.pool, t, gd.GD_K_GATHER32_I64, gd.gd_args_gather(out, b, idx, n), mode=gd.GD_FENCE_MODULO)
+        r.sim.run("gather32_i64", (base, size), ok.MODE_MODULO, out, b, idx, n)
+        assert r.sim.last[2] > 0.9 * len(where)
+        assert r.images_equal()
+    finally:
+        r.close()
+
+
+def test_modulo_mode_rmsnorm_and_gemm_match_the_oracle():
+    r = FlexRig([6 * MiB + 512, 2 * MiB + 256])
+    try:
+        g = si.rng(6, 60)
+        base, size = r.table[0]
+        rows, cols = 9, 2048
+        x, y, gain = r.alloc(0, 2 * rows * cols), r.alloc(0, 2 * rows * cols), r.alloc(0, 2 * cols)
+        r.upload(0, x, si.f32_to_bf16_bits(si.normal_f32(g, rows * cols)))
+        r.upload(0, gain, si.f32_to_bf16_bits(si.uniform_f32(g, cols, 0.5, 1.5)))
+        gd.gd_launch_fenced(r.pool, 0, gd.GD_K_RMSNORM_BF16, gd.gd_args_rmsnorm(y + size, x - size, gain, rows, cols, 1e-6, 0), mode=gd.GD_FENCE_MODULO)
+        r.sim.run("rmsnorm_bf16", (base, size), ok.MODE_MODULO, y + size, x - size, gain, rows, cols, 1e-6)
+        got, want = r.download(y, np.uint16, rows * cols), r.sim.view(y, np.uint16, rows * cols)
+        assert rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want)) <= 1e-3
+        for (M, N, K) in ((256, 256, 128), (100, 72, 40)):
+            A, B, Cc = r.alloc(0, 2 * M * K), r.alloc(0, 2 * K * N), r.alloc(0, 2 * M * N)
+            r.upload(0, A, si.f32_to_bf16_bits(si.normal_f32(g, M * K) * np.float32(K ** -0.5)))
+            r.upload(0, B, si.f32_to_bf16_bits(si.normal_f32(g, K * N)))
+            gd.gd_launch_fenced(r.pool, 0, gd.GD_K_GEMM_BF16, gd.gd_args_gemm(Cc, A + size, B - 2 * size, M, N, K, 1), mode=gd.GD_FENCE_MODULO)
+            r.sim.run("gemm_bf16", (base, size), ok.MODE_MODULO, Cc, A + size, B - 2 * size, M, N, K, 1, 0, M, 0, N)
+            got, want = r.download(Cc, np.uint16, M * N), r.sim.view(Cc, np.uint16, M * N)
+            assert rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want)) <= 1e-3
+        # nothing outside tenant 0's partition changed
+        lo = r.table[1][0] - r.base
+        assert np.all(r.dev[lo:].cpu().numpy() == 0xA5)
+    finally:
+        r.close()
+
+
+# ---------------------------------------------------------------------------
+# address checking
+# ---------------------------------------------------------------------------
+
+@pytest.fixture()
+def checked():
+    r = Rig([4 * MiB, 4 * MiB])
+    counters = torch.zeros(8, dtype=torch.int64, device="cuda")
+    gd.gd_pool_set_fault_counters(r.pool, counters.data_ptr(), 8)
+    yield r, counters
+    r.close()
+
+
+def faults(counters, tenant):
+    torch.cuda.synchronize()
+    return int(counters[tenant].item())
+
+
+def test_checking_stops_exactly_the_offending_threads_and_counts_them(checked):
+    r, counters = checked
+    (b0, s0), (b1, s1) = r.row(0), r.row(1)
+    total = {0: 0, 1: 0}
+    # stores that run over the end of partition 0, or start in front of partition 1
+    for tenant, A, n in ((0, b0 + s0 - 4096, 5000), (1, b1 - 400, 300), (0, b0 + 64, 100), (1, b0, 50)):
+        r.launch(tenant, gd.GD_K_STORE_TID, gd.gd_args_store_tid(A, n, 7 + tenant, 0), mode=gd.GD_FENCE_CHECK)
+        r.oracle("store_tid", tenant, A, 7 + tenant, n, mode=ok.MODE_CHECK)
+        total[tenant] += r.sim.last[1]
+        assert faults(counters, tenant) == total[tenant]
+        r.assert_images_equal(what="checked store_tid")
+    assert total[0] == 5000 - 1024 and total[1] == 100 + 50
+
+    # triad whose arrays straddle the end of the partition: vectors that cross are redone by element
+    g = si.rng(6, 70)
+    n = 40000
+    for shift in (0, 4):
+        a = b0 + s0 - 4 * 30000 + shift                  # last 10000 stores fall outside
+        b, c = r.alloc(0, 4 * n + 64) + shift, r.alloc(0, 4 * n + 64) + (shift and 12)
+        r.upload(0, b, si.uniform_f32(g, n))
+        r.upload(0, c, si.uniform_f32(g, n))
+        r.launch(0, gd.GD_K_TRIAD, gd.gd_args_triad(a, b, c, n, 0.5, 0), mode=gd.GD_FENCE_CHECK)
+        r.oracle("triad", 0, a, b, c, 0.5, n, mode=ok.MODE_CHECK)
+        assert r.sim.last[1] == 10000 + (1 if shift else 0)
+        total[0] += r.sim.last[1]
+        assert faults(counters, 0) == total[0]
+        inb = 30000 - (1 if shift else 0)
+        assert rel_frobenius(r.download(a, np.float32, inb), r.sim.view(a, np.float32, inb)) <= 1e-5
+        r.assert_images_equal(skip=[(a, 4 * inb)], what="checked triad")
+        r.launch(0, gd.GD_K_COPY, gd.gd_args_copy(b, c - 4 * n - 4 * MiB, n), mode=gd.GD_FENCE_CHECK)     # every load refused
+        r.oracle("copy", 0, b, c - 4 * n - 4 * MiB, n, mode=ok.MODE_CHECK)
+        total[0] += n
+        assert r.sim.last[1] == n and faults(counters, 0) == total[0]
+        r.assert_images_equal(skip=[(a, 4 * inb)], what="checked copy")
+
+
+def test_checking_on_indexed_kernels_and_sum(checked):
+    r, counters = checked
+    t = 1
+    base, size = r.row(t)
+    g = si.rng(6, 80)
+    n = 120003
+    x, y, off, out = (r.alloc(t, 4 * n + 64) for _ in range(4))
+    r.upload(t, x, si.uniform_f32(g, n))
+    r.upload(t, y, si.uniform_f32(g, n))
+    offs, where = si.c1_offsets(g, n, y, base, size, frac=0.02)
+    r.upload(t, off, offs)
+    total = 0
+    r.launch(t, gd.GD_K_SAXPY_IDX, gd.gd_args_saxpy_idx(x, y, off, n, 0.25, 0), mode=gd.GD_FENCE_CHECK)
+    r.oracle("saxpy_idx", t, x, y, off, 0.25, n, mode=ok.MODE_CHECK)
+    total += r.sim.last[1]
+    assert r.sim.last[1] == len(where) and faults(counters, t) == total
+    assert rel_frobenius(r.download(y, np.float32, n), r.sim.view(y, np.float32, n)) <= 1e-5
+    r.assert_images_equal(skip=[(y, 4 * n)], what="checked saxpy")
+    # refused elements keep their old value bit for bit
+    assert np.array_equal(r.download(y, np.uint32, n)[where], r.sim.view(y, np.uint32, n)[where])
+
+    idx = r.alloc(t, 8 * n)
+    ix, where = si.c2_indices(g, n, n, frac=0.01, oob_hi=1 << 34)
+    ix[where[::2]] *= -1
+    inside = (x + 4 * ix[where] >= base) & (x + 4 * ix[where] + 4 <= base + size)
+    r.upload(t, idx, ix)
+    r.dview(out, np.uint8, 4 * n).fill_(0x11)
+    r.sim.view(out, np.uint8, 4 * n)[:] = 0x11
+    r.launch(t, gd.GD_K_GATHER32_I64, gd.gd_args_gather(out, x, idx, n), mode=gd.GD_FENCE_CHECK)
+    r.oracle("gather32_i64", t, out, x, idx, n, mode=ok.MODE_CHECK)
+    total += r.sim.last[1]
+    assert r.sim.last[1] == int((~inside).sum()) and faults(counters, t) == total
+    racy = where[inside]                                  # in-partition but outside the table: may read `out`/`y`
+    keep = np.ones(n, bool)
+    keep[racy] = False
+    assert np.array_equal(r.download(out, np.uint32, n)[keep], r.sim.view(out, np.uint32, n)[keep])
+    assert np.all(r.download(out, np.uint32, n)[where[~inside]] == 0x11111111)
+
+    r.launch(t, gd.GD_K_SCATTER_F32_I64, gd.gd_args_scatter(y, x, idx, n, 2.0, 0), mode=gd.GD_FENCE_CHECK)
+    r.oracle("scatter_f32_i64", t, y, x, idx, 2.0, n, mode=ok.MODE_CHECK)
+    total += r.sim.last[1]
+    assert faults(counters, t) == total
+
+    # sum over a range that runs past the end of the partition: the part inside is summed, the rest counted
+    ws, res = r.alloc(t, gd.GD_SUM_WORKSPACE), r.alloc(t, 256)
+    m = 50000
+    start = base + size - 4 * 30000
+    r.upload(t, start, si.uniform_f32(g, 30000, 0.0, 1.0))
+    r.launch(t, gd.GD_K_SUM_F32, gd.gd_args_sum(res, start, ws, m), mode=gd.GD_FENCE_CHECK)
+    exact = r.oracle("sum_f32_exact", t, start, m, mode=ok.MODE_CHECK)
+    assert r.sim.last[1] == 20000
+    total += 20000
+    assert faults(counters, t) == total
+    assert abs(float(r.download(res, np.float32, 1)[0]) - exact) <= 1e-5 * exact
+    assert faults(counters, 0) == 0
+
+
+def test_checking_is_not_built_for_rmsnorm_and_gemm(checked):
+    r, _ = checked
+    base, _ = r.row(0)
+    for kid, args in ((gd.GD_K_RMSNORM_BF16, gd.gd_args_rmsnorm(base, base + 4096, base + 8192, 1, 64, 1e-6, 0)),
+                      (gd.GD_K_GEMM_BF16, gd.gd_args_gemm(base, base + 65536, base + 131072, 16, 16, 16, 1))):
+        with pytest.raises(gd.GuardianError) as e:
+            r.launch(0, kid, args, mode=gd.GD_FENCE_CHECK)
+        assert e.value.status == gd.GD_ENOKERNEL

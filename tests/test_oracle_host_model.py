@@ -103,6 +103,37 @@ def test_unaligned_base_would_alter_in_bounds_addresses():
         hm.fence(inside, base, size)
 
 
+def test_modulo_fence_with_width_keeps_whole_access_inside_odd_partitions():
+    # Section 4.4: no power of two, no alignment.  Brute force on small odd partitions.
+    for base, size in ((256 * 7, 256 * 3), (256 * 100, 256 * 17), (4096, 4096)):
+        inside = set(range(base, base + size))
+        for a in range(base - 2 * size, base + 3 * size, 3):
+            for w in hm.ACCESS_WIDTHS:
+                f = hm.fence_modulo(a, base, size, w)
+                assert all(q in inside for q in (f, f + w - 1))
+                if a % w == 0 and a in inside and a + w - 1 in inside:
+                    assert f == a
+                if a >= base:
+                    assert (f - (a - a % w)) % size == 0 or (a - base) % size % w != 0
+
+
+def test_carve_flex_is_disjoint_ordered_and_inside():
+    rnd = random.Random(2)
+    for _ in range(300):
+        sizes = [256 * rnd.randint(16, 400) for _ in range(rnd.randint(1, 8))]
+        pool_base = 256 * rnd.randint(1, 1000) + rnd.choice([0, 8])
+        table = hm.carve_flex(pool_base, sum(sizes) + 256, sizes)
+        assert table is not None
+        owner = {}
+        for t, (b, s) in enumerate(table):
+            assert s == sizes[t] and b % 256 == 0 and pool_base <= b and b + s <= pool_base + sum(sizes) + 256
+            for a in range(b, b + s, 256):
+                assert a not in owner
+                owner[a] = t
+        assert [b for b, _ in table] == sorted(b for b, _ in table)      # tenant order = address order
+        assert hm.carve_flex(pool_base, sum(sizes) - 256, sizes) is None
+
+
 def test_fence_on_64bit_extremes():
     base, size = 0x7FA2D0000000, 1 << 24
     for a in (0, hm.U64, 1 << 63, 0xFFFF_FFFF_0000_0000, 0x0000_0000_FFFF_FFFF):
