@@ -37,7 +37,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--configs", default="c3,c4,c2,c1,c5", help="comma list out of c1..c5 (c3 is the headline)")
+    ap.add_argument("--configs", default="c3,c4,c2,c1,c5,modes",
+                    help="comma list out of c1..c5 (c3 is the headline) and modes (the paper's three rules side by side)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--prewarm-ms", type=float, default=250.0,
                     help="untimed launches in front of every measurement until this much GPU time has passed "
@@ -441,6 +442,73 @@ def run_c5(torch, gd, si, args):
 
 
 # ---------------------------------------------------------------------------------
+# the paper's three bounds-checking rules side by side; cache-resident regime; host path
+# ---------------------------------------------------------------------------------
+
+def run_modes(torch, gd, si, args):
+    """Section 4.4 / 7.2 ordering (native < bitwise < modulo < checking) and the
+    Section 7.4 question (what the fence costs when data sit in cache), on one
+    tenant with a 4 GiB partition; Section 7.6's host-side costs per call."""
+    log("[modes] none / bitwise / modulo / checking on one tenant")
+    dp = DevPool(torch, gd, [4 * GiB])
+    counters = torch.zeros(4, dtype=torch.int64, device="cuda")
+    gd.gd_pool_set_fault_counters(dp.pool, counters.data_ptr(), 4)
+    st = torch.cuda.Stream()
+    g = si.rng(6, 0)
+    modes = (("none", gd.GD_FENCE_NONE), ("bitwise", gd.GD_FENCE_BITWISE), ("modulo", gd.GD_FENCE_MODULO), ("check", gd.GD_FENCE_CHECK))
+    res = {"workload": "1 tenant, 4 GiB partition, all accesses in bounds: fp32 triad 2^26 (HBM resident), triad 2^22 repeated 200 times inside one launch (each workgroup re-reads its own 12 KiB: cache resident), gather 2^24 with int64 indices"}
+
+    def sweep(label, kid, kargs, nbytes, reps):
+        out = {}
+        for name, mode in modes:
+            sec = solo_avg_seconds(torch, st, lambda: gd.gd_launch_fenced(dp.pool, 0, kid, kargs, stream=st.cuda_stream, mode=mode), reps)
+            out[name + "_GBps"] = nbytes / sec / 1e9
+            out[name + "_us"] = sec * 1e6
+        for name, _ in modes[1:]:
+            out[name + "_overhead_pct"] = pct_overhead(out[name + "_GBps"], out["none_GBps"])
+        log(f"[modes] {label}: " + ", ".join(f"{n} {out[n + '_us']:.2f} us" for n, _ in modes)
+            + " | overhead " + ", ".join(f"{n} {out[n + '_overhead_pct']:+.1f} %" for n, _ in modes[1:]))
+        res[label] = out
+
+    n = 1 << 26
+    a, b, c = (dp.alloc(0, 4 * n) for _ in range(3))
+    host = np.empty(n, np.float32)
+    for ptr, part in ((b, 1), (c, 2)):
+        si.fill_chunked(host, 6, part, "uniform", threads=16)
+        dp.upload(0, ptr, host)
+    sweep("triad_hbm_2^26", gd.GD_K_TRIAD, gd.gd_args_triad(a, b, c, n, 0.5, 0), 12 * n, args.steps)
+    small, repeat = 1 << 22, 200                                    # 48 MiB working set, swept 200 times per launch
+    sweep("triad_cache_resident_2^22_x200", gd.GD_K_TRIAD, gd.gd_args_triad(a, b, c, small, 0.5, repeat), 12 * small * repeat, args.steps)
+    ng = 1 << 24
+    idx = dp.alloc(0, 8 * ng)
+    dp.upload(0, idx, g.integers(0, n, size=ng, dtype=np.int64))
+    sweep("gather_i64_2^24", gd.GD_K_GATHER32_I64, gd.gd_args_gather(a, b, idx, ng), 16 * ng, args.steps)
+    res["check_faults_counted"] = int(counters.sum().item())       # all accesses were in bounds: must be 0
+
+    # host path, per call, Python binding included (the trivial call shows the binding's own share)
+    def per_call_ns(fn, reps=20000):
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        return (time.perf_counter() - t0) / reps * 1e9
+    torch.cuda.synchronize()
+    kargs = gd.gd_args_store_tid(a, 0, 1, 0)                        # n = 0: lookup + augmentation, no launch
+    host_ns = {
+        "binding_trivial_call": per_call_ns(lambda: gd.gd_kernel_count()),
+        "gd_check_copy": per_call_ns(lambda: gd.gd_check_copy(dp.pool, 0, a, 4096)),
+        "gd_alloc_plus_gd_free": per_call_ns(lambda: gd.gd_free(dp.pool, 0, gd.gd_alloc(dp.pool, 0, 4096))),
+        "gd_launch_fenced_lookup_and_augmentation_only": per_call_ns(lambda: gd.gd_launch_fenced(dp.pool, 0, gd.GD_K_STORE_TID, kargs, stream=st.cuda_stream)),
+    }
+    kargs1 = gd.gd_args_store_tid(a, 64, 1, 0)
+    host_ns["gd_launch_fenced_with_launch"] = per_call_ns(lambda: gd.gd_launch_fenced(dp.pool, 0, gd.GD_K_STORE_TID, kargs1, stream=st.cuda_stream), 5000)
+    torch.cuda.synchronize()
+    res["host_ns_per_call"] = {k: round(v, 1) for k, v in host_ns.items()}
+    log("[modes] host ns per call: " + ", ".join(f"{k} {v:.0f}" for k, v in host_ns.items()))
+    dp.close()
+    return res
+
+
+# ---------------------------------------------------------------------------------
 # CPU baseline: the oracle as it stands, one tenant's share of a round
 # ---------------------------------------------------------------------------------
 
@@ -491,7 +559,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
-    runners = {"c1": run_c1, "c2": run_c2, "c3": run_c3, "c4": run_c4, "c5": run_c5}
+    runners = {"c1": run_c1, "c2": run_c2, "c3": run_c3, "c4": run_c4, "c5": run_c5, "modes": run_modes}
     wanted = [c.strip() for c in args.configs.split(",") if c.strip()]
     per = {}
     for c in wanted:

@@ -144,7 +144,9 @@ typedef enum {
 typedef struct { uint64_t A; uint64_t n; uint32_t j; uint32_t pad; } gd_args_store_tid;
 typedef struct { uint64_t out; uint64_t in; uint64_t n; uint32_t width; uint32_t pad; } gd_args_fence_addrs;
 typedef struct { uint64_t a; uint64_t b; uint64_t n; } gd_args_copy;
-typedef struct { uint64_t a; uint64_t b; uint64_t c; uint64_t n; float s; uint32_t pad; } gd_args_triad;
+/* repeat: the whole operation is performed max(repeat, 1) times (same result; lets a caller keep a
+ * small working set cache resident inside one launch, Section 7.4's regime). */
+typedef struct { uint64_t a; uint64_t b; uint64_t c; uint64_t n; float s; uint32_t repeat; } gd_args_triad;
 typedef struct { uint64_t x; uint64_t y; uint64_t off; uint64_t n; float alpha; uint32_t pad; } gd_args_saxpy_idx;
 typedef struct { uint64_t out; uint64_t tab; uint64_t idx; uint64_t n; } gd_args_gather;
 typedef struct { uint64_t dst; uint64_t src; uint64_t idx; uint64_t n; float scale; uint32_t pad; } gd_args_scatter;

@@ -31,7 +31,7 @@ def _struct(name, fields):
 gd_args_store_tid = _struct("gd_args_store_tid", [("A", _u64), ("n", _u64), ("j", _u32), ("pad", _u32)])
 gd_args_fence_addrs = _struct("gd_args_fence_addrs", [("out", _u64), ("in_", _u64), ("n", _u64), ("width", _u32), ("pad", _u32)])
 gd_args_copy = _struct("gd_args_copy", [("a", _u64), ("b", _u64), ("n", _u64)])
-gd_args_triad = _struct("gd_args_triad", [("a", _u64), ("b", _u64), ("c", _u64), ("n", _u64), ("s", _f32), ("pad", _u32)])
+gd_args_triad = _struct("gd_args_triad", [("a", _u64), ("b", _u64), ("c", _u64), ("n", _u64), ("s", _f32), ("repeat", _u32)])
 gd_args_saxpy_idx = _struct("gd_args_saxpy_idx", [("x", _u64), ("y", _u64), ("off", _u64), ("n", _u64), ("alpha", _f32), ("pad", _u32)])
 gd_args_gather = _struct("gd_args_gather", [("out", _u64), ("tab", _u64), ("idx", _u64), ("n", _u64)])
 gd_args_scatter = _struct("gd_args_scatter", [("dst", _u64), ("src", _u64), ("idx", _u64), ("n", _u64), ("scale", _f32), ("pad", _u32)])

@@ -97,7 +97,8 @@ struct Fence {
     __device__ __forceinline__ void fault() const
     {
         if constexpr (V == V_CHECK)
-            atomicAdd((unsigned long long *)(faults + 8 * (uint64_t)tenant), 1ULL);
+            __hip_atomic_fetch_add((GD_GLOBAL unsigned long long *)(faults + 8 * (uint64_t)tenant), 1ULL,
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 
     // The fenced address of a W-byte access to `raw` (what the probe kernel reports).

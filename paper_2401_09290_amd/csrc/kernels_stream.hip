@@ -61,9 +61,10 @@ __global__ __launch_bounds__(1024) void k_fence_addrs(gd_args_fence_addrs p, Fen
 // logical threads stop.
 template <int V, int OP>
 __global__ __launch_bounds__(1024) void k_stream(uint64_t pa, uint64_t pb, uint64_t pc, uint64_t n,
-                                                 float s, FenceArgs fa)
+                                                 float s, uint32_t repeat, FenceArgs fa)
 {
     const Fence<V> F(fa);
+  for (uint32_t rep = 0; rep < repeat; ++rep) {      // repeat > 1: the cache-resident regime in one launch
     // one logical thread: accesses in the order load b, load c, store a
     auto element = [&](uint64_t i) {
         if (!F.template inside<4>(pb + 4 * i)) { F.fault(); return; }
@@ -108,6 +109,7 @@ __global__ __launch_bounds__(1024) void k_stream(uint64_t pa, uint64_t pb, uint6
         const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
         for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) element(i);
     }
+  }
 }
 
 // ---- launchers -------------------------------------------------------------------
@@ -159,7 +161,7 @@ int launch_copy(const void *args, const FenceArgs &f, int variant, const Shape &
     uint32_t grid, block;
     if (!pick_1d(shape, b0 ? stream_tiles(p.n, b0) : 1, 256, &grid, &block)) return GD_EINVAL;
     if (p.n == 0) return GD_OK;
-    GD_STREAM_LAUNCH(variant, 0, dim3(grid), dim3(block), stream, p.a, p.b, (uint64_t)0, p.n, 0.0f, f);
+    GD_STREAM_LAUNCH(variant, 0, dim3(grid), dim3(block), stream, p.a, p.b, (uint64_t)0, p.n, 0.0f, 1u, f);
     GD_CHECK_LAUNCH();
     return GD_OK;
 }
@@ -171,7 +173,7 @@ int launch_triad(const void *args, const FenceArgs &f, int variant, const Shape 
     uint32_t grid, block;
     if (!pick_1d(shape, b0 ? stream_tiles(p.n, b0) : 1, 256, &grid, &block)) return GD_EINVAL;
     if (p.n == 0) return GD_OK;
-    GD_STREAM_LAUNCH(variant, 1, dim3(grid), dim3(block), stream, p.a, p.b, p.c, p.n, p.s, f);
+    GD_STREAM_LAUNCH(variant, 1, dim3(grid), dim3(block), stream, p.a, p.b, p.c, p.n, p.s, p.repeat ? p.repeat : 1u, f);
     GD_CHECK_LAUNCH();
     return GD_OK;
 }
