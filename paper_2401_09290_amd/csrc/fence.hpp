@@ -167,6 +167,30 @@ struct Fence {
             __builtin_amdgcn_global_load_lds((const GD_GLOBAL void *)h, lds_base, 16, 0, 0);
     }
 
+    // The same copy as an instruction the compiler does not model.  The compiler
+    // orders every LDS read it cannot tell apart from an earlier global -> LDS copy
+    // behind s_waitcnt vmcnt(0), which drains a software pipeline that keeps copies
+    // in flight across basic blocks.  Issued this way the copy is invisible to that
+    // bookkeeping: the caller owns the s_waitcnt vmcnt and the workgroup barrier
+    // between the copy and the first read of its data.  `lds_addr` is the
+    // wave-uniform LDS byte address lane 0 lands at; M0 carries it (one wait state
+    // between the write of M0 and the copy).  M0 is a reserved register the compiler
+    // does not track through inline asm: use this only in kernels where nothing else
+    // depends on M0 (no compiler-issued LDS copies, no indexed register moves).
+    __device__ __forceinline__ void dma16_unordered(Handle h, uint32_t lds_addr) const
+    {
+        if constexpr (V == V_BIT32)
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(lds_addr), "v"(h), "s"(base)
+                         : "memory");
+        else
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                         :
+                         : "s"(lds_addr), "v"(h)
+                         : "memory");
+    }
+
     // Fenced global -> LDS copy of 16 bytes per lane (global_load_lds_dwordx4): the
     // global side takes the fenced address, the LDS side (wave-uniform base; lane i
     // lands at base + 16*i) is not tenant-addressable.

@@ -372,13 +372,26 @@ void k_gemm_dma(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_n
 }
 
 
-// ---- tiled MFMA kernel, four-stage ring of K=32 slices ---------------------------------------
+// ---- tiled MFMA kernel, five-stage ring of K=32 slices -----------------------------------------
 // Same 256 x 256 tile and wavefront layout as k_gemm_dma, but K advances in
-// slices of 32 through a ring of four 32 KiB LDS stages (A 256x32 + B 256x32):
-// the slice of step t+3 is requested while step t computes, so a DMA has three
-// steps to land and about 64 KiB per CU stay in flight all the time.  LDS rows
-// are 64 bytes; granule g of row r sits in slot g ^ ((r/4) & 3), which spreads 16
-// consecutive rows of one granule column over all 64 banks.
+// slices of 32 through a ring of five 32 KiB LDS stages (A 256x32 + B 256x32),
+// all 160 KiB of the compute unit.  LDS rows are 64 bytes; granule g of row r sits
+// in slot g ^ ((r/4) & 3), which spreads 16 consecutive rows of one granule column
+// over all 64 banks.
+//
+// A 64-byte row of a slice is half of a 128-byte cache line, and the L2 serves
+// one request per channel and clock whether it asks for 64 or 128 bytes.  Slices
+// are therefore requested in pairs (2j, 2j+1) whose rows together are whole lines:
+// the two DMA instructions for the halves of the same rows are issued back to
+// back, and the vector cache merges them into one 128-byte request (half the L2
+// requests per byte).
+//
+// The global -> LDS path of a compute unit delivers little more than the 32 bytes
+// per clock this tile shape consumes, and a wavefront that issues a DMA while the
+// path is backed up stalls, MFMAs included.  The 16 DMAs of a pair of slices are
+// therefore spread evenly over the two steps (32 MFMA pairs) in which both target
+// stages are free: pair (t+3, t+4), t odd, goes out between the barrier of step
+// t-1 and the barrier of step t+1, two DMAs every fourth MFMA pair.
 // Requirements: as k_gemm_dma, and K % 128 == 0.
 constexpr int RK = 32;                       // K per ring step
 constexpr int RSTAGE = (BM + BN) * RK * 2;   // 32 KiB
@@ -388,15 +401,19 @@ constexpr int RA = BM * RK * 2;              // 16 KiB: offset of the B slice in
 // 4..7 = B fragments; MFMAs run A-fragment-major): B0 A0 B1 B2 B3 A1 A2 A3.
 __device__ constexpr int FRAG_ORDER[8] = {4, 0, 5, 6, 7, 1, 2, 3};
 
-// Workgroup barrier of the ring: wait until at most 16 of this wavefront's DMA
+// Workgroup barrier of the ring: wait until at most `vm` of this wavefront's DMA
 // loads are still in flight (they complete in order, so everything older has
 // landed in LDS) and all its LDS reads have returned, then meet the other
-// wavefronts.  s_waitcnt immediate: vmcnt = 16, lgkmcnt = 0, expcnt untouched
-// (gfx9 encoding).  The empty asm statements keep the compiler from moving LDS
-// accesses across the barrier.
-#define GD_RING_BARRIER()                       \
+// wavefronts.  The argument is the s_waitcnt immediate in gfx9 encoding:
+// vmcnt[3:0] in bits 3:0 and vmcnt[5:4] in bits 15:14, expcnt (untouched, 7) in
+// bits 6:4, lgkmcnt = 0 in bits 11:8.  The empty asm statements keep the
+// compiler from moving LDS accesses across the barrier.
+#define GD_WAIT_VM8 0x0078      // vmcnt <= 8
+#define GD_WAIT_VM10 0x007A     // vmcnt <= 10
+#define GD_WAIT_VM_ANY 0xC07F   // vmcnt <= 63: no constraint
+#define GD_RING_BARRIER(imm)                    \
     do {                                        \
-        __builtin_amdgcn_s_waitcnt(0x4070);     \
+        __builtin_amdgcn_s_waitcnt(imm);        \
         asm volatile("" ::: "memory");          \
         __builtin_amdgcn_s_barrier();           \
         asm volatile("" ::: "memory");          \
@@ -407,10 +424,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_n)
 {
     const Fence<V> F(fa);
+    // Separate arrays, so that the compiler can tell a fragment load from one stage
+    // apart from a DMA into another and does not wait for the DMA.
     __shared__ __attribute__((aligned(1024))) uint8_t ring0[RSTAGE];
     __shared__ __attribute__((aligned(1024))) uint8_t ring1[RSTAGE];
     __shared__ __attribute__((aligned(1024))) uint8_t ring2[RSTAGE];
     __shared__ __attribute__((aligned(1024))) uint8_t ring3[RSTAGE];
+    __shared__ __attribute__((aligned(1024))) uint8_t ring4[RSTAGE];
 
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & 63;
@@ -428,20 +448,25 @@ void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_
 
     // One DMA instruction fills 1 KiB = 16 slice rows; lane l lands in row l/4, slot
     // l%4, and fetches granule (l%4) ^ ((row/4) & 3) = (l%4) ^ ((l/16) & 3).  Wavefront
-    // w moves rows [64w, 64w+64) of A and of B: 4 + 4 instructions per step.
+    // w moves rows [64w, 64w+64) of A and of B.  DMA number d of a pair of slices:
+    // d/2 = operand and 16-row chunk (0..3 A, 4..7 B), d%2 = slice of the pair, so the
+    // two halves of the same cache lines are neighbours in issue order.
     const uint32_t drow = wave * 64 + (lane >> 2);
     const uint32_t dgran = (lane & 3) ^ ((lane >> 4) & 3);
     const uint64_t a_lane = p.A + 2 * ((uint64_t)(m0 + drow) * p.K + dgran * 8);
     const uint64_t b_lane = p.B + 2 * ((uint64_t)(n0 + drow) * p.K + dgran * 8);
     const uint64_t chunk_step = 2 * 16 * (uint64_t)p.K;      // 16 rows further down
-    typename Fence<V>::Handle pre[8];                      // fenced addresses of the next step's 8 DMAs
-    auto pre_one = [&](uint32_t k0, int c) {
-        const uint64_t uni = (c & 3) * chunk_step + 2 * (uint64_t)k0;
-        pre[c] = F.template fenced<16>(c < 4 ? a_lane : b_lane, uni);
+    typename Fence<V>::Handle pre[16];                     // fenced addresses of the next pair's 16 DMAs
+    auto pre_one = [&](uint32_t k0, int d) {
+        const int c = d >> 1;
+        const uint64_t uni = (c & 3) * chunk_step + 2 * (uint64_t)k0 + (d & 1) * (2 * RK);
+        pre[d] = F.template fenced<16>(c < 4 ? a_lane : b_lane, uni);
     };
-    auto dma_one = [&](uint8_t *stage, int c) {
+    auto dma_one = [&](uint8_t *stage_even, uint8_t *stage_odd, int d) {
+        const int c = d >> 1;
+        uint8_t *stage = (d & 1) ? stage_odd : stage_even;
         GD_LDS uint8_t *dst = (GD_LDS uint8_t *)stage + wave * 4096 + (c & 3) * 1024 + (c < 4 ? 0 : RA);
-        F.dma16(pre[c], dst);
+        F.dma16_unordered(pre[d], (uint32_t)(uintptr_t)dst);
     };
 
     f32x16 acc[TM][TN];
@@ -471,64 +496,102 @@ void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_
         for (int e = 2 * q; e < 2 * q + 2; ++e)
             acc[e / TN][e % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb_[e % TN], fa_[e / TN], acc[e / TN][e % TN], 0, 0, 0);
     };
-    // One ring step.  In: substep-0 fragments of `cur` in fa0/fb0.  Out: substep-0
-    // fragments of `nxt` in fa0/fb0.  `refill` is the stage read one step ago.
-    // `k_after` is the slice the FOLLOWING step will request: its fenced addresses are
-    // computed here, in the shadow of MFMAs, so the DMA issue never waits for them.
-    auto step = [&](const uint8_t *cur, const uint8_t *nxt, uint8_t *refill, uint32_t k_after) {
+    // DMA pair number pr (0..7) of a pair of slices: operand and 16-row chunk pr,
+    // both halves.  The fenced addresses are computed before the MFMA pair of the
+    // slot, the DMAs go out after it.
+    auto pre_pair = [&](uint32_t k_pair, int pr) {
+        pre_one(k_pair, 2 * pr);
+        pre_one(k_pair, 2 * pr + 1);
+    };
+    auto dma_pair = [&](uint8_t *stage_even, uint8_t *stage_odd, int pr) {
+        dma_one(stage_even, stage_odd, 2 * pr);
+        dma_one(stage_even, stage_odd, 2 * pr + 1);
+    };
+    // One ring step of 16 slots, one MFMA pair each.  In: substep-0 fragments of `cur`
+    // in fa0/fb0.  Out: substep-0 fragments of `nxt` in fa0/fb0.  LDS serves the
+    // fragment loads of four wavefronts and the DMA writes at about three quarters of
+    // its bandwidth, so the loads are spread out: the 8 substep-1 fragments of `cur`
+    // one per slot in slots 0..7 (first needed in slot 8), the 8 substep-0 fragments
+    // of `nxt` behind the barrier, two per slot in slots 10..13 (all back before the
+    // next step starts).  Slots 0, 4 and 8 carry DMA pairs
+    // p0, p0+1, p0+2 of the slice pair (ea, oa, ka); slot 12 carries DMA pair p3 of the
+    // slice pair (eb, ob, kb).  An odd step t sends DMA pairs 1..4 of slices (t+3, t+4);
+    // an even step t sends pairs 5..7 of slices (t+2, t+3) and pair 0 of slices
+    // (t+4, t+5), whose second stage is the one this step has just finished reading.
+    auto step = [&](const uint8_t *cur, const uint8_t *nxt, bool odd, uint8_t *ea, uint8_t *oa, uint32_t ka,
+                    uint8_t *eb, uint8_t *ob, uint32_t kb) {
+        const int p0 = odd ? 1 : 5, p3 = odd ? 4 : 0;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {                    // substep 0
-            if (q < 4) {
-                frag_one(cur, 1, FRAG_ORDER[2 * q], fa1, fb1);
-                frag_one(cur, 1, FRAG_ORDER[2 * q + 1], fa1, fb1);
+        for (int sl = 0; sl < 16; ++sl) {
+            if (sl == 10) {
+                // Odd step t: slice t+1 must have landed, i.e. everything but the 4 DMA
+                // pairs sent since the previous odd barrier.  Even step: `nxt` landed a
+                // step ago; the barrier only releases the stage of `cur` for refilling.
+                if (odd) GD_RING_BARRIER(GD_WAIT_VM8);
+                else GD_RING_BARRIER(GD_WAIT_VM_ANY);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            dma_one(refill, q);
-            mfma_pair(q, fa0, fb0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {                    // substep 1, first half
-            pre_one(k_after, 2 * q);
-            pre_one(k_after, 2 * q + 1);
-            mfma_pair(q, fa1, fb1);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        GD_RING_BARRIER();                               // 16 DMAs may stay in flight: `nxt` is older
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int q = 4; q < 8; ++q) {                    // substep 1, second half
-            if (q < 6) {
-#pragma unroll
-                for (int f = 0; f < 4; ++f) frag_one(nxt, 0, FRAG_ORDER[4 * (q - 4) + f], fa0, fb0);
+            if (sl < 8) frag_one(cur, 1, FRAG_ORDER[sl], fa1, fb1);
+            if (sl >= 10 && sl < 14) {
+                frag_one(nxt, 0, FRAG_ORDER[2 * (sl - 10)], fa0, fb0);
+                frag_one(nxt, 0, FRAG_ORDER[2 * (sl - 10) + 1], fa0, fb0);
             }
-            mfma_pair(q, fa1, fb1);
+            if (sl == 0 || sl == 4 || sl == 8) pre_pair(ka, p0 + sl / 4);
+            if (sl == 12) pre_pair(kb, p3);
+            if (sl < 8) mfma_pair(sl, fa0, fb0);
+            else mfma_pair(sl - 8, fa1, fb1);
+            if (sl == 0 || sl == 4 || sl == 8) dma_pair(ea, oa, p0 + sl / 4);
+            if (sl == 12) dma_pair(eb, ob, p3);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
 
     const uint32_t ksteps = p.K / RK;                    // multiple of 4
-    const uint32_t k_last = p.K - RK;
-    auto clamp_k = [&](uint32_t k) { return k < k_last ? k : k_last; };   // past the end: refetch the last slice, unused
+    const uint32_t k_last = p.K - 2 * RK;
+    auto clamp_k = [&](uint32_t k) { return k < k_last ? k : k_last; };   // past the end: refetch the last pair, unused
 #pragma unroll
-    for (int s3 = 0; s3 < 3; ++s3) {
-#pragma unroll
-        for (int c = 0; c < 8; ++c) {
-            pre_one(s3 * RK, c);
-            dma_one(s3 == 0 ? ring0 : s3 == 1 ? ring1 : ring2, c);
-        }
+    for (int pr = 0; pr < 8; ++pr) {                     // slices 0 and 1
+        pre_pair(0, pr);
+        dma_pair(ring0, ring1, pr);
     }
 #pragma unroll
-    for (int c = 0; c < 8; ++c) pre_one(clamp_k(3 * RK), c);
-    GD_RING_BARRIER();
+    for (int pr = 0; pr < 5; ++pr) {                     // slices 2 and 3, DMA pairs 0..4
+        pre_pair(clamp_k(2 * RK), pr);
+        dma_pair(ring2, ring3, pr);
+    }
+    GD_RING_BARRIER(GD_WAIT_VM10);                       // slices 0 and 1 have landed
 #pragma unroll
     for (int q = 0; q < 8; ++q) frag_one(ring0, 0, FRAG_ORDER[q], fa0, fb0);
-    for (uint32_t t = 0; t < ksteps; t += 4) {
-        const uint32_t k4 = (t + 4) * RK;
-        step(ring0, ring1, ring3, clamp_k(k4));
-        step(ring1, ring2, ring0, clamp_k(k4 + RK));
-        step(ring2, ring3, ring1, clamp_k(k4 + 2 * RK));
-        step(ring3, ring0, ring2, clamp_k(k4 + 3 * RK));
+    // Slice s lives in stage s % 5 and the DMA pattern has period 2, so the code
+    // repeats every 10 steps; K % 128 == 0 lets the loop end after any odd step.
+    for (uint32_t t = 0; t < ksteps;) {
+        step(ring0, ring1, false, ring2, ring3, clamp_k((t + 2) * RK), ring4, ring0, clamp_k((t + 4) * RK));
+        step(ring1, ring2, true, ring4, ring0, clamp_k((t + 4) * RK), ring4, ring0, clamp_k((t + 4) * RK));
+        t += 2;
+        if (t < ksteps) {
+            step(ring2, ring3, false, ring4, ring0, clamp_k((t + 2) * RK), ring1, ring2, clamp_k((t + 4) * RK));
+            step(ring3, ring4, true, ring1, ring2, clamp_k((t + 4) * RK), ring1, ring2, clamp_k((t + 4) * RK));
+            t += 2;
+        }
+        if (t < ksteps) {
+            step(ring4, ring0, false, ring1, ring2, clamp_k((t + 2) * RK), ring3, ring4, clamp_k((t + 4) * RK));
+            step(ring0, ring1, true, ring3, ring4, clamp_k((t + 4) * RK), ring3, ring4, clamp_k((t + 4) * RK));
+            t += 2;
+        }
+        if (t < ksteps) {
+            step(ring1, ring2, false, ring3, ring4, clamp_k((t + 2) * RK), ring0, ring1, clamp_k((t + 4) * RK));
+            step(ring2, ring3, true, ring0, ring1, clamp_k((t + 4) * RK), ring0, ring1, clamp_k((t + 4) * RK));
+            t += 2;
+        }
+        if (t < ksteps) {
+            step(ring3, ring4, false, ring0, ring1, clamp_k((t + 2) * RK), ring2, ring3, clamp_k((t + 4) * RK));
+            step(ring4, ring0, true, ring2, ring3, clamp_k((t + 4) * RK), ring2, ring3, clamp_k((t + 4) * RK));
+            t += 2;
+        }
     }
+    // The compiler does not know of the ring's DMAs: wait for the last ones by hand
+    // (vmcnt = 0, lgkmcnt = 0) before the stages are reused to park the result.
+    __builtin_amdgcn_s_waitcnt(0x0070);
     __syncthreads();                                     // every DMA has landed, every fragment is read
 
     // Epilogue.  The MFMAs take the B fragment as their row operand, so acc[i][j][r]

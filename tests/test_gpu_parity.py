@@ -414,7 +414,10 @@ def test_rmsnorm_against_oracle(rows, cols, shift):
 @pytest.mark.parametrize("M,N,K,b_is_nk", [(256, 256, 64, 1), (512, 256, 192, 1), (256, 768, 128, 1), (512, 512, 1024, 1),
                                            (128, 128, 64, 1), (256, 384, 512, 1), (200, 136, 96, 1), (37, 300, 72, 1),
                                            (129, 1, 8, 1), (64, 64, 20, 1), (50, 70, 33, 0), (128, 96, 64, 0),
-                                           (16, 16, 0, 1)])
+                                           (16, 16, 0, 1),
+                                           # every way the slice ring can end (K/32 mod 10 = 8, 2, 6, 0, 4, 8) and restart
+                                           (256, 256, 256, 1), (256, 256, 384, 1), (256, 512, 512, 1), (256, 256, 640, 1),
+                                           (512, 256, 768, 1), (256, 256, 896, 1), (256, 256, 1280, 1)])
 def test_gemm_against_oracle(M, N, K, b_is_nk):
     r = Rig([8 * MiB, 4 * MiB])
     try:
