@@ -25,6 +25,7 @@
 namespace gd {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -397,9 +398,7 @@ constexpr int RK = 32;                       // K per ring step
 constexpr int RSTAGE = (BM + BN) * RK * 2;   // 32 KiB
 constexpr int RA = BM * RK * 2;              // 16 KiB: offset of the B slice inside a stage
 
-// Fragment loads are issued in the order the MFMAs need them (0..3 = A fragments,
-// 4..7 = B fragments; MFMAs run A-fragment-major): B0 A0 B1 B2 B3 A1 A2 A3.
-__device__ constexpr int FRAG_ORDER[8] = {4, 0, 5, 6, 7, 1, 2, 3};
+constexpr int RT = 8;                        // 16 x 16 MFMA tiles per wavefront, each way
 
 // Workgroup barrier of the ring: wait until at most `vm` of this wavefront's DMA
 // loads are still in flight (they complete in order, so everything older has
@@ -408,6 +407,7 @@ __device__ constexpr int FRAG_ORDER[8] = {4, 0, 5, 6, 7, 1, 2, 3};
 // vmcnt[3:0] in bits 3:0 and vmcnt[5:4] in bits 15:14, expcnt (untouched, 7) in
 // bits 6:4, lgkmcnt = 0 in bits 11:8.  The empty asm statements keep the
 // compiler from moving LDS accesses across the barrier.
+#define GD_WAIT_VM7 0x0077      // vmcnt <= 7
 #define GD_WAIT_VM8 0x0078      // vmcnt <= 8
 #define GD_WAIT_VM10 0x007A     // vmcnt <= 10
 #define GD_WAIT_VM_ANY 0xC07F   // vmcnt <= 63: no constraint
@@ -469,36 +469,42 @@ void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_
         F.dma16_unordered(pre[d], (uint32_t)(uintptr_t)dst);
     };
 
-    f32x16 acc[TM][TN];
+    // 8 x 8 tiles of 16 x 16 per wavefront, v_mfma_f32_16x16x32_bf16: one instruction
+    // takes the whole K = 32 of a slice.  Per flop this shape moves half as many
+    // accumulator registers as the 32x32x16 one, and the chip, which is power limited
+    // under this load, sustains a clearly higher clock on it.
+    f32x4 acc[RT][RT];
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < RT; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < RT; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+            for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0f;
 
-    const uint32_t frow = lane & 31, fhalf = lane >> 5;
-    const uint32_t a_frag = (wm * 128 + frow) * 64;
-    const uint32_t b_frag = RA + (wn * 128 + frow) * 64;
-    uint32_t gsw[2];
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk) gsw[kk] = ((2 * kk + fhalf) ^ ((frow >> 2) & 3)) << 4;
-
-    bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-    auto frag_one = [&](const uint8_t *stage, int kk, int q, bf16x8 (&fa_)[TM], bf16x8 (&fb_)[TN]) {
-        if (q < TM)
-            fa_[q] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(stage + a_frag + q * 32 * 64 + gsw[kk]));
-        else
-            fb_[q - TM] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(stage + b_frag + (q - TM) * 32 * 64 + gsw[kk]));
+    // Fragment i of an operand: lane l holds row 16*i + l%16, granule l/16 (8 of the
+    // 32 k) -- one ds_read_b128.  (16*i)/4 is a multiple of 4, so the swizzle term of
+    // a lane does not depend on i and fragments sit at immediate offsets of 1 KiB.
+    const uint32_t l16 = lane & 15, lg = lane >> 4;
+    const uint32_t gsw = (lg ^ ((l16 >> 2) & 3)) << 4;
+    const uint32_t a_frag = (wm * 128 + l16) * 64 + gsw;
+    const uint32_t b_frag = RA + (wn * 128 + l16) * 64 + gsw;
+    bf16x8 fra[RT], fbx[RT], fby[RT];                     // B fragments are double-buffered across steps
+    auto load_a = [&](const uint8_t *stage, int i) {
+        fra[i] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(stage + a_frag + i * 1024));
     };
-    auto mfma_pair = [&](int q, const bf16x8 (&fa_)[TM], const bf16x8 (&fb_)[TN]) {
+    auto load_b = [&](const uint8_t *stage, int j, bf16x8 (&fb_)[RT]) {
+        fb_[j] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(stage + b_frag + j * 1024));
+    };
+    // Slot sl (0..15) of a step: A fragment sl/2 against B fragments 4*(sl%2)..+3.
+    auto mfma_quad = [&](int sl, const bf16x8 (&fb_)[RT]) {
+        const int i = sl >> 1;
 #pragma unroll
-        for (int e = 2 * q; e < 2 * q + 2; ++e)
-            acc[e / TN][e % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb_[e % TN], fa_[e / TN], acc[e / TN][e % TN], 0, 0, 0);
+        for (int j = 4 * (sl & 1); j < 4 * (sl & 1) + 4; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb_[j], fra[i], acc[i][j], 0, 0, 0);
     };
     // DMA pair number pr (0..7) of a pair of slices: operand and 16-row chunk pr,
-    // both halves.  The fenced addresses are computed before the MFMA pair of the
-    // slot, the DMAs go out after it.
+    // both halves.  The fenced addresses are computed before the MFMAs of the slot,
+    // the DMAs go out after them.
     auto pre_pair = [&](uint32_t k_pair, int pr) {
         pre_one(k_pair, 2 * pr);
         pre_one(k_pair, 2 * pr + 1);
@@ -507,41 +513,44 @@ void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_
         dma_one(stage_even, stage_odd, 2 * pr);
         dma_one(stage_even, stage_odd, 2 * pr + 1);
     };
-    // One ring step of 16 slots, one MFMA pair each.  In: substep-0 fragments of `cur`
-    // in fa0/fb0.  Out: substep-0 fragments of `nxt` in fa0/fb0.  LDS serves the
-    // fragment loads of four wavefronts and the DMA writes at about three quarters of
-    // its bandwidth, so the loads are spread out: the 8 substep-1 fragments of `cur`
-    // one per slot in slots 0..7 (first needed in slot 8), the 8 substep-0 fragments
-    // of `nxt` behind the barrier, two per slot in slots 10..13 (all back before the
-    // next step starts).  Slots 0, 4 and 8 carry DMA pairs
-    // p0, p0+1, p0+2 of the slice pair (ea, oa, ka); slot 12 carries DMA pair p3 of the
-    // slice pair (eb, ob, kb).  An odd step t sends DMA pairs 1..4 of slices (t+3, t+4);
-    // an even step t sends pairs 5..7 of slices (t+2, t+3) and pair 0 of slices
-    // (t+4, t+5), whose second stage is the one this step has just finished reading.
-    auto step = [&](const uint8_t *cur, const uint8_t *nxt, bool odd, uint8_t *ea, uint8_t *oa, uint32_t ka,
-                    uint8_t *eb, uint8_t *ob, uint32_t kb) {
+    // One ring step of 16 slots, four MFMAs (64 clocks) each.  In: fra[0..3] and all
+    // of fb_cur hold fragments of `cur`.  Out: fra[0..3] and fb_nxt hold fragments of
+    // `nxt`.  A fragments 4..7 of `cur` are fetched in slots 0..3 (first needed in
+    // slot 8).  Behind the barrier, slots 10..13 fetch the 12 fragments the next step
+    // starts with, in the order it needs them; fra[0..3] are dead by then.  Slots 0, 4
+    // and 8 carry DMA pairs p0, p0+1, p0+2 of the slice pair (ea, oa, ka); slot 12
+    // carries DMA pair p3 of the slice pair (eb, ob, kb).  An odd step t sends DMA
+    // pairs 1..4 of slices (t+3, t+4); an even step t sends pairs 5..7 of slices
+    // (t+2, t+3) and pair 0 of slices (t+4, t+5), whose second stage is the one this
+    // step has just finished reading.
+    auto step = [&](const uint8_t *cur, const uint8_t *nxt, bf16x8 (&fb_cur)[RT], bf16x8 (&fb_nxt)[RT], bool odd,
+                    uint8_t *ea, uint8_t *oa, uint32_t ka, uint8_t *eb, uint8_t *ob, uint32_t kb) {
         const int p0 = odd ? 1 : 5, p3 = odd ? 4 : 0;
 #pragma unroll
         for (int sl = 0; sl < 16; ++sl) {
             if (sl == 10) {
-                // Odd step t: slice t+1 must have landed, i.e. everything but the 4 DMA
-                // pairs sent since the previous odd barrier.  Even step: `nxt` landed a
-                // step ago; the barrier only releases the stage of `cur` for refilling.
-                if (odd) GD_RING_BARRIER(GD_WAIT_VM8);
+                // Odd step t: slice t+1 must have landed, i.e. everything but the 7 DMAs
+                // sent since slot 12 of step t-1.  Even step: `nxt` landed a step ago; the
+                // barrier only releases the stage of `cur` for refilling.
+                if (odd) GD_RING_BARRIER(GD_WAIT_VM7);
                 else GD_RING_BARRIER(GD_WAIT_VM_ANY);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (sl < 8) frag_one(cur, 1, FRAG_ORDER[sl], fa1, fb1);
-            if (sl >= 10 && sl < 14) {
-                frag_one(nxt, 0, FRAG_ORDER[2 * (sl - 10)], fa0, fb0);
-                frag_one(nxt, 0, FRAG_ORDER[2 * (sl - 10) + 1], fa0, fb0);
+            if (sl < 4) load_a(cur, 4 + sl);
+            if (sl == 10) { load_b(nxt, 0, fb_nxt); load_a(nxt, 0); load_b(nxt, 1, fb_nxt); }
+            if (sl == 11) { load_b(nxt, 2, fb_nxt); load_b(nxt, 3, fb_nxt); load_b(nxt, 4, fb_nxt); }
+            if (sl == 12) { load_b(nxt, 5, fb_nxt); load_b(nxt, 6, fb_nxt); load_b(nxt, 7, fb_nxt); }
+            if (sl == 13) { load_a(nxt, 1); load_a(nxt, 2); load_a(nxt, 3); }
+            // one DMA every second slot: DMA number 2*pr + h of the slice pair, h = sl/2 % 2
+            if ((sl & 1) == 0) {
+                const int pr = sl < 12 ? p0 + sl / 4 : p3;
+                const int d = 2 * pr + ((sl >> 1) & 1);
+                pre_one(sl < 12 ? ka : kb, d);
+                mfma_quad(sl, fb_cur);
+                dma_one(sl < 12 ? ea : eb, sl < 12 ? oa : ob, d);
+            } else {
+                mfma_quad(sl, fb_cur);
             }
-            if (sl == 0 || sl == 4 || sl == 8) pre_pair(ka, p0 + sl / 4);
-            if (sl == 12) pre_pair(kb, p3);
-            if (sl < 8) mfma_pair(sl, fa0, fb0);
-            else mfma_pair(sl - 8, fa1, fb1);
-            if (sl == 0 || sl == 4 || sl == 8) dma_pair(ea, oa, p0 + sl / 4);
-            if (sl == 12) dma_pair(eb, ob, p3);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -561,31 +570,33 @@ void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_
     }
     GD_RING_BARRIER(GD_WAIT_VM10);                       // slices 0 and 1 have landed
 #pragma unroll
-    for (int q = 0; q < 8; ++q) frag_one(ring0, 0, FRAG_ORDER[q], fa0, fb0);
+    for (int j = 0; j < RT; ++j) load_b(ring0, j, fbx);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) load_a(ring0, i);
     // Slice s lives in stage s % 5 and the DMA pattern has period 2, so the code
     // repeats every 10 steps; K % 128 == 0 lets the loop end after any odd step.
     for (uint32_t t = 0; t < ksteps;) {
-        step(ring0, ring1, false, ring2, ring3, clamp_k((t + 2) * RK), ring4, ring0, clamp_k((t + 4) * RK));
-        step(ring1, ring2, true, ring4, ring0, clamp_k((t + 4) * RK), ring4, ring0, clamp_k((t + 4) * RK));
+        step(ring0, ring1, fbx, fby, false, ring2, ring3, clamp_k((t + 2) * RK), ring4, ring0, clamp_k((t + 4) * RK));
+        step(ring1, ring2, fby, fbx, true, ring4, ring0, clamp_k((t + 4) * RK), ring4, ring0, clamp_k((t + 4) * RK));
         t += 2;
         if (t < ksteps) {
-            step(ring2, ring3, false, ring4, ring0, clamp_k((t + 2) * RK), ring1, ring2, clamp_k((t + 4) * RK));
-            step(ring3, ring4, true, ring1, ring2, clamp_k((t + 4) * RK), ring1, ring2, clamp_k((t + 4) * RK));
+            step(ring2, ring3, fbx, fby, false, ring4, ring0, clamp_k((t + 2) * RK), ring1, ring2, clamp_k((t + 4) * RK));
+            step(ring3, ring4, fby, fbx, true, ring1, ring2, clamp_k((t + 4) * RK), ring1, ring2, clamp_k((t + 4) * RK));
             t += 2;
         }
         if (t < ksteps) {
-            step(ring4, ring0, false, ring1, ring2, clamp_k((t + 2) * RK), ring3, ring4, clamp_k((t + 4) * RK));
-            step(ring0, ring1, true, ring3, ring4, clamp_k((t + 4) * RK), ring3, ring4, clamp_k((t + 4) * RK));
+            step(ring4, ring0, fbx, fby, false, ring1, ring2, clamp_k((t + 2) * RK), ring3, ring4, clamp_k((t + 4) * RK));
+            step(ring0, ring1, fby, fbx, true, ring3, ring4, clamp_k((t + 4) * RK), ring3, ring4, clamp_k((t + 4) * RK));
             t += 2;
         }
         if (t < ksteps) {
-            step(ring1, ring2, false, ring3, ring4, clamp_k((t + 2) * RK), ring0, ring1, clamp_k((t + 4) * RK));
-            step(ring2, ring3, true, ring0, ring1, clamp_k((t + 4) * RK), ring0, ring1, clamp_k((t + 4) * RK));
+            step(ring1, ring2, fbx, fby, false, ring3, ring4, clamp_k((t + 2) * RK), ring0, ring1, clamp_k((t + 4) * RK));
+            step(ring2, ring3, fby, fbx, true, ring0, ring1, clamp_k((t + 4) * RK), ring0, ring1, clamp_k((t + 4) * RK));
             t += 2;
         }
         if (t < ksteps) {
-            step(ring3, ring4, false, ring0, ring1, clamp_k((t + 2) * RK), ring2, ring3, clamp_k((t + 4) * RK));
-            step(ring4, ring0, true, ring2, ring3, clamp_k((t + 4) * RK), ring2, ring3, clamp_k((t + 4) * RK));
+            step(ring3, ring4, fbx, fby, false, ring0, ring1, clamp_k((t + 2) * RK), ring2, ring3, clamp_k((t + 4) * RK));
+            step(ring4, ring0, fby, fbx, true, ring2, ring3, clamp_k((t + 4) * RK), ring2, ring3, clamp_k((t + 4) * RK));
             t += 2;
         }
     }
@@ -595,37 +606,34 @@ void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_
     __syncthreads();                                     // every DMA has landed, every fragment is read
 
     // Epilogue.  The MFMAs take the B fragment as their row operand, so acc[i][j][r]
-    // is C[row, col] of the wavefront's block with row = 32*i + lane%32 and
-    // col = 32*j + 8*(r/4) + 4*(lane/32) + r%4: four consecutive columns per r/4,
-    // i.e. 8 contiguous bytes of bf16.  Wavefront w parks its 128 x 128 bf16 block
-    // in ring stage w (rows of 256 bytes = 32 units of 8 bytes; unit u of row q is
-    // kept at u ^ (q & 31) so that the 32 rows written together spread over the
-    // banks), then streams it out as 16-byte runs, 16 lanes per row.
+    // is C[row, col] of the wavefront's block with row = 16*i + lane%16 and
+    // col = 16*j + 4*(lane/16) + r: four consecutive columns, i.e. 8 contiguous bytes
+    // of bf16.  Wavefront w parks its 128 x 128 bf16 block in ring stage w (rows of
+    // 256 bytes = 32 units of 8 bytes; unit u of row q is kept at u ^ 2*(q%16), so
+    // that the 16 rows written together spread over the banks and the two units of
+    // a 16-byte granule stay neighbours), then streams it out as 16-byte runs, 16
+    // lanes per row.
     uint8_t *park = wave == 0 ? ring0 : wave == 1 ? ring1 : wave == 2 ? ring2 : ring3;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < RT; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const f32x2 lo = {acc[i][j][4 * g + 0], acc[i][j][4 * g + 1]};
-                const f32x2 hi = {acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                u32x2 w;
-                w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
-                w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
-                const uint32_t row = 32 * i + frow;
-                const uint32_t unit = (8 * j + 2 * g + fhalf) ^ (row & 31);
-                *(u32x2 *)(park + row * 256 + unit * 8) = w;
-            }
+        for (int j = 0; j < RT; ++j) {
+            const f32x2 lo = {acc[i][j][0], acc[i][j][1]};
+            const f32x2 hi = {acc[i][j][2], acc[i][j][3]};
+            u32x2 w;
+            w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+            w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
+            const uint32_t row = 16 * i + l16;
+            const uint32_t unit = (4 * j + lg) ^ (2 * l16);
+            *(u32x2 *)(park + row * 256 + unit * 8) = w;
+        }
     __syncthreads();
     const uint32_t orow = lane >> 4, og = lane & 15;
 #pragma unroll 4
     for (int it = 0; it < 32; ++it) {
         const uint32_t row = orow + 4 * it;
         const uint32_t m = m0 + wm * 128 + row, n = n0 + wn * 128 + og * 8;
-        // units 2*og and 2*og+1 sit in granule og ^ ((row & 31) / 2), swapped if the row is odd
-        u32x4 v = *(const u32x4 *)(park + row * 256 + ((og ^ ((row & 31) >> 1)) << 4));
-        if (row & 1) v = (u32x4){v[2], v[3], v[0], v[1]};
+        const u32x4 v = *(const u32x4 *)(park + row * 256 + ((og ^ (row & 15)) << 4));
         F.template st<u32x4>(p.C + 2 * ((uint64_t)m * p.N + n), v);
     }
 }
