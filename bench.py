@@ -456,7 +456,7 @@ def run_modes(torch, gd, si, args):
     st = torch.cuda.Stream()
     g = si.rng(6, 0)
     modes = (("none", gd.GD_FENCE_NONE), ("bitwise", gd.GD_FENCE_BITWISE), ("modulo", gd.GD_FENCE_MODULO), ("check", gd.GD_FENCE_CHECK))
-    res = {"workload": "1 tenant, 4 GiB partition, all accesses in bounds: fp32 triad 2^26 (HBM resident), triad 2^22 repeated 200 times inside one launch (each workgroup re-reads its own 12 KiB: cache resident), gather 2^24 with int64 indices"}
+    res = {"workload": "1 tenant, 4 GiB partition, all accesses in bounds: fp32 triad 2^26 (HBM resident), triad 2^22 repeated 200 times inside one launch (each workgroup re-reads its own 3 KiB: cache resident), gather 2^24 with int64 indices"}
 
     def sweep(label, kid, kargs, nbytes, reps):
         out = {}
