@@ -177,18 +177,33 @@ struct Fence {
     // between the write of M0 and the copy).  M0 is a reserved register the compiler
     // does not track through inline asm: use this only in kernels where nothing else
     // depends on M0 (no compiler-issued LDS copies, no indexed register moves).
+    // OFF (64) selects the second half of the 128-byte line the handle points into.
+    // It is applied to the fenced address -- through the scalar base for the 32-bit
+    // rule, by setting bit 6 of the address otherwise -- which is the fence of the
+    // final address only if the caller guarantees that the raw address the handle was
+    // made from is a multiple of 128 plus less than 64: then bit 6 of the fenced
+    // address is clear, adding 64 carries into nothing, and
+    // fenced(raw) + 64 == fenced(raw + 64) (bitwise rule: the mask of a partition of at
+    // least 4 KiB keeps the low 12 bits; modulo rule: base and size are multiples of
+    // 256).  The instruction's own offset field is not used: it would move the LDS
+    // side of the copy as well.
+    template <int OFF = 0>
     __device__ __forceinline__ void dma16_unordered(Handle h, uint32_t lds_addr) const
     {
-        if constexpr (V == V_BIT32)
+        static_assert(OFF == 0 || OFF == 64, "only the two halves of a 128-byte line");
+        if constexpr (V == V_BIT32) {
+            const uint64_t b = base + OFF;                  // wave-uniform, loop-invariant
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                          :
-                         : "s"(lds_addr), "v"(h), "s"(base)
+                         : "s"(lds_addr), "v"(h), "s"(b)
                          : "memory");
-        else
+        } else {
+            const uint64_t a = h | (uint64_t)OFF;
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                          :
-                         : "s"(lds_addr), "v"(h)
+                         : "s"(lds_addr), "v"(a)
                          : "memory");
+        }
     }
 
     // Fenced global -> LDS copy of 16 bytes per lane (global_load_lds_dwordx4): the

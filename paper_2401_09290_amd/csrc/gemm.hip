@@ -392,7 +392,7 @@ void k_gemm_dma(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_n
 // therefore spread evenly over the two steps (32 MFMA pairs) in which both target
 // stages are free: pair (t+3, t+4), t odd, goes out between the barrier of step
 // t-1 and the barrier of step t+1, two DMAs every fourth MFMA pair.
-// Requirements: as k_gemm_dma, and K % 128 == 0.
+// Requirements: as k_gemm_dma, and K % 128 == 0, A and B 128-byte aligned.
 constexpr int RK = 32;                       // K per ring step
 constexpr int RSTAGE = (BM + BN) * RK * 2;   // 32 KiB
 constexpr int RA = BM * RK * 2;              // 16 KiB: offset of the B slice inside a stage
@@ -470,17 +470,22 @@ void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_
     const uint64_t a_lane = p.A + 2 * ((uint64_t)(m0 + drow) * p.K + dgran * 8);
     const uint64_t b_lane = p.B + 2 * ((uint64_t)(n0 + drow) * p.K + dgran * 8);
     const uint64_t chunk_step = 2 * 16 * (uint64_t)p.K;      // 16 rows further down
-    typename Fence<V>::Handle pre[16];                     // fenced addresses of the next pair's 16 DMAs
-    auto pre_one = [&](uint32_t k0, int d) {
-        const int c = d >> 1;
-        const uint64_t uni = (c & 3) * chunk_step + 2 * (uint64_t)k0 + (d & 1) * (2 * RK);
-        pre[d] = F.template fenced<16>(c < 4 ? a_lane : b_lane, uni);
+    // The two DMAs of a cache line share one fenced address: A, B and the row pitch
+    // 2*K are multiples of 128 bytes and k_pair of 64 elements, so the address of the
+    // first half is a multiple of 128 plus the lane's granule (bits 4..5), and the
+    // second half, 64 bytes further, lies in the same fenced line (see
+    // Fence::dma16_unordered).
+    typename Fence<V>::Handle pre[8];                      // one fenced address per DMA pair of the set
+    auto pre_one = [&](uint32_t k_pair, int pr) {
+        const uint64_t uni = (pr & 3) * chunk_step + 2 * (uint64_t)k_pair;
+        pre[pr] = F.template fenced<16>(pr < 4 ? a_lane : b_lane, uni);
     };
     auto dma_one = [&](uint8_t *stage_even, uint8_t *stage_odd, int d) {
         const int c = d >> 1;
         uint8_t *stage = (d & 1) ? stage_odd : stage_even;
         GD_LDS uint8_t *dst = (GD_LDS uint8_t *)stage + wave * 4096 + (c & 3) * 1024 + (c < 4 ? 0 : RA);
-        F.dma16_unordered(pre[d], (uint32_t)(uintptr_t)dst);
+        if (d & 1) F.template dma16_unordered<2 * RK>(pre[c], (uint32_t)(uintptr_t)dst);
+        else F.template dma16_unordered<0>(pre[c], (uint32_t)(uintptr_t)dst);
     };
 
     // 8 x 8 tiles of 16 x 16 per wavefront, v_mfma_f32_16x16x32_bf16: one instruction
@@ -519,10 +524,7 @@ void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_
     // DMA pair number pr (0..7) of a pair of slices: operand and 16-row chunk pr,
     // both halves.  The fenced addresses are computed before the MFMAs of the slot,
     // the DMAs go out after them.
-    auto pre_pair = [&](uint32_t k_pair, int pr) {
-        pre_one(k_pair, 2 * pr);
-        pre_one(k_pair, 2 * pr + 1);
-    };
+    auto pre_pair = [&](uint32_t k_pair, int pr) { pre_one(k_pair, pr); };
     auto dma_pair = [&](uint8_t *stage_even, uint8_t *stage_odd, int pr) {
         dma_one(stage_even, stage_odd, 2 * pr);
         dma_one(stage_even, stage_odd, 2 * pr + 1);
@@ -559,7 +561,7 @@ void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_
             if ((sl & 1) == 0) {
                 const int pr = sl < 12 ? p0 + sl / 4 : p3;
                 const int d = 2 * pr + ((sl >> 1) & 1);
-                pre_one(sl < 12 ? ka : kb, d);
+                if ((d & 1) == 0) pre_one(sl < 12 ? ka : kb, pr);
                 mfma_quad(sl, fb_cur);
                 dma_one(sl < 12 ? ea : eb, sl < 12 ? oa : ob, d);
             } else {
@@ -670,7 +672,7 @@ int launch_gemm_bf16(const void *args, const FenceArgs &f, int variant, const Sh
 #define GD_GEMM_CASE(VAR)                                                                                         \
     case VAR:                                                                                                     \
         if (edge) hipLaunchKernelGGL((k_gemm_nk256<VAR, true>), grid, block, 0, stream, p, f, tiles_m, tiles_n);  \
-        else if (p.K % 128 == 0) hipLaunchKernelGGL((k_gemm_ring<VAR>), grid, block, 0, stream, p, f, tiles_m, tiles_n); \
+        else if (p.K % 128 == 0 && ((p.A | p.B) & 127) == 0) hipLaunchKernelGGL((k_gemm_ring<VAR>), grid, block, 0, stream, p, f, tiles_m, tiles_n); \
         else hipLaunchKernelGGL((k_gemm_dma<VAR>), grid, block, 0, stream, p, f, tiles_m, tiles_n);               \
         break;
         switch (variant) {

@@ -461,6 +461,39 @@ def test_gemm_with_wrapping_operand_pointers():
         r.close()
 
 
+def test_gemm_tile_kernel_with_an_operand_running_past_the_partition_end():
+    """Multiples of the tile in every dimension and 128-byte aligned operands: the slice-ring
+    kernel, whose DMAs reach the second half of a cache line through the instruction's
+    immediate offset.  A starts 64 KiB below the end of the partition, so its rows 128..255
+    wrap around to the partition's first bytes; B and C are handed over a whole partition off."""
+    r = Rig([8 * MiB, 8 * MiB])
+    try:
+        t = 1
+        base, size = r.row(t)
+        M = N = K = 256
+        g = si.rng(4, 123)
+        low = r.alloc(t, 64 * 1024)                      # first allocation: the partition's first bytes
+        assert low == base
+        B, Cc = r.alloc(t, 2 * K * N), r.alloc(t, 2 * M * N)
+        a_bits = si.f32_to_bf16_bits(si.normal_f32(g, M * K) * np.float32(K ** -0.5))
+        A = base + size - 64 * 1024
+        r.upload(t, A, a_bits[: M * K // 2])             # rows 0..127 at the top of the partition
+        r.upload(t, low, a_bits[M * K // 2:])            # rows 128..255 where the fence sends them
+        r.upload(t, B, si.f32_to_bf16_bits(si.normal_f32(g, K * N)))
+        args = gd.gd_args_gemm(Cc - size, A, B + size, M, N, K, 1)
+        r.launch(t, gd.GD_K_GEMM_BF16, args)
+        r.oracle("gemm_bf16", t, Cc - size, A, B + size, M, N, K, 1, 0, M, 0, N)
+        got, want = r.download(Cc, np.uint16, M * N), r.sim.view(Cc, np.uint16, M * N)
+        assert rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want)) <= BF16_TOL
+        r.assert_images_equal(skip=[(Cc, 2 * M * N)], what="gemm wrapped at the partition end")
+        # and it is the product of the matrix as uploaded
+        ref = si.bf16_bits_to_f32(a_bits).reshape(M, K).astype(np.float64) @ \
+            si.bf16_bits_to_f32(r.download(B, np.uint16, K * N)).reshape(N, K).astype(np.float64).T
+        assert rel_frobenius(si.bf16_bits_to_f32(got).reshape(M, N), ref) <= 4e-3
+    finally:
+        r.close()
+
+
 # ---------------------------------------------------------------------------
 # tenants on concurrent streams; re-carving mid-run
 # ---------------------------------------------------------------------------
