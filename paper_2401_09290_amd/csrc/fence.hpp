@@ -167,7 +167,29 @@ struct Fence {
             __builtin_amdgcn_global_load_lds((const GD_GLOBAL void *)h, lds_base, 16, 0, 0);
     }
 
-    // The same copy as an instruction the compiler does not model.  The compiler
+    // A fenced address for dma16_unordered(), made from a wave-uniform 64-bit part
+    // and a 32-bit per-lane byte offset.  The unfenced build keeps the two apart --
+    // scalar base plus lane offset is an addressing mode of the copy instruction, so a
+    // native kernel spends no vector instruction on the address -- and every fenced
+    // build forms the sum and fences it (32-bit rule: in 32-bit arithmetic).
+    struct Split { uint64_t s; uint32_t v; };
+    using SplitHandle = typename std::conditional<V == V_NONE, Split, Handle>::type;
+
+    template <int W>
+    __device__ __forceinline__ SplitHandle fenced_split(uint64_t uniform_part, uint32_t lane_off) const
+    {
+        if constexpr (V == V_NONE) {
+            return Split{uniform_part, lane_off};
+        } else if constexpr (V == V_BIT32) {
+            const uint32_t m = (uint32_t)mask & ~(uint32_t)(W - 1);
+            return fence_and32((uint32_t)uniform_part + lane_off, m);
+        } else {
+            return address<W>(uniform_part + lane_off);
+        }
+    }
+
+    // global -> LDS copy of 16 bytes per lane from an address fenced_split<16>()
+    // produced, as an instruction the compiler does not model.  The compiler
     // orders every LDS read it cannot tell apart from an earlier global -> LDS copy
     // behind s_waitcnt vmcnt(0), which drains a software pipeline that keeps copies
     // in flight across basic blocks.  Issued this way the copy is invisible to that
@@ -177,6 +199,7 @@ struct Fence {
     // between the write of M0 and the copy).  M0 is a reserved register the compiler
     // does not track through inline asm: use this only in kernels where nothing else
     // depends on M0 (no compiler-issued LDS copies, no indexed register moves).
+    //
     // OFF (64) selects the second half of the 128-byte line the handle points into.
     // It is applied to the fenced address -- through the scalar base for the 32-bit
     // rule, by setting bit 6 of the address otherwise -- which is the fence of the
@@ -188,10 +211,16 @@ struct Fence {
     // 256).  The instruction's own offset field is not used: it would move the LDS
     // side of the copy as well.
     template <int OFF = 0>
-    __device__ __forceinline__ void dma16_unordered(Handle h, uint32_t lds_addr) const
+    __device__ __forceinline__ void dma16_unordered(SplitHandle h, uint32_t lds_addr) const
     {
         static_assert(OFF == 0 || OFF == 64, "only the two halves of a 128-byte line");
-        if constexpr (V == V_BIT32) {
+        if constexpr (V == V_NONE) {
+            const uint64_t b = h.s + OFF;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(lds_addr), "v"(h.v), "s"(b)
+                         : "memory");
+        } else if constexpr (V == V_BIT32) {
             const uint64_t b = base + OFF;                  // wave-uniform, loop-invariant
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                          :

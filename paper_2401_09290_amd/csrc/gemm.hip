@@ -392,7 +392,7 @@ void k_gemm_dma(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_n
 // therefore spread evenly over the two steps (32 MFMA pairs) in which both target
 // stages are free: pair (t+3, t+4), t odd, goes out between the barrier of step
 // t-1 and the barrier of step t+1, two DMAs every fourth MFMA pair.
-// Requirements: as k_gemm_dma, and K % 128 == 0, A and B 128-byte aligned.
+// Requirements: as k_gemm_dma, and K % 128 == 0, K <= 2^22, A and B 128-byte aligned.
 constexpr int RK = 32;                       // K per ring step
 constexpr int RSTAGE = (BM + BN) * RK * 2;   // 32 KiB
 constexpr int RA = BM * RK * 2;              // 16 KiB: offset of the B slice inside a stage
@@ -467,18 +467,19 @@ void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_
     // two halves of the same cache lines are neighbours in issue order.
     const uint32_t drow = wave * 64 + (lane >> 2);
     const uint32_t dgran = (lane & 3) ^ ring_swizzle(lane >> 4);
-    const uint64_t a_lane = p.A + 2 * ((uint64_t)(m0 + drow) * p.K + dgran * 8);
-    const uint64_t b_lane = p.B + 2 * ((uint64_t)(n0 + drow) * p.K + dgran * 8);
+    const uint32_t lane_off = 2 * (drow * p.K + dgran * 8);     // below 2^32: the launcher bounds K
+    const uint64_t a_tile = p.A + 2 * (uint64_t)m0 * p.K;
+    const uint64_t b_tile = p.B + 2 * (uint64_t)n0 * p.K;
     const uint64_t chunk_step = 2 * 16 * (uint64_t)p.K;      // 16 rows further down
     // The two DMAs of a cache line share one fenced address: A, B and the row pitch
     // 2*K are multiples of 128 bytes and k_pair of 64 elements, so the address of the
     // first half is a multiple of 128 plus the lane's granule (bits 4..5), and the
     // second half, 64 bytes further, lies in the same fenced line (see
     // Fence::dma16_unordered).
-    typename Fence<V>::Handle pre[8];                      // one fenced address per DMA pair of the set
+    typename Fence<V>::SplitHandle pre[8];                 // one fenced address per DMA pair of the set
     auto pre_one = [&](uint32_t k_pair, int pr) {
-        const uint64_t uni = (pr & 3) * chunk_step + 2 * (uint64_t)k_pair;
-        pre[pr] = F.template fenced<16>(pr < 4 ? a_lane : b_lane, uni);
+        const uint64_t uni = (pr < 4 ? a_tile : b_tile) + (pr & 3) * chunk_step + 2 * (uint64_t)k_pair;
+        pre[pr] = F.template fenced_split<16>(uni, lane_off);
     };
     auto dma_one = [&](uint8_t *stage_even, uint8_t *stage_odd, int d) {
         const int c = d >> 1;
@@ -672,7 +673,7 @@ int launch_gemm_bf16(const void *args, const FenceArgs &f, int variant, const Sh
 #define GD_GEMM_CASE(VAR)                                                                                         \
     case VAR:                                                                                                     \
         if (edge) hipLaunchKernelGGL((k_gemm_nk256<VAR, true>), grid, block, 0, stream, p, f, tiles_m, tiles_n);  \
-        else if (p.K % 128 == 0 && ((p.A | p.B) & 127) == 0) hipLaunchKernelGGL((k_gemm_ring<VAR>), grid, block, 0, stream, p, f, tiles_m, tiles_n); \
+        else if (p.K % 128 == 0 && p.K <= (1u << 22) && ((p.A | p.B) & 127) == 0) hipLaunchKernelGGL((k_gemm_ring<VAR>), grid, block, 0, stream, p, f, tiles_m, tiles_n); \
         else hipLaunchKernelGGL((k_gemm_dma<VAR>), grid, block, 0, stream, p, f, tiles_m, tiles_n);               \
         break;
         switch (variant) {
