@@ -1,25 +1,28 @@
-// C = A * B, bfloat16 operands, fp32 accumulation on the matrix cores
-// (v_mfma_f32_32x32x16_bf16), bfloat16 result.  A is row-major M x K; B is
-// stored N x K with K contiguous (b_is_nk) -- both operands are then read as
-// 16-byte runs along K -- or row-major K x N (handled by the generic kernel).
-// Tiles of A and B are staged through LDS; every global tile load and every
-// store of C carries the fence on its final address.  LDS is not fenced.
+// C = A * B, bfloat16 operands, fp32 accumulation on the matrix cores, bfloat16
+// result.  A is row-major M x K; B is stored N x K with K contiguous (b_is_nk) --
+// both operands are then read as 16-byte runs along K -- or row-major K x N
+// (handled by the generic kernel).  Tiles of A and B are staged through LDS; every
+// global tile load and every store of C carries the fence on its final address.
+// LDS is not fenced.
 //
 // Tiled kernels: one workgroup of 4 wavefronts (2 x 2) computes a 256 x 256 tile
-// of C; each wavefront owns 128 x 128 of it as 4 x 4 MFMA tiles (256 fp32
-// accumulators per lane, one wavefront per SIMD).  K advances in steps of 64
-// through two LDS stages of 64 KiB (A 256x64 + B 256x64 bf16 each).  LDS rows
-// are 128 bytes; the eight 16-byte granules of a row are XOR-swizzled with half
-// the row number, so that 16 consecutive rows of one granule column (what a
-// fragment load touches per pass) spread over all 64 banks.  The finished tile is converted to bf16, transposed through LDS and
-// stored as 16-byte runs.
-//   k_gemm_dma   (shapes that are multiples of the tile) moves tiles global -> LDS
-//                with global_load_lds_dwordx4: no staging registers, no LDS store
-//                instructions; each lane picks the global granule that belongs in
-//                the LDS slot the hardware assigns to it, which is how the swizzle
-//                is applied.  Fragment loads run one k-substep ahead of the MFMAs.
+// of C; each wavefront owns 128 x 128 of it (256 fp32 accumulators per lane, one
+// wavefront per SIMD).  The finished tile is converted to bf16, transposed
+// through LDS and stored as 16-byte runs.
+//   k_gemm_ring  (shapes that are multiples of the tile, K % 128 == 0, operands
+//                128-byte aligned: the measured path) v_mfma_f32_16x16x32_bf16; K
+//                advances in slices of 32 through a ring of five 32 KiB LDS stages
+//                filled by global_load_lds_dwordx4 (no staging registers, no LDS
+//                store instructions); described in front of the kernel.
+//   k_gemm_dma   (other multiples of the tile) v_mfma_f32_32x32x16_bf16, K in steps
+//                of 64 through two LDS stages of 64 KiB, same global -> LDS copies;
+//                LDS rows are 128 bytes, their eight 16-byte granules XOR-swizzled
+//                with half the row number; each lane picks the global granule that
+//                belongs in the LDS slot the hardware assigns to it, which is how
+//                the swizzle is applied.
 //   k_gemm_nk256 (ragged shapes) stages through registers so that out-of-range
 //                rows and the K tail can be zero-filled.
+//   k_gemm_generic  any shape, alignment and layout of B: one thread per entry.
 #include "launchers.hpp"
 
 namespace gd {
