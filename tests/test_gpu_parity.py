@@ -461,6 +461,28 @@ def test_gemm_with_wrapping_operand_pointers():
         r.close()
 
 
+def test_gemm_operands_aligned_to_16_bytes_only():
+    """Tile-multiple shape, but A and B are not 128-byte aligned: the launcher must fall back
+    from the slice-ring kernel (which relies on that alignment) to the two-stage one."""
+    r = Rig([8 * MiB, 4 * MiB])
+    try:
+        M = N = 256
+        K = 256
+        g = si.rng(4, 77)
+        A, B, Cc = r.alloc(0, 2 * M * K + 256) + 16, r.alloc(0, 2 * K * N + 256) + 48, r.alloc(0, 2 * M * N)
+        r.upload(0, A, si.f32_to_bf16_bits(si.normal_f32(g, M * K) * np.float32(K ** -0.5)))
+        r.upload(0, B, si.f32_to_bf16_bits(si.normal_f32(g, K * N)))
+        args = gd.gd_args_gemm(Cc, A, B, M, N, K, 1)
+        r.launch(0, gd.GD_K_GEMM_BF16, args)
+        r.oracle("gemm_bf16", 0, Cc, A, B, M, N, K, 1, 0, M, 0, N)
+        got = r.download(Cc, np.uint16, M * N)
+        want = r.sim.view(Cc, np.uint16, M * N)
+        assert rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want)) <= BF16_TOL
+        r.assert_images_equal(skip=[(Cc, 2 * M * N)], what="gemm, 16-byte aligned operands")
+    finally:
+        r.close()
+
+
 def test_gemm_tile_kernel_with_an_operand_running_past_the_partition_end():
     """Multiples of the tile in every dimension and 128-byte aligned operands: the slice-ring
     kernel, whose DMAs reach the second half of a cache line through the instruction's
