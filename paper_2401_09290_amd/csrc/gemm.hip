@@ -425,7 +425,6 @@ __device__ __forceinline__ uint32_t ring_swizzle(uint32_t row_div4)
 // bits 6:4, lgkmcnt = 0 in bits 11:8.  The empty asm statements keep the
 // compiler from moving LDS accesses across the barrier.
 #define GD_WAIT_VM7 0x0077      // vmcnt <= 7
-#define GD_WAIT_VM8 0x0078      // vmcnt <= 8
 #define GD_WAIT_VM10 0x007A     // vmcnt <= 10
 #define GD_WAIT_VM_ANY 0xC07F   // vmcnt <= 63: no constraint
 #define GD_RING_BARRIER(imm)                    \
@@ -526,10 +525,9 @@ void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_
             acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb_[j], fra[i], acc[i][j], 0, 0, 0);
     };
     // DMA pair number pr (0..7) of a pair of slices: operand and 16-row chunk pr,
-    // both halves.  The fenced addresses are computed before the MFMAs of the slot,
-    // the DMAs go out after them.
-    auto pre_pair = [&](uint32_t k_pair, int pr) { pre_one(k_pair, pr); };
-    auto dma_pair = [&](uint8_t *stage_even, uint8_t *stage_odd, int pr) {
+    // both halves (prologue only: the steps below send the two halves two slots apart).
+    auto dma_pair = [&](uint32_t k_pair, uint8_t *stage_even, uint8_t *stage_odd, int pr) {
+        pre_one(k_pair, pr);
         dma_one(stage_even, stage_odd, 2 * pr);
         dma_one(stage_even, stage_odd, 2 * pr + 1);
     };
@@ -537,12 +535,14 @@ void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_
     // of fb_cur hold fragments of `cur`.  Out: fra[0..3] and fb_nxt hold fragments of
     // `nxt`.  A fragments 4..7 of `cur` are fetched in slots 0..3 (first needed in
     // slot 8).  Behind the barrier, slots 10..13 fetch the 12 fragments the next step
-    // starts with, in the order it needs them; fra[0..3] are dead by then.  Slots 0, 4
-    // and 8 carry DMA pairs p0, p0+1, p0+2 of the slice pair (ea, oa, ka); slot 12
-    // carries DMA pair p3 of the slice pair (eb, ob, kb).  An odd step t sends DMA
-    // pairs 1..4 of slices (t+3, t+4); an even step t sends pairs 5..7 of slices
-    // (t+2, t+3) and pair 0 of slices (t+4, t+5), whose second stage is the one this
-    // step has just finished reading.
+    // starts with, in the order it needs them; fra[0..3] are dead by then.  Every
+    // even slot sends one DMA: slots 0..10 the two halves of DMA pairs p0, p0+1, p0+2
+    // of the slice pair (ea, oa, ka), slots 12 and 14 those of DMA pair p3 of the slice
+    // pair (eb, ob, kb); the fenced address of a pair is computed in the slot of its
+    // first half, before that slot's MFMAs.  An odd step t sends DMA pairs 1..4 of
+    // slices (t+3, t+4); an even step t sends pairs 5..7 of slices (t+2, t+3) and pair 0
+    // of slices (t+4, t+5), whose second stage is the one this step has just finished
+    // reading.
     auto step = [&](const uint8_t *cur, const uint8_t *nxt, bf16x8 (&fb_cur)[RT], bf16x8 (&fb_nxt)[RT], bool odd,
                     uint8_t *ea, uint8_t *oa, uint32_t ka, uint8_t *eb, uint8_t *ob, uint32_t kb) {
         const int p0 = odd ? 1 : 5, p3 = odd ? 4 : 0;
@@ -580,13 +580,11 @@ void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_
     auto clamp_k = [&](uint32_t k) { return k < k_last ? k : k_last; };   // past the end: refetch the last pair, unused
 #pragma unroll
     for (int pr = 0; pr < 8; ++pr) {                     // slices 0 and 1
-        pre_pair(0, pr);
-        dma_pair(ring0, ring1, pr);
+        dma_pair(0, ring0, ring1, pr);
     }
 #pragma unroll
     for (int pr = 0; pr < 5; ++pr) {                     // slices 2 and 3, DMA pairs 0..4
-        pre_pair(clamp_k(2 * RK), pr);
-        dma_pair(ring2, ring3, pr);
+        dma_pair(clamp_k(2 * RK), ring2, ring3, pr);
     }
     GD_RING_BARRIER(GD_WAIT_VM10);                       // slices 0 and 1 have landed
 #pragma unroll
