@@ -14,12 +14,10 @@
 //                advances in slices of 32 through a ring of five 32 KiB LDS stages
 //                filled by global_load_lds_dwordx4 (no staging registers, no LDS
 //                store instructions); described in front of the kernel.
-//   k_gemm_dma   (other multiples of the tile) v_mfma_f32_32x32x16_bf16, K in steps
-//                of 64 through two LDS stages of 64 KiB, same global -> LDS copies;
-//                LDS rows are 128 bytes, their eight 16-byte granules XOR-swizzled
-//                with half the row number; each lane picks the global granule that
-//                belongs in the LDS slot the hardware assigns to it, which is how
-//                the swizzle is applied.
+//   k_gemm_units (other multiples of the tile: K % 64 == 0, operands 16-byte
+//                aligned) same MFMA shape and copies, a ring of five operand blocks
+//                of K = 64 and one barrier per 64 k; as fast as k_gemm_ring when the
+//                chip is not power limited, 1 % slower on N(0,1) data.
 //   k_gemm_nk256 (ragged shapes) stages through registers so that out-of-range
 //                rows and the K tail can be zero-filled.
 //   k_gemm_generic  any shape, alignment and layout of B: one thread per entry.
@@ -217,167 +215,9 @@ void k_gemm_nk256(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles
 // K % 64 == 0; A, B, C 16-byte aligned.
 #define GD_LDS __attribute__((address_space(3)))
 
-template <int V>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
-void k_gemm_dma(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_n)
-{
-    const Fence<V> F(fa);
-    __shared__ __attribute__((aligned(1024))) uint8_t stage0[STAGE_BYTES];
-    __shared__ __attribute__((aligned(1024))) uint8_t stage1[STAGE_BYTES];
-
-    const uint32_t tid = threadIdx.x;
-    const uint32_t lane = tid & 63;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const uint32_t wm = wave >> 1, wn = wave & 1;
-
-    uint32_t lin = blockIdx.x;
-    const uint32_t nblk = gridDim.x;
-    if ((nblk & 7) == 0) lin = (lin & 7) * (nblk >> 3) + (lin >> 3);
-    const uint32_t width = GROUP_M * tiles_n;
-    const uint32_t first_m = (lin / width) * GROUP_M;
-    const uint32_t gsize = (tiles_m - first_m < GROUP_M) ? tiles_m - first_m : GROUP_M;
-    const uint32_t m0 = (first_m + (lin % width) % gsize) * BM;
-    const uint32_t n0 = ((lin % width) / gsize) * BN;
-
-    // One DMA instruction fills 1 KiB of LDS = 8 tile rows; lane l lands in row l/8,
-    // slot l%8 of chunk c, so it fetches granule (l%8) ^ ((row/2) & 7) of that row,
-    // row = 8c + l/8: the key is (4c + l/16) & 7, one value for even c, one for odd c.
-    // Wavefront w moves rows [64w, 64w+64) of the A tile and of the B tile: 8 + 8
-    // instructions.
-    const uint32_t drow = wave * 64 + (lane >> 3);
-    const uint32_t dgran[2] = {(lane & 7) ^ (lane >> 4), (lane & 7) ^ (4 + (lane >> 4))};
-    const uint64_t a_row = p.A + 2 * (uint64_t)(m0 + drow) * p.K;
-    const uint64_t b_row = p.B + 2 * (uint64_t)(n0 + drow) * p.K;
-    const uint64_t a_lane[2] = {a_row + 16 * dgran[0], a_row + 16 * dgran[1]};
-    const uint64_t b_lane[2] = {b_row + 16 * dgran[0], b_row + 16 * dgran[1]};
-    const uint64_t chunk_step = 2 * 8 * (uint64_t)p.K;      // 8 rows further down
-    auto dma_tile = [&](uint8_t *stage, uint32_t k0) {
-        GD_LDS uint8_t *dst = (GD_LDS uint8_t *)stage + wave * (64 * 128);
-#pragma unroll
-        for (int c = 0; c < 8; ++c) {
-            const uint64_t uni = c * chunk_step + 2 * (uint64_t)k0;          // wave-uniform part
-            F.ld_to_lds16(a_lane[c & 1], uni, dst + c * 1024);
-            F.ld_to_lds16(b_lane[c & 1], uni, dst + A_BYTES + c * 1024);
-        }
-    };
-
-    f32x16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
-    const uint32_t frow = lane & 31, fhalf = lane >> 5;
-    const uint32_t a_frag = (wm * 128 + frow) * 128;
-    const uint32_t b_frag = A_BYTES + (wn * 128 + frow) * 128;
-    uint32_t gsw[BK / 16];
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) gsw[kk] = ((2 * kk + fhalf) ^ ((frow >> 1) & 7)) << 4;
-
-    bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-    auto frags = [&](const uint8_t *stage, int kk, bf16x8 (&fa_)[TM], bf16x8 (&fb_)[TN]) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-            fa_[i] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(stage + a_frag + i * 32 * 128 + gsw[kk]));
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-            fb_[j] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(stage + b_frag + j * 32 * 128 + gsw[kk]));
-    };
-    auto mfmas = [&](const bf16x8 (&fa_)[TM], const bf16x8 (&fb_)[TN]) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa_[i], fb_[j], acc[i][j], 0, 0, 0);
-    };
-    // One K step: MFMAs on `cur` (its substep-0 fragments are already in fa0/fb0),
-    // tile at k_next streams into `nxt` meanwhile; leaves substep 0 of `nxt` in fa0/fb0.
-    // Issue order inside a region: one MFMA, then one fragment load (or two DMA
-    // loads), and so on, so that the matrix pipe never waits for the other units.
-    auto interleave_ds = [&]() {
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // 1 MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    // 1 DS read
-        }
-    };
-    auto step = [&](uint8_t *cur, uint8_t *nxt, uint32_t k_next) {
-        __builtin_amdgcn_sched_barrier(0);
-        {   // substep 0, written out: per pair of MFMAs one fragment load and two DMA loads
-            GD_LDS uint8_t *dst = (GD_LDS uint8_t *)nxt + wave * (64 * 128);
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                if (q < TM)
-                    fa1[q] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(cur + a_frag + q * 32 * 128 + gsw[1]));
-                else
-                    fb1[q - TM] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(cur + b_frag + (q - TM) * 32 * 128 + gsw[1]));
-                const uint64_t uni = q * chunk_step + 2 * (uint64_t)k_next;   // wave-uniform part
-                F.ld_to_lds16(a_lane[q & 1], uni, dst + q * 1024);
-                F.ld_to_lds16(b_lane[q & 1], uni, dst + A_BYTES + q * 1024);
-#pragma unroll
-                for (int e = 2 * q; e < 2 * q + 2; ++e)
-                    acc[e / TN][e % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[e / TN], fb0[e % TN], acc[e / TN][e % TN], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        frags(cur, 2, fa0, fb0);
-        mfmas(fa1, fb1);
-        interleave_ds();
-        __builtin_amdgcn_sched_barrier(0);
-        frags(cur, 3, fa1, fb1);
-        mfmas(fa0, fb0);
-        interleave_ds();
-        __builtin_amdgcn_sched_barrier(0);
-        __syncthreads();                // waits for this wavefront's DMA too: `nxt` is complete, `cur` is free
-        __builtin_amdgcn_sched_barrier(0);
-        frags(nxt, 0, fa0, fb0);
-        mfmas(fa1, fb1);
-        interleave_ds();
-        __builtin_amdgcn_sched_barrier(0);
-    };
-
-    const uint32_t ksteps = p.K / BK;
-    const uint32_t k_last = p.K - BK;
-    dma_tile(stage0, 0);
-    __syncthreads();
-    frags(stage0, 0, fa0, fb0);
-    uint32_t t = 0;
-    for (; t + 1 < ksteps; t += 2) {
-        uint32_t k1 = (t + 1) * BK, k2 = (t + 2) * BK;
-        step(stage0, stage1, k1);
-        step(stage1, stage0, k2 < k_last ? k2 : k_last);   // past the end: refetch the last tile, unused
-    }
-    if (t < ksteps) step(stage0, stage1, k_last);
-    __syncthreads();
-
-    // Epilogue: see k_gemm_nk256.  Wavefronts 0,1 park in stage0, 2,3 in stage1.
-    uint8_t *park = (wave < 2 ? stage0 : stage1) + (wave & 1) * (128 * 256);
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const uint32_t row = 32 * i + 8 * (r / 4) + 4 * fhalf + (r & 3);
-                const uint32_t col = 32 * j + frow;
-                *(uint16_t *)(park + row * 256 + col * 2) = (uint16_t)gemm_f32_to_bf16(acc[i][j][r]);
-            }
-    __syncthreads();
-    const uint32_t orow = lane >> 4, og = lane & 15;
-#pragma unroll 4
-    for (int it = 0; it < 32; ++it) {
-        const uint32_t row = orow + 4 * it;
-        const uint32_t m = m0 + wm * 128 + row, n = n0 + wn * 128 + og * 8;
-        const u32x4 v = *(const u32x4 *)(park + row * 256 + og * 16);
-        F.template st<u32x4>(p.C + 2 * ((uint64_t)m * p.N + n), v);
-    }
-}
-
 
 // ---- tiled MFMA kernel, five-stage ring of K=32 slices -----------------------------------------
-// Same 256 x 256 tile and wavefront layout as k_gemm_dma, but K advances in
+// 256 x 256 tile, 2 x 2 wavefronts of 128 x 128 each.  K advances in
 // slices of 32 through a ring of five 32 KiB LDS stages (A 256x32 + B 256x32),
 // all 160 KiB of the compute unit.  LDS rows are 64 bytes; granule g of row r sits
 // in slot g ^ ring_swizzle(r/4).
@@ -395,7 +235,8 @@ void k_gemm_dma(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_n
 // therefore spread evenly over the two steps (32 MFMA pairs) in which both target
 // stages are free: pair (t+3, t+4), t odd, goes out between the barrier of step
 // t-1 and the barrier of step t+1, two DMAs every fourth MFMA pair.
-// Requirements: as k_gemm_dma, and K % 128 == 0, K <= 2^22, A and B 128-byte aligned.
+// Requirements: M and N multiples of 256, K % 128 == 0, K <= 2^22, B stored N x K,
+// A and B 128-byte aligned, C 16-byte aligned.
 constexpr int RK = 32;                       // K per ring step
 constexpr int RSTAGE = (BM + BN) * RK * 2;   // 32 KiB
 constexpr int RA = BM * RK * 2;              // 16 KiB: offset of the B slice inside a stage
@@ -656,6 +497,205 @@ void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_
     }
 }
 
+// ---- tiled MFMA kernel, ring of five operand blocks of K = 64 -----------------------------------
+// Same tile, wavefront layout, MFMA shape and epilogue as k_gemm_ring.  The ring's
+// unit is one operand block: 256 rows x 64 k (LDS rows of 128 bytes = whole cache
+// lines, 32 KiB), A and B blocks alternating: unit n is A_{n/2} for even n, B_{n/2}
+// for odd n, and lives in LDS slot n % 5.  One step takes K = 64 (two MFMA
+// substeps, 128 MFMAs per wavefront) and one workgroup barrier, which does both
+// jobs: it publishes the two units of the next step and it releases the two units
+// just read, into which the DMAs for units 2j+5 and 2j+6 then go, one every second
+// slot until the next barrier.  A DMA instruction moves 8 rows x 128 bytes.
+// Granule g of row r sits in slot g ^ 2*h(r/2 % 8), h = 0,1,0,1,2,3,2,3: within each
+// of the lane sets a 128-bit LDS read is served in (see ring_swizzle) the 8 rows
+// of equal parity then use 8 different slots.
+// Requirements: M and N multiples of 256, K % 64 == 0, K <= 2^22, B stored N x K,
+// A, B and C 16-byte aligned.
+constexpr int UK = 64;                       // K per step
+constexpr int UBYTES = BM * UK * 2;          // 32 KiB per unit
+constexpr int UBAR = 26;                     // slot (of 32) in front of which the barrier sits
+
+__device__ __forceinline__ uint32_t unit_swizzle(uint32_t row)
+{
+    const uint32_t x = (row >> 1) & 7;
+    return 2 * ((x & 1) | ((x >> 1) & 2));
+}
+
+template <int V>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void k_gemm_units(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_n)
+{
+    const Fence<V> F(fa);
+    __shared__ __attribute__((aligned(1024))) uint8_t u0[UBYTES];
+    __shared__ __attribute__((aligned(1024))) uint8_t u1[UBYTES];
+    __shared__ __attribute__((aligned(1024))) uint8_t u2[UBYTES];
+    __shared__ __attribute__((aligned(1024))) uint8_t u3[UBYTES];
+    __shared__ __attribute__((aligned(1024))) uint8_t u4[UBYTES];
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = tid & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t wm = wave >> 1, wn = wave & 1;
+
+    uint32_t lin = blockIdx.x;
+    const uint32_t nblk = gridDim.x;
+    if ((nblk & 7) == 0) lin = (lin & 7) * (nblk >> 3) + (lin >> 3);
+    const uint32_t width = GROUP_M * tiles_n;
+    const uint32_t first_m = (lin / width) * GROUP_M;
+    const uint32_t gsize = (tiles_m - first_m < GROUP_M) ? tiles_m - first_m : GROUP_M;
+    const uint32_t m0 = (first_m + (lin % width) % gsize) * BM;
+    const uint32_t n0 = ((lin % width) / gsize) * BN;
+
+    // DMA c (0..7) of a unit: wavefront w moves rows 64w + 8c + l/8; lane l lands in
+    // slot l%8 of its row and fetches granule (l%8) ^ unit_swizzle(row).  (row/2) % 8 =
+    // (4c + l/16) % 8, so there is one lane offset for even c and one for odd c.
+    const uint32_t drow = wave * 64 + (lane >> 3);
+    uint32_t lane_off[2];
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+        const uint32_t gran = (lane & 7) ^ unit_swizzle(8 * par + (lane >> 3));
+        lane_off[par] = 2 * (drow * p.K + gran * 8);           // below 2^32: the launcher bounds K
+    }
+    const uint64_t a_tile = p.A + 2 * (uint64_t)m0 * p.K;
+    const uint64_t b_tile = p.B + 2 * (uint64_t)n0 * p.K;
+    const uint64_t chunk_step = 2 * 8 * (uint64_t)p.K;           // 8 rows further down
+    typename Fence<V>::SplitHandle pre;
+    auto dma = [&](bool is_b, uint32_t k0, uint8_t *unit, int c) {
+        const uint64_t uni = (is_b ? b_tile : a_tile) + c * chunk_step + 2 * (uint64_t)k0;
+        pre = F.template fenced_split<16>(uni, lane_off[c & 1]);
+        GD_LDS uint8_t *dst = (GD_LDS uint8_t *)unit + wave * 8192 + c * 1024;
+        F.template dma16_unordered<0>(pre, (uint32_t)(uintptr_t)dst);
+    };
+
+    f32x4 acc[RT][RT];
+#pragma unroll
+    for (int i = 0; i < RT; ++i)
+#pragma unroll
+        for (int j = 0; j < RT; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0f;
+
+    // Fragment i of an operand, substep kk: lane l holds row 16*i + l%16, granule
+    // 4*kk + l/16.  16*i is a multiple of 16, so the swizzle term of a lane does not
+    // depend on i and fragments sit at immediate offsets of 2 KiB.
+    const uint32_t l16 = lane & 15, lg = lane >> 4;
+    uint32_t a_frag[2], b_frag[2];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+        const uint32_t slot = ((4 * kk) | lg) ^ unit_swizzle(l16);
+        a_frag[kk] = (wm * 128 + l16) * 128 + slot * 16;
+        b_frag[kk] = (wn * 128 + l16) * 128 + slot * 16;
+    }
+    bf16x8 fra[RT], fbx[RT], fby[RT];        // A fragments; B fragments of substep 0 and of substep 1
+    auto load_a = [&](const uint8_t *unit, int kk, int i) {
+        fra[i] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(unit + a_frag[kk] + i * 2048));
+    };
+    auto load_b = [&](const uint8_t *unit, int kk, int j, bf16x8 (&fb_)[RT]) {
+        fb_[j] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(unit + b_frag[kk] + j * 2048));
+    };
+    auto mfma_quad = [&](int sl, const bf16x8 (&fb_)[RT]) {
+        const int i = sl >> 1;
+#pragma unroll
+        for (int j = 4 * (sl & 1); j < 4 * (sl & 1) + 4; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb_[j], fra[i], acc[i][j], 0, 0, 0);
+    };
+    // One step of 32 slots, four MFMAs (64 clocks) each: slots 0..15 substep 0 (fbx),
+    // slots 16..31 substep 1 (fby).  In: fra[0..3] and fbx hold substep-0 fragments of
+    // (ac, bc).  Out: the same for (an, bn).
+    // Fragment loads: A 4..7 of substep 0 in slots 0..3; B of substep 1 in slots 4..11,
+    // A 0..3 of substep 1 in slots 8..11 (their registers are free from slot 8), A 4..7
+    // of substep 1 in slots 16..19; behind the barrier, slots 26..29, the 12 fragments
+    // the next step starts with.
+    // DMAs, one every second slot: slots 0..8 finish unit B_{j+1} (DMAs 3..7; its first
+    // three went out behind the previous barrier), slots 10..24 send A_{j+2}, slots
+    // 26..30 start B_{j+2} in the unit A_j has just left.
+    auto step = [&](const uint8_t *ac, const uint8_t *bc, const uint8_t *an, uint8_t *bn, uint8_t *a2,
+                    uint8_t *ac_w, uint32_t k1, uint32_t k2) {
+#pragma unroll
+        for (int sl = 0; sl < 32; ++sl) {
+            if (sl == UBAR) {
+                // Units A_{j+1}, B_{j+1} must have landed: everything but the 8 DMAs of
+                // A_{j+2}.  All fragment loads of this step have been issued by slot 19.
+                GD_RING_BARRIER(0x0078);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (sl < 4) load_a(ac, 0, 4 + sl);
+            if (sl >= 4 && sl < 12) load_b(bc, 1, sl - 4, fby);
+            if (sl >= 8 && sl < 12) load_a(ac, 1, sl - 8);
+            if (sl >= 16 && sl < 20) load_a(ac, 1, 4 + sl - 16);
+            if (sl == UBAR) { load_b(bn, 0, 0, fbx); load_a(an, 0, 0); load_b(bn, 0, 1, fbx); }
+            if (sl == UBAR + 1) { load_b(bn, 0, 2, fbx); load_b(bn, 0, 3, fbx); load_b(bn, 0, 4, fbx); }
+            if (sl == UBAR + 2) { load_b(bn, 0, 5, fbx); load_b(bn, 0, 6, fbx); load_b(bn, 0, 7, fbx); }
+            if (sl == UBAR + 3) { load_a(an, 0, 1); load_a(an, 0, 2); load_a(an, 0, 3); }
+            if (sl < 16) mfma_quad(sl, fbx);
+            else mfma_quad(sl - 16, fby);
+            if ((sl & 1) == 0) {
+                constexpr int NB = (32 - UBAR) / 2;            // DMAs of B_{j+2} sent behind the barrier
+                if (sl >= UBAR) dma(true, k2, ac_w, (sl - UBAR) / 2);
+                else if (sl / 2 < 8 - NB) dma(true, k1, bn, NB + sl / 2);
+                else if (sl / 2 < 16 - NB) dma(false, k2, a2, sl / 2 - (8 - NB));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    const uint32_t nsteps = p.K / UK;
+    const uint32_t k_last = p.K - UK;
+    auto clamp_k = [&](uint32_t k) { return k < k_last ? k : k_last; };   // past the end: refetch the last block, unused
+#pragma unroll
+    for (int c = 0; c < 8; ++c) dma(false, 0, u0, c);                    // A_0
+#pragma unroll
+    for (int c = 0; c < 8; ++c) dma(true, 0, u1, c);                     // B_0
+#pragma unroll
+    for (int c = 0; c < 8; ++c) dma(false, clamp_k(UK), u2, c);          // A_1
+#pragma unroll
+    for (int c = 0; c < (32 - UBAR) / 2; ++c) dma(true, clamp_k(UK), u3, c);   // B_1, its first DMAs
+    GD_RING_BARRIER(0x0078 + (32 - UBAR) / 2);                           // vmcnt <= 8 + those: A_0 and B_0 have landed
+#pragma unroll
+    for (int j = 0; j < RT; ++j) load_b(u1, 0, j, fbx);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) load_a(u0, 0, i);
+    // Unit n lives in u[n % 5]: step j reads u[2j % 5] and u[(2j+1) % 5], the next step's
+    // units are the two after them, A_{j+2} goes into the fifth.  Period: 5 steps.
+    for (uint32_t j = 0; j < nsteps;) {
+        step(u0, u1, u2, u3, u4, u0, clamp_k((j + 1) * UK), clamp_k((j + 2) * UK));
+        ++j;
+        if (j < nsteps) { step(u2, u3, u4, u0, u1, u2, clamp_k((j + 1) * UK), clamp_k((j + 2) * UK)); ++j; }
+        if (j < nsteps) { step(u4, u0, u1, u2, u3, u4, clamp_k((j + 1) * UK), clamp_k((j + 2) * UK)); ++j; }
+        if (j < nsteps) { step(u1, u2, u3, u4, u0, u1, clamp_k((j + 1) * UK), clamp_k((j + 2) * UK)); ++j; }
+        if (j < nsteps) { step(u3, u4, u0, u1, u2, u3, clamp_k((j + 1) * UK), clamp_k((j + 2) * UK)); ++j; }
+    }
+    // The compiler does not know of the ring's DMAs: wait for the last ones by hand
+    // (vmcnt = 0, lgkmcnt = 0) before the units are reused to park the result.
+    __builtin_amdgcn_s_waitcnt(0x0070);
+    __syncthreads();
+
+    // Epilogue: as in k_gemm_ring.
+    uint8_t *park = wave == 0 ? u0 : wave == 1 ? u1 : wave == 2 ? u2 : u3;
+#pragma unroll
+    for (int i = 0; i < RT; ++i)
+#pragma unroll
+        for (int j = 0; j < RT; ++j) {
+            const f32x2 lo = {acc[i][j][0], acc[i][j][1]};
+            const f32x2 hi = {acc[i][j][2], acc[i][j][3]};
+            u32x2 w;
+            w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+            w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
+            const uint32_t row = 16 * i + l16;
+            const uint32_t unit = (4 * j + lg) ^ (2 * l16);
+            *(u32x2 *)(park + row * 256 + unit * 8) = w;
+        }
+    __syncthreads();
+    const uint32_t orow = lane >> 4, og = lane & 15;
+#pragma unroll 4
+    for (int it = 0; it < 32; ++it) {
+        const uint32_t row = orow + 4 * it;
+        const uint32_t m = m0 + wm * 128 + row, n = n0 + wn * 128 + og * 8;
+        const u32x4 v = *(const u32x4 *)(park + row * 256 + ((og ^ (row & 15)) << 4));
+        F.template st<u32x4>(p.C + 2 * ((uint64_t)m * p.N + n), v);
+    }
+}
+
 // ---- launcher ---------------------------------------------------------------------------
 
 int launch_gemm_bf16(const void *args, const FenceArgs &f, int variant, const Shape &shape,
@@ -669,13 +709,14 @@ int launch_gemm_bf16(const void *args, const FenceArgs &f, int variant, const Sh
         const uint32_t tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
         const uint64_t tiles = (uint64_t)tiles_m * tiles_n;
         if (tiles > 0x7fffffffull) return GD_ESHAPE;
-        const bool edge = (p.M % BM) || (p.N % BN) || (p.K % BK) || (p.C & 15);
+        // the ring kernels keep per-lane byte offsets of up to 256 rows in 32 bits
+        const bool edge = (p.M % BM) || (p.N % BN) || (p.K % BK) || (p.C & 15) || p.K > (1u << 22);
         const dim3 grid((uint32_t)tiles), block(256);
 #define GD_GEMM_CASE(VAR)                                                                                         \
     case VAR:                                                                                                     \
         if (edge) hipLaunchKernelGGL((k_gemm_nk256<VAR, true>), grid, block, 0, stream, p, f, tiles_m, tiles_n);  \
-        else if (p.K % 128 == 0 && p.K <= (1u << 22) && ((p.A | p.B) & 127) == 0) hipLaunchKernelGGL((k_gemm_ring<VAR>), grid, block, 0, stream, p, f, tiles_m, tiles_n); \
-        else hipLaunchKernelGGL((k_gemm_dma<VAR>), grid, block, 0, stream, p, f, tiles_m, tiles_n);               \
+        else if (p.K % 128 == 0 && ((p.A | p.B) & 127) == 0) hipLaunchKernelGGL((k_gemm_ring<VAR>), grid, block, 0, stream, p, f, tiles_m, tiles_n); \
+        else hipLaunchKernelGGL((k_gemm_units<VAR>), grid, block, 0, stream, p, f, tiles_m, tiles_n);             \
         break;
         switch (variant) {
             GD_GEMM_CASE(V_NONE)

@@ -417,7 +417,9 @@ def test_rmsnorm_against_oracle(rows, cols, shift):
                                            (16, 16, 0, 1),
                                            # every way the slice ring can end (K/32 mod 10 = 8, 2, 6, 0, 4, 8) and restart
                                            (256, 256, 256, 1), (256, 256, 384, 1), (256, 512, 512, 1), (256, 256, 640, 1),
-                                           (512, 256, 768, 1), (256, 256, 896, 1), (256, 256, 1280, 1)])
+                                           (512, 256, 768, 1), (256, 256, 896, 1), (256, 256, 1280, 1),
+                                           # K % 128 = 64: the ring of K = 64 blocks, every way it can end (K/64 mod 5)
+                                           (256, 256, 320, 1), (256, 512, 448, 1), (256, 256, 576, 1)])
 def test_gemm_against_oracle(M, N, K, b_is_nk):
     r = Rig([8 * MiB, 4 * MiB])
     try:
@@ -463,7 +465,7 @@ def test_gemm_with_wrapping_operand_pointers():
 
 def test_gemm_operands_aligned_to_16_bytes_only():
     """Tile-multiple shape, but A and B are not 128-byte aligned: the launcher must fall back
-    from the slice-ring kernel (which relies on that alignment) to the two-stage one."""
+    from the slice-ring kernel (which relies on that alignment) to the ring of K = 64 blocks."""
     r = Rig([8 * MiB, 4 * MiB])
     try:
         M = N = 256
