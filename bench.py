@@ -323,6 +323,42 @@ def run_c1(torch, gd, si, args):
         res[f"{name}_GBps"] = 2 * 16 * n * launches / dev / 1e9
         res[f"{name}_us_per_round"] = dev / launches * 1e6
         log(f"[c1] {name}: {res[f'{name}_GBps']:.1f} GB/s effective ({dev / launches * 1e6:.2f} us per 2-tenant round)")
+    # The same in-bounds rounds recorded once into a HIP graph (gd_launch_fenced allocates and
+    # synchronises nothing, so it can be captured) and replayed: what a launch-bound caller gains.
+    def graph_us_per_round(mode, rounds=200, replays=5):
+        cap, side = torch.cuda.Stream(), torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        plan = plans[False]
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=cap):
+            cur = torch.cuda.current_stream()
+            side.wait_stream(cur)
+            for _ in range(rounds):
+                for (t, x, y, off, offs, alpha), st in zip(plan, (cur, side)):
+                    gd.gd_launch_fenced(dp.pool, t, gd.GD_K_SAXPY_IDX, gd.gd_args_saxpy_idx(x, y, off, n, alpha * 1e-3, 0), stream=st.cuda_stream, mode=mode)
+            cur.wait_stream(side)
+        for _ in range(2):
+            graph.replay()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(replays):
+            graph.replay()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / (rounds * replays)
+
+    try:
+        upload(plans[False])
+        res["graph_fenced_inbounds_us_per_round"] = graph_us_per_round(gd.GD_FENCE_BITWISE)
+        res["graph_unfenced_inbounds_us_per_round"] = graph_us_per_round(gd.GD_FENCE_NONE)
+        log(f"[c1] graph replay: fenced {res['graph_fenced_inbounds_us_per_round']:.2f} / unfenced "
+            f"{res['graph_unfenced_inbounds_us_per_round']:.2f} us per 2-tenant round")
+    except Exception as ex:                       # informational figure: never lose the run over it
+        res["graph_error"] = repr(ex)
+        log(f"[c1] graph replay failed: {ex!r}")
+        torch.cuda.synchronize()
+
     # literal offsets: the clock is warm from the runs above; fresh inputs, no further warm-up
     global PREWARM_MS
     keep, PREWARM_MS = PREWARM_MS, 0.0
