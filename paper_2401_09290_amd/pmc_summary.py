@@ -1,21 +1,21 @@
 """Turns the rocprofv3 --pmc runs listed in profiles/pmc_fence_overhead_and_traffic.md into that file.
 
 Expects the counter CSVs the commands in the summary write (directories pmc_insts, pmc_fetch, pmc_write,
-pmc_l2, pmc_c2f, pmc_c2w under the directory given as argument, default gpurun_out), averages every counter
+pmc_l2, pmc_c2f, pmc_c2w under the directory given as argument), averages every counter
 per kernel and dispatch, calibrates FETCH_SIZE / WRITE_SIZE on the unfenced copy kernel (whose traffic is
 known) and prints the summary; bench.py reads the line `traffic_bytes_per_launch:` from it.
 
-usage: python -m paper_2401_09290_amd.pmc_summary [DIR] > profiles/pmc_fence_overhead_and_traffic.md
+usage: python -m paper_2401_09290_amd.pmc_summary DIR > profiles/pmc_fence_overhead_and_traffic.md
 """
 import collections
 import csv
 import sys
 
-ROOT = 'gpurun_out'
+ROOT = '.'
 
 
 def load(d, pre, needle="gd::"):
-    d = d.replace('gpurun_out', ROOT, 1)
+    d = f'{ROOT}/{d}'
     rows = list(csv.DictReader(open(f'{d}/{pre}_counter_collection.csv')))
     agg=collections.defaultdict(lambda: collections.defaultdict(list))
     for r in rows:
@@ -27,15 +27,15 @@ def load(d, pre, needle="gd::"):
 def main(root):
     global ROOT
     ROOT = root
-    ins=load('gpurun_out/pmc_insts','p')
-    fe=load('gpurun_out/pmc_fetch','p'); wr=load('gpurun_out/pmc_write','p')
+    ins=load('pmc_insts','p')
+    fe=load('pmc_fetch','p'); wr=load('pmc_write','p')
     cf=1048576.0/fe['k_stream<0, 0>']['FETCH_SIZE']; cw=1048576.0/wr['k_stream<0, 0>']['WRITE_SIZE']
     out=[]
     out.append("# Hardware counters: fenced vs unfenced instruction counts, MFMA utilisation, HBM traffic\n")
-    out.append("All runs on one MI355X box, from the repository root, counters averaged per dispatch; this file is the output of `python -m paper_2401_09290_amd.pmc_summary gpurun_out` after the commands below. Template arguments:")
+    out.append("All runs on one MI355X box, from the repository root, counters averaged per dispatch; this file is the output of `python -m paper_2401_09290_amd.pmc_summary " + ROOT + "` after the commands below. Template arguments:")
     out.append("first = fence variant (0 unfenced, 1 = 32-bit bitwise fence for partitions <= 4 GiB, 2 = 64-bit bitwise fence, 3 = modulo fence, 4 = address checking), second = op/index kind.\n")
     out.append("## Instruction counts per dispatch\n")
-    out.append("Command:\n\n    rocprofv3 --pmc SQ_INSTS_VALU SQ_INSTS_SALU SQ_INSTS_VMEM SQ_INSTS_LDS SQ_WAVES SQ_INSTS_VALU_MFMA_BF16 SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES GRBM_GUI_ACTIVE --output-format csv -d gpurun_out/pmc_insts -o p -- python3 bench.py --configs c3,c4,c2,c1,c5 --steps 3 --warmup 1 --prewarm-ms 0 --no-cpu-baseline\n")
+    out.append("Command:\n\n    rocprofv3 --pmc SQ_INSTS_VALU SQ_INSTS_SALU SQ_INSTS_VMEM SQ_INSTS_LDS SQ_WAVES SQ_INSTS_VALU_MFMA_BF16 SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES GRBM_GUI_ACTIVE --output-format csv -d " + ROOT + "/pmc_insts -o p -- python3 bench.py --configs c3,c4,c2,c1,c5 --steps 3 --warmup 1 --prewarm-ms 0 --no-cpu-baseline\n")
     out.append("kernel | waves | VALU | of which MFMA | SALU | VMEM | LDS | VALU per wave | time us (serialised by the profiler)")
     out.append("---|---|---|---|---|---|---|---|---")
     for k,v in ins.items():
@@ -48,15 +48,15 @@ def main(root):
     for k in ("k_gemm_ring<1>","k_gemm_ring<0>"):
         v=ins[k]; cyc=v['GRBM_GUI_ACTIVE']/8
         out.append(f"* {k}: SQ_VALU_MFMA_BUSY_CYCLES {v['SQ_VALU_MFMA_BUSY_CYCLES']:.0f} (= {v['SQ_INSTS_VALU_MFMA_BF16']:.0f} MFMA x {v['SQ_VALU_MFMA_BUSY_CYCLES']/v['SQ_INSTS_VALU_MFMA_BF16']:.0f} cycles) over {cyc:.0f} shader cycles x 1024 SIMDs = {100*v['SQ_VALU_MFMA_BUSY_CYCLES']/(cyc*1024):.1f} % of the matrix-pipe cycles; shader clock during the kernel {cyc/v['dur_ns']:.2f} GHz (GRBM_GUI_ACTIVE / 8 XCDs / duration), i.e. the chip runs well below its 2.4 GHz peak clock under this load (the counter run serialises dispatches and adds its own overhead; bench.py's timing is the reference for throughput).")
-    l2=load('gpurun_out/pmc_l2','p')
+    l2=load('pmc_l2','p')
     out.append("\n## L2 requests and LDS bank conflicts of the GEMM (8192^3)\n")
-    out.append("Command:\n\n    rocprofv3 --pmc TCP_TCC_READ_REQ_sum TCP_TOTAL_CACHE_ACCESSES_sum TCC_REQ_sum TCC_HIT_sum TCC_MISS_sum TCC_EA0_RDREQ_sum SQ_LDS_BANK_CONFLICT SQ_ACTIVE_INST_LDS --output-format csv -d gpurun_out/pmc_l2 -o p -- python3 bench.py --configs c4 --steps 4 --warmup 1 --prewarm-ms 0 --no-cpu-baseline\n")
+    out.append("Command:\n\n    rocprofv3 --pmc TCP_TCC_READ_REQ_sum TCP_TOTAL_CACHE_ACCESSES_sum TCC_REQ_sum TCC_HIT_sum TCC_MISS_sum TCC_EA0_RDREQ_sum SQ_LDS_BANK_CONFLICT SQ_ACTIVE_INST_LDS --output-format csv -d " + ROOT + "/pmc_l2 -o p -- python3 bench.py --configs c4 --steps 4 --warmup 1 --prewarm-ms 0 --no-cpu-baseline\n")
     for k in ("k_gemm_ring<1>","k_gemm_ring<0>"):
         v=l2[k]
         out.append(f"* {k}: vector-cache accesses (64 B each) {v['TCP_TOTAL_CACHE_ACCESSES_sum']:.0f}; read requests to L2 {v['TCP_TCC_READ_REQ_sum']:.0f} = {v['TCP_TCC_READ_REQ_sum']/(1024*2*256*8192*2/128):.3f} per 128-byte line of operand data a tile reads (8 GiB over all tiles: the two 64-byte halves of a line, fetched by neighbouring DMA instructions, merge into one request); L2 requests {v['TCC_REQ_sum']:.0f}, hits {v['TCC_HIT_sum']:.0f} ({100*v['TCC_HIT_sum']/v['TCC_REQ_sum']:.1f} %), misses {v['TCC_MISS_sum']:.0f}; SQ_LDS_BANK_CONFLICT {v['SQ_LDS_BANK_CONFLICT']:.0f} cycles.")
     gf=(fe['k_gemm_ring<1>']['FETCH_SIZE'], wr['k_gemm_ring<1>']['WRITE_SIZE'])
     out.append("\n## HBM traffic of the streaming kernels (configuration 3 sizes: 2^28 fp32 elements per array)\n")
-    out.append("Commands (one counter group per run):\n\n    rocprofv3 --pmc FETCH_SIZE --output-format csv -d gpurun_out/pmc_fetch -o p -- python3 bench.py --configs c3,c4 --steps 4 --warmup 1 --prewarm-ms 0 --no-cpu-baseline\n    rocprofv3 --pmc WRITE_SIZE --output-format csv -d gpurun_out/pmc_write -o p -- python3 bench.py --configs c3,c4 --steps 4 --warmup 1 --prewarm-ms 0 --no-cpu-baseline\n")
+    out.append("Commands (one counter group per run):\n\n    rocprofv3 --pmc FETCH_SIZE --output-format csv -d " + ROOT + "/pmc_fetch -o p -- python3 bench.py --configs c3,c4 --steps 4 --warmup 1 --prewarm-ms 0 --no-cpu-baseline\n    rocprofv3 --pmc WRITE_SIZE --output-format csv -d " + ROOT + "/pmc_write -o p -- python3 bench.py --configs c3,c4 --steps 4 --warmup 1 --prewarm-ms 0 --no-cpu-baseline\n")
     cf=1048576.0/fe['k_stream<0, 0>']['FETCH_SIZE']; cw=1048576.0/wr['k_stream<0, 0>']['WRITE_SIZE']
     out.append(f"Calibration on the plain copy kernel k_stream<0, 0> (reads 1 GiB = 1048576 KiB, writes 1 GiB): FETCH_SIZE reads {fe['k_stream<0, 0>']['FETCH_SIZE']:.1f}, WRITE_SIZE reads {wr['k_stream<0, 0>']['WRITE_SIZE']:.1f}; scale factors {cf:.5f} (fetch) and {cw:.5f} (write).\n")
     out.append("kernel | FETCH_SIZE raw | WRITE_SIZE raw | HBM bytes per launch (scaled) | algorithmic bytes")
@@ -69,9 +69,9 @@ def main(root):
         out.append(f"{k} | {fe[k]['FETCH_SIZE']:.1f} | {wr[k]['WRITE_SIZE']:.1f} | {b:.0f} | {alg[k]}")
     out.append(f"\nThe fenced triad moves {tri/alg['k_stream<2, 1>']:.4f} x its algorithmic bytes: no re-reads.\n")
     out.append(f"GEMM k_gemm_ring<1> (same runs): FETCH_SIZE {gf[0]:.1f}, WRITE_SIZE {gf[1]:.1f} -> {(gf[0]*cf+gf[1]*cw)*1024/2**20:.0f} MiB leave the L2 towards the last-level cache and HBM per launch, against 384 MiB of operands and result: each XCD works on 4 x 8 tiles at a time, so A is fetched 4 times (once per group of 8 tile columns) and B 8 times (once per XCD): 512 + 1024 MiB.\n")
-    c2f=load('gpurun_out/pmc_c2f','p'); c2w=load('gpurun_out/pmc_c2w','p')
+    c2f=load('pmc_c2f','p'); c2w=load('pmc_c2w','p')
     out.append("## Fabric traffic of the indexed and reduction kernels (configurations 2 and 5)\n")
-    out.append("Commands (same calibration factors as above):\n\n    rocprofv3 --pmc FETCH_SIZE --output-format csv -d gpurun_out/pmc_c2f -o p -- python3 bench.py --configs c2,c5 --steps 4 --warmup 1 --prewarm-ms 0 --no-cpu-baseline\n    rocprofv3 --pmc WRITE_SIZE --output-format csv -d gpurun_out/pmc_c2w -o p -- python3 bench.py --configs c2,c5 --steps 4 --warmup 1 --prewarm-ms 0 --no-cpu-baseline\n")
+    out.append("Commands (same calibration factors as above):\n\n    rocprofv3 --pmc FETCH_SIZE --output-format csv -d " + ROOT + "/pmc_c2f -o p -- python3 bench.py --configs c2,c5 --steps 4 --warmup 1 --prewarm-ms 0 --no-cpu-baseline\n    rocprofv3 --pmc WRITE_SIZE --output-format csv -d " + ROOT + "/pmc_c2w -o p -- python3 bench.py --configs c2,c5 --steps 4 --warmup 1 --prewarm-ms 0 --no-cpu-baseline\n")
     out.append("kernel | FETCH_SIZE raw | WRITE_SIZE raw | bytes per launch past the L2 (scaled) | algorithmic bytes | duration us | traffic rate TB/s")
     out.append("---|---|---|---|---|---|---")
     algo={"k_gather32<1, 1>":16*2**26,"k_gather32<0, 1>":16*2**26,"k_scatter_f32_i64<1>":16*2**26,"k_scatter_f32_i64<0>":16*2**26,"k_gather32<0, 0>":12*2**24,"k_sum_partial<0>":4*2**27,"k_rmsnorm_bf16<0>":4*4096*8192}
@@ -85,4 +85,4 @@ def main(root):
 
 
 if __name__ == "__main__":
-    main(sys.argv[1] if len(sys.argv) > 1 else 'gpurun_out')
+    main(sys.argv[1] if len(sys.argv) > 1 else '.')
