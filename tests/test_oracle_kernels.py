@@ -70,6 +70,28 @@ def test_c_fence_modes_on_random_64bit_addresses():
         assert ok.fence(base, size, a, w, ok.MODE_NONE) == a
 
 
+@pytest.mark.parametrize("width", hm.ACCESS_WIDTHS)
+def test_c_modulo_fence_with_width_against_integer_arithmetic(width):
+    """Section 4.4's modulo rule with the width reading: the remainder is rounded down
+    to a multiple of the access width.  The expected value is written out in Python
+    integers (floor division, no bit tricks) next to the Python model's own value."""
+    # every address around a tiny pool of odd-sized, 256-byte aligned partitions
+    for (base, size) in ((0x40000, 4096 + 256), (0x41100, 4096 + 3 * 256), (0x43000, 7 * 256 + 4096)):
+        for a in range(base - 2 * size - 7, base + 3 * size + 7):
+            want = base + ((a - base) % (1 << 64)) % size // width * width   # the subtraction wraps at 2^64
+            got = ok.fence(base, size, a, width, ok.MODE_MODULO)
+            assert got == want == hm.fence_modulo(a, base, size, width)
+            assert base <= got and got + width <= base + size
+    # random 64-bit addresses, sizes up to 2^40 that are multiples of 256 but not powers of two
+    rnd = random.Random(11 + width)
+    for _ in range(20000):
+        size = 256 * rnd.randint(17, 1 << 32)
+        base = 256 * rnd.randint(1, 1 << 30)
+        a = rnd.getrandbits(64)
+        want = base + ((a - base) % (1 << 64)) % size // width * width
+        assert ok.fence(base, size, a, width, ok.MODE_MODULO) == want == hm.fence_modulo(a, base, size, width)
+
+
 def test_modulo_mode_accepts_unaligned_odd_sized_partitions():
     base, size = 1000, 300            # Section 4.4: modulo needs no alignment
     for a in range(0, 5000):
@@ -192,6 +214,65 @@ def test_negative_offsets_and_indices_are_signed(one_tenant):
         e = k - 64
         want = 2.0 * k + 1000 + k if -n < e <= 0 else 1000 + k
         assert got[k] == want
+
+
+def test_gather_i32_sign_extends_negative_and_large_indices(one_tenant):
+    """Signed 32-bit indices: the element address is tab + 4*idx with idx sign-extended to
+    64 bits, then fenced.  Expected values come from NumPy indexing of the partition seen
+    as an array of words, at word number ((tab - base)/4 + idx) mod (size/4)."""
+    pool, row, _ = one_tenant
+    base, size = row
+    words = size // 4
+    n = 4096
+    g = si.rng(0, 7)
+    pool.view(base, np.uint32, words)[:] = g.integers(0, 1 << 32, size=words, dtype=np.uint64).astype(np.uint32)
+    tab, idxp, out = base + 300 * KiB, base + 512 * KiB, base + 768 * KiB
+    idx = np.concatenate([
+        g.integers(-(1 << 31), 0, size=n // 4, dtype=np.int64),          # negative
+        g.integers(1 << 30, 1 << 31, size=n // 4, dtype=np.int64),       # above 2^30
+        g.integers(-70000, 70000, size=n // 4, dtype=np.int64),          # around the table start
+        np.array([-(1 << 31), (1 << 31) - 1, -1, 0], dtype=np.int64),
+        g.integers(0, 1 << 16, size=n // 4 - 4, dtype=np.int64)]).astype(np.int32)
+    assert (idx < 0).sum() > n // 4 and (idx.astype(np.int64) > (1 << 30)).sum() >= n // 4
+    pool.view(idxp, np.int32, n)[:] = idx
+    pool.view(out, np.uint32, n)[:] = 0
+    image = pool.view(base, np.uint32, words).copy()
+    for mode in (ok.MODE_BITWISE, ok.MODE_MODULO):
+        esc, vio, wrapped = pool.run("gather32_i32", row, mode, out, tab, idxp, n)
+        assert esc == 0 and vio == 0 and wrapped > n // 2
+        word = ((tab - base) // 4 + idx.astype(np.int64)) % words          # floor modulo on signed values
+        want = image.copy()                     # in element order: a load may hit a word of `out` written earlier
+        for i in range(n):
+            want[(out - base) // 4 + i] = want[word[i]]
+        assert np.array_equal(pool.view(base, np.uint32, words), want)
+        pool.view(out, np.uint32, n)[:] = 0
+    # With a power-of-two partition below 2^34 bytes the fence masks away exactly the bits in which a
+    # sign-extended and a zero-extended index differ.  Two settings where they do show:
+    # (1) no fence: a small negative index reads in front of the table;
+    small = -np.arange(1, n + 1, dtype=np.int32)
+    pool.view(idxp, np.int32, n)[:] = small
+    assert pool.run("gather32_i32", row, ok.MODE_NONE, out, tab, idxp, n) == (0, 0, 0)
+    assert np.array_equal(pool.view(out, np.uint32, n), image[(tab - base) // 4 + small.astype(np.int64)])
+    # (2) the modulo fence on a partition whose size does not divide 2^34 (Section 4.4: any size).
+    odd_base, odd_size = base + 256, 900 * KiB + 256
+    pool.view(idxp, np.int32, n)[:] = idx
+    pool.view(out, np.uint32, n)[:] = 0
+    before = pool.mem.copy()
+    esc, vio, _ = pool.run("gather32_i32", (odd_base, odd_size), ok.MODE_MODULO, out, tab, idxp, n)
+    assert esc == 0 and vio == 0
+    mem_words = before.view(np.uint32)
+    want, want_zext = [], []
+    for k in idx.tolist():
+        a = odd_base + ((tab + 4 * k - odd_base) % (1 << 64)) % odd_size // 4 * 4
+        z = odd_base + ((tab + 4 * (k % (1 << 32)) - odd_base) % (1 << 64)) % odd_size // 4 * 4
+        want.append(mem_words[(a - pool.pool_base) // 4])
+        want_zext.append(mem_words[(z - pool.pool_base) // 4])
+    # `out` and the index array lie inside this partition too: skip loads that hit words `out` already holds
+    clean = np.array([not (out <= odd_base + ((tab + 4 * k - odd_base) % (1 << 64)) % odd_size < out + 4 * n)
+                      for k in idx.tolist()])
+    got = pool.view(out, np.uint32, n)
+    assert clean.mean() > 0.9 and np.array_equal(got[clean], np.array(want, np.uint32)[clean])
+    assert not np.array_equal(got[clean], np.array(want_zext, np.uint32)[clean])
 
 
 def test_sum_matches_fsum(one_tenant):
