@@ -286,25 +286,37 @@ double gdo_sum_f32_exact(gdo_ctx *c, uint64_t in, uint64_t n)
 }
 
 /* Row-wise RMS normalisation of a row-major rows x cols bfloat16 matrix:
- * y[r,j] = bf16( x[r,j] / sqrt(mean_j(x[r,j]^2) + eps) * g[j] ). */
+ * y[r,j] = bf16( x[r,j] / sqrt(mean_j(x[r,j]^2) + eps) * g[j] ).
+ *
+ * Logical thread (r, j) produces y[r,j]: it reads all of row r (the mean needs
+ * every value), then g[j], then stores.  Under address checking (mode 3) a
+ * thread returns at its first refused access (Section 4.3, last sentence;
+ * Section 4.4), so a refused access to x[r,k] stops all `cols` threads of the row
+ * -- each of them meets it -- and each counts one violation; a refused g[j] or
+ * y[r,j] stops that one thread. */
 void gdo_rmsnorm_bf16(gdo_ctx *c, uint64_t y, uint64_t x, uint64_t g,
                       uint64_t rows, uint64_t cols, double eps)
 {
     for (uint64_t r = 0; r < rows; r++) {
         double ss = 0.0;
+        int row_read = 1;
         for (uint64_t j = 0; j < cols; j++) {
             uint16_t h;
-            ld(c, x + 2 * (r * cols + j), 2, &h);
+            if (!ld(c, x + 2 * (r * cols + j), 2, &h)) { row_read = 0; break; }
             double v = bf16_to_double(h);
             ss += v * v;
+        }
+        if (!row_read) {
+            c->violations += cols - 1;     /* the other threads of the row stop at the same access */
+            continue;
         }
         double inv = 1.0 / sqrt(ss / (double)cols + eps);
         for (uint64_t j = 0; j < cols; j++) {
             uint16_t h, hg, o;
-            ld(c, x + 2 * (r * cols + j), 2, &h);
-            ld(c, g + 2 * j, 2, &hg);
+            if (!ld(c, x + 2 * (r * cols + j), 2, &h)) continue;    /* passed above */
+            if (!ld(c, g + 2 * j, 2, &hg)) continue;
             o = double_to_bf16(bf16_to_double(h) * inv * bf16_to_double(hg));
-            st(c, y + 2 * (r * cols + j), 2, &o);
+            if (!st(c, y + 2 * (r * cols + j), 2, &o)) continue;
         }
     }
 }
@@ -313,7 +325,11 @@ void gdo_rmsnorm_bf16(gdo_ctx *c, uint64_t y, uint64_t x, uint64_t g,
  * A is row-major M x K.  B is row-major K x N if b_is_nk == 0, or stored as
  * N x K (each column of B contiguous) if b_is_nk != 0.  C is row-major M x N.
  * Only rows [m0, m1) and columns [n0, n1) of C are computed, so that a test
- * can ask for a slab or single entries of a large product. */
+ * can ask for a slab or single entries of a large product.
+ *
+ * Logical thread (m, n) produces C[m,n] from row m of A and column n of B; under
+ * address checking (mode 3) it returns at its first refused access and stores
+ * nothing (one violation per stopped thread). */
 void gdo_gemm_bf16(gdo_ctx *c, uint64_t C, uint64_t A, uint64_t B,
                    uint64_t M, uint64_t N, uint64_t K, int32_t b_is_nk,
                    uint64_t m0, uint64_t m1, uint64_t n0, uint64_t n1)
@@ -322,14 +338,16 @@ void gdo_gemm_bf16(gdo_ctx *c, uint64_t C, uint64_t A, uint64_t B,
     for (uint64_t m = m0; m < m1; m++) {
         for (uint64_t n = n0; n < n1; n++) {
             double acc = 0.0;
+            int stopped = 0;
             for (uint64_t k = 0; k < K; k++) {
                 uint16_t ha, hb;
-                ld(c, A + 2 * (m * K + k), 2, &ha);
-                ld(c, B + 2 * (b_is_nk ? n * K + k : k * N + n), 2, &hb);
+                if (!ld(c, A + 2 * (m * K + k), 2, &ha)) { stopped = 1; break; }
+                if (!ld(c, B + 2 * (b_is_nk ? n * K + k : k * N + n), 2, &hb)) { stopped = 1; break; }
                 acc += bf16_to_double(ha) * bf16_to_double(hb);
             }
+            if (stopped) continue;
             uint16_t o = double_to_bf16(acc);
-            st(c, C + 2 * (m * N + n), 2, &o);
+            if (!st(c, C + 2 * (m * N + n), 2, &o)) continue;
         }
     }
 }

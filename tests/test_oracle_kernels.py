@@ -437,3 +437,113 @@ def test_fence_addrs_probe_and_scatter_wrap():
     assert changed.size and changed.min() >= base - pool.pool_base
     images = {hm.fence((tab + 4 * int(k)) & hm.U64, base, size, 4) for k in idx}
     assert {int(c) // 4 * 4 + pool.pool_base for c in changed} <= images
+
+
+# ---------------------------------------------------------------------------
+# address checking (Sections 4.3, 4.4) in the kernels whose threads share operands
+# ---------------------------------------------------------------------------
+
+def test_checking_mode_gemm_stops_exactly_the_threads_with_a_refused_operand():
+    """Thread (m, n) reads row m of A and column n of B and writes C[m,n]; it returns at its
+    first refused access.  Expected image and count are built from set inclusion in NumPy."""
+    sizes = [16 * KiB, 16 * KiB]
+    pool, table = make_pool(sizes, fill=0xA5, pool_base=1 << 20)
+    base, size = table[0]
+    end = base + size
+    M, N, K = 9, 14, 24
+    g = si.rng(0, 8)
+    for b_is_nk in (1, 0):
+        A = base - 2 * (3 * K - 5)                # rows 0..2 of A start in front of the partition
+        if b_is_nk:
+            B = end - 2 * (10 * K + 7)            # stored N x K: columns 10.. of B run past the end
+            Cc = base + 6 * KiB + 2               # inside
+        else:
+            B = base + 4 * KiB
+            Cc = end - 2 * (5 * N + 3)            # C runs past the end of the partition from row 5 on
+        pool.mem[:] = 0xA5
+        Ab = si.f32_to_bf16_bits(si.normal_f32(g, M * K))
+        Bb = si.f32_to_bf16_bits(si.normal_f32(g, K * N))
+        stored = Bb.reshape(K, N).T.copy().reshape(-1) if b_is_nk else Bb
+        # place what fits; the simulated pool covers both partitions, so out-of-partition operands exist in memory
+        lo = pool.pool_base
+        for ptr, bits in ((A, Ab), (B, stored)):
+            for i, h in enumerate(bits.tolist()):
+                a = ptr + 2 * i
+                if lo <= a < lo + sum(sizes) - 1:
+                    pool.view(a, np.uint16, 1)[0] = h
+        before = pool.mem.copy()
+        esc, vio, wrapped = pool.run("gemm_bf16", table[0], ok.MODE_CHECK, Cc, A, B, M, N, K, b_is_nk, 0, M, 0, N)
+        assert esc == 0 and wrapped == 0
+
+        def inside(a):
+            return base <= a and a + 2 <= end
+        a_ok = [all(inside(A + 2 * (m * K + k)) for k in range(K)) for m in range(M)]
+        b_ok = [all(inside(B + 2 * ((n * K + k) if b_is_nk else (k * N + n))) for k in range(K)) for n in range(N)]
+        Af = si.bf16_bits_to_f32(Ab).astype(np.float64).reshape(M, K)
+        Bf = si.bf16_bits_to_f32(Bb).astype(np.float64).reshape(K, N)
+        ref = Af @ Bf
+        want = before.copy()
+        stopped = 0
+        for m in range(M):
+            for n in range(N):
+                c_addr = Cc + 2 * (m * N + n)
+                if a_ok[m] and b_ok[n] and inside(c_addr):
+                    h = ok.lib().gdo_double_to_bf16(float(ref[m, n]))
+                    want[c_addr - lo:c_addr - lo + 2] = np.frombuffer(struct.pack("<H", h), np.uint8)
+                else:
+                    stopped += 1
+        assert 0 < stopped < M * N and not all(a_ok) and any(a_ok)
+        assert vio == stopped
+        diff = np.flatnonzero(pool.mem != want)
+        # fp64 accumulation order may differ from NumPy's in the last bit of a tie: allow no more than that
+        assert diff.size <= 2, diff
+        assert np.array_equal(pool.mem[size:], before[size:])          # the neighbour is untouched
+
+
+def test_checking_mode_rmsnorm_row_and_element_refusals():
+    """A row of x that is not wholly inside stops all of that row's threads (each counted);
+    a gain or an output element outside stops that one thread."""
+    sizes = [16 * KiB, 16 * KiB]
+    pool, table = make_pool(sizes, fill=0xA5, pool_base=1 << 20)
+    base, size = table[0]
+    end = base + size
+    rows, cols, eps = 6, 40, 1e-6
+    g = si.rng(0, 9)
+    x = base - 2 * (cols + 7)                      # row 0 and part of row 1 lie in front of the partition
+    gain = end - 2 * 33                            # gains 33.. are past the end
+    y = base + 4 * KiB - 2 * (rows * cols - 25)    # harmless: inside
+    y2 = end - 2 * (4 * cols + 11)                 # second run: the output leaves the partition in row 4
+    xb = si.f32_to_bf16_bits(si.normal_f32(g, rows * cols))
+    gb = si.f32_to_bf16_bits(si.uniform_f32(g, cols, 0.5, 1.5))
+    lo = pool.pool_base
+    for yy, gain in ((y, gain), (y2, base + 8 * KiB)):    # second run: gains inside, so the output cannot overwrite them
+        pool.mem[:] = 0xA5
+        for ptr, bits in ((x, xb), (gain, gb)):
+            for i, h in enumerate(bits.tolist()):
+                a = ptr + 2 * i
+                if lo <= a < lo + sum(sizes) - 1:
+                    pool.view(a, np.uint16, 1)[0] = h
+        before = pool.mem.copy()
+        esc, vio, wrapped = pool.run("rmsnorm_bf16", table[0], ok.MODE_CHECK, yy, x, gain, rows, cols, eps)
+        assert esc == 0 and wrapped == 0
+
+        def inside(a):
+            return base <= a and a + 2 <= end
+        xf = si.bf16_bits_to_f32(xb).astype(np.float64).reshape(rows, cols)
+        gf = si.bf16_bits_to_f32(gb).astype(np.float64)
+        want = before.copy()
+        stopped = 0
+        for r in range(rows):
+            row_ok = all(inside(x + 2 * (r * cols + j)) for j in range(cols))
+            inv = 1.0 / math.sqrt(float((xf[r] * xf[r]).sum()) / cols + eps)
+            for j in range(cols):
+                out_addr = yy + 2 * (r * cols + j)
+                if row_ok and inside(gain + 2 * j) and inside(out_addr):
+                    h = ok.lib().gdo_double_to_bf16(float(xf[r, j] * inv * gf[j]))
+                    want[out_addr - lo:out_addr - lo + 2] = np.frombuffer(struct.pack("<H", h), np.uint8)
+                else:
+                    stopped += 1
+        assert vio == stopped and 2 * cols < stopped < rows * cols
+        diff = np.flatnonzero(pool.mem != want)
+        assert diff.size <= 2, diff                                    # summation order: at most a last-bit tie
+        assert np.array_equal(pool.mem[size:], before[size:])
