@@ -15,8 +15,9 @@
  * never dereferences pool memory on the host, so every call except
  * gd_launch_fenced also works with made-up addresses and without a GPU.  All
  * functions return a gd_status; on error, out-parameters are left untouched.
- * Nothing aborts, nothing throws across the ABI.  A pool is protected by one
- * mutex: calls on the same pool from several threads are serialised.
+ * Nothing aborts, nothing throws across the ABI (host allocation failure is
+ * reported as GD_ENOMEM).  A pool is protected by one mutex: calls on the same
+ * pool from several threads are serialised.
  */
 #ifndef GUARDIAN_H
 #define GUARDIAN_H
@@ -52,7 +53,9 @@ typedef enum {
     GD_FENCE_BITWISE = 1,  /* AND with mask, OR with base (Listing 1); needs size-aligned pow2 partitions */
     GD_FENCE_MODULO = 2,   /* base + (addr - base) % size (Section 4.4); any size, any alignment */
     GD_FENCE_CHECK = 3     /* compare against base/end; an offending logical thread stops and is counted
-                              (Sections 4.3, 4.4).  Built for kernel ids 0..8; others: GD_ENOKERNEL */
+                              (Sections 4.3, 4.4).  A logical thread is the computation of one output
+                              element: in RMSNorm and GEMM it reads a whole operand row (and column), so
+                              an operand row that is not wholly inside stops every thread that needs it */
 } gd_fence_mode;
 
 /* ---- pool and partition bounds table (Section 4.2.1) ---------------------- */
@@ -91,7 +94,10 @@ int gd_pool_destroy(gd_pool *pool);
 /* Re-carving while other tenants keep running (Section 2.2, point (1): partitions
  * sized per application, no reset).  attach places a new partition by the same
  * rule and returns the lowest unused tenant number; detach releases a partition
- * (GD_EBUSY while the tenant has live allocations).  Other rows never move. */
+ * (GD_EBUSY while the tenant has live allocations).  Other rows never move.
+ * The library cannot see kernels in flight: the caller must drain the tenant's
+ * stream(s) before gd_tenant_detach, or a kernel still queued for the old
+ * tenant can write into a range that gd_tenant_attach has handed to a new one. */
 int gd_tenant_attach(gd_pool *pool, uint64_t bytes, int *tenant_out);
 int gd_tenant_detach(gd_pool *pool, int tenant);
 

@@ -40,29 +40,44 @@ static const KernelEntry g_registry[GD_K_COUNT] = {
 
 }  // namespace gd
 
+// Nothing may leave an extern "C" function by exception: the host containers
+// (std::vector, std::map) can throw std::bad_alloc, which is reported as GD_ENOMEM.
+#define GD_ABI_GUARD(expr)                                  \
+    try {                                                   \
+        return (expr);                                      \
+    } catch (const std::bad_alloc &) {                      \
+        return GD_ENOMEM;                                   \
+    } catch (...) {                                         \
+        return GD_EINVAL;                                   \
+    }
+
+static int create_pool(uint64_t dev_base, uint64_t dev_bytes, const uint64_t *part_bytes, int n_tenants,
+                       bool flex, gd_pool **out)
+{
+    if (!out) return GD_EINVAL;
+    gd::Pool *p = nullptr;
+    const int rc = gd::pool_create(dev_base, dev_bytes, part_bytes, n_tenants, flex, &p);
+    if (rc == GD_OK) *out = p;
+    return rc;
+}
+
 extern "C" {
 
 int gd_pool_create(uint64_t dev_base, uint64_t dev_bytes, const uint64_t *part_bytes, int n_tenants,
                    gd_pool **out)
 {
-    gd::Pool *p = nullptr;
-    int rc = gd::pool_create(dev_base, dev_bytes, part_bytes, n_tenants, false, &p);
-    if (rc == GD_OK) *out = p;
-    return rc;
+    GD_ABI_GUARD(create_pool(dev_base, dev_bytes, part_bytes, n_tenants, false, out))
 }
 
 int gd_pool_create_flex(uint64_t dev_base, uint64_t dev_bytes, const uint64_t *part_bytes, int n_tenants,
                         gd_pool **out)
 {
-    gd::Pool *p = nullptr;
-    int rc = gd::pool_create(dev_base, dev_bytes, part_bytes, n_tenants, true, &p);
-    if (rc == GD_OK) *out = p;
-    return rc;
+    GD_ABI_GUARD(create_pool(dev_base, dev_bytes, part_bytes, n_tenants, true, out))
 }
 
 int gd_pool_set_fault_counters(gd_pool *pool, uint64_t dev_counters, int slots)
 {
-    return gd::set_fault_counters(pool, dev_counters, slots);
+    GD_ABI_GUARD(gd::set_fault_counters(pool, dev_counters, slots))
 }
 
 int gd_pool_destroy(gd_pool *pool)
@@ -72,24 +87,24 @@ int gd_pool_destroy(gd_pool *pool)
     return GD_OK;
 }
 
-int gd_tenant_attach(gd_pool *pool, uint64_t bytes, int *tenant_out) { return gd::tenant_attach(pool, bytes, tenant_out); }
-int gd_tenant_detach(gd_pool *pool, int tenant) { return gd::tenant_detach(pool, tenant); }
+int gd_tenant_attach(gd_pool *pool, uint64_t bytes, int *tenant_out) { GD_ABI_GUARD(gd::tenant_attach(pool, bytes, tenant_out)) }
+int gd_tenant_detach(gd_pool *pool, int tenant) { GD_ABI_GUARD(gd::tenant_detach(pool, tenant)) }
 
 int gd_partition_info(const gd_pool *pool, int tenant, uint64_t *base, uint64_t *size, uint64_t *mask)
 {
-    return gd::partition_info(pool, tenant, base, size, mask);
+    GD_ABI_GUARD(gd::partition_info(pool, tenant, base, size, mask))
 }
 
 int gd_alloc(gd_pool *pool, int tenant, uint64_t bytes, uint64_t align, uint64_t *dptr_out)
 {
-    return gd::alloc(pool, tenant, bytes, align, dptr_out);
+    GD_ABI_GUARD(gd::alloc(pool, tenant, bytes, align, dptr_out))
 }
 
-int gd_free(gd_pool *pool, int tenant, uint64_t dptr) { return gd::free_(pool, tenant, dptr); }
+int gd_free(gd_pool *pool, int tenant, uint64_t dptr) { GD_ABI_GUARD(gd::free_(pool, tenant, dptr)) }
 
 int gd_check_copy(const gd_pool *pool, int tenant, uint64_t dptr, uint64_t bytes)
 {
-    return gd::check_copy(pool, tenant, dptr, bytes);
+    GD_ABI_GUARD(gd::check_copy(pool, tenant, dptr, bytes))
 }
 
 uint64_t gd_fence_host(uint64_t base, uint64_t size, uint64_t addr, uint32_t width, int mode)
@@ -103,58 +118,73 @@ const char *gd_kernel_name(int id) { return (id >= 0 && id < GD_K_COUNT) ? gd::g
 
 size_t gd_kernel_args_bytes(int id) { return (id >= 0 && id < GD_K_COUNT) ? gd::g_registry[id].args_bytes : 0; }
 
-int gd_launch_fenced(gd_pool *pool, int tenant, int kernel_id, const void *args, size_t args_bytes,
-                     const uint32_t grid[3], const uint32_t block[3], void *hip_stream, int mode)
+// Bounds table row of the launching tenant -> the extra kernel parameters and the
+// kernel variant for `mode` (the parameter augmentation of Section 4.2.3).
+static int fence_args_for(gd_pool *pool, int tenant, int mode, int *variant, gd::FenceArgs *extra)
+{
+    gd::LaunchRow row;
+    const int rc = gd::launch_row(pool, tenant, &row);                       // under the pool's lock
+    if (rc != GD_OK) return rc;
+    const uint64_t base = row.base, size = row.size, mask = row.size - 1;
+    *extra = gd::FenceArgs{base, mask, 0, 0, (uint32_t)tenant, 0};
+    switch (mode) {
+    case GD_FENCE_NONE:
+        *variant = gd::V_NONE;
+        return GD_OK;
+    case GD_FENCE_BITWISE:
+        if (row.flex) return GD_EINVAL;              // needs power-of-two, size-aligned partitions
+        // A mask that fits 32 bits lets the kernel fence a 32-bit offset and add
+        // the base in the addressing mode; larger partitions fence the high word.
+        *variant = (mask <= 0xffffffffull) ? gd::V_BIT32 : gd::V_BIT64;
+        return GD_OK;
+    case GD_FENCE_MODULO: {
+        // Reciprocal for the exact 64-bit remainder by `size` (division by an
+        // invariant integer, round-up method): shift = ceil(log2 size),
+        // magic = floor(2^64 * (2^shift - size) / size) + 1.
+        *variant = gd::V_MOD;
+        uint32_t l = 0;
+        while (l < 64 && ((uint64_t)1 << l) < size) ++l;
+        const unsigned __int128 pow_l = (unsigned __int128)1 << l;
+        extra->mask = size;
+        extra->shift = l;
+        extra->magic = (uint64_t)((((unsigned __int128)1 << 64) * (pow_l - size)) / size) + 1;
+        return GD_OK;
+    }
+    case GD_FENCE_CHECK:
+        if (!row.fault_counters || tenant >= row.fault_slots) return GD_EINVAL;
+        *variant = gd::V_CHECK;
+        extra->mask = size;
+        extra->faults = row.fault_counters;
+        return GD_OK;
+    default:
+        return GD_ENOKERNEL;
+    }
+}
+
+static int launch_fenced(gd_pool *pool, int tenant, int kernel_id, const void *args, size_t args_bytes,
+                         const uint32_t grid[3], const uint32_t block[3], void *hip_stream, int mode)
 {
     if (!pool || !args) return GD_EINVAL;
     if (kernel_id < 0 || kernel_id >= GD_K_COUNT) return GD_ENOKERNEL;
     const gd::KernelEntry &k = gd::g_registry[kernel_id];                    // lookup
     if (args_bytes != k.args_bytes) return GD_EINVAL;
 
-    uint64_t base = 0, size = 0, mask = 0;
-    int rc = gd::partition_info(pool, tenant, &base, &size, &mask);          // bounds table row
-    if (rc != GD_OK) return rc;
-
     int variant;
-    gd::FenceArgs extra = {base, mask, 0, 0, (uint32_t)tenant, 0};
-    switch (mode) {
-    case GD_FENCE_NONE:
-        variant = gd::V_NONE;
-        break;
-    case GD_FENCE_BITWISE:
-        if (pool->flex) return GD_EINVAL;            // needs power-of-two, size-aligned partitions
-        // A mask that fits 32 bits lets the kernel fence a 32-bit offset and add
-        // the base in the addressing mode; larger partitions fence the high word.
-        variant = (mask <= 0xffffffffull) ? gd::V_BIT32 : gd::V_BIT64;
-        break;
-    case GD_FENCE_MODULO: {
-        // Reciprocal for the exact 64-bit remainder by `size` (division by an
-        // invariant integer, round-up method): shift = ceil(log2 size),
-        // magic = floor(2^64 * (2^shift - size) / size) + 1.
-        variant = gd::V_MOD;
-        uint32_t l = 0;
-        while (l < 64 && ((uint64_t)1 << l) < size) ++l;
-        const unsigned __int128 pow_l = (unsigned __int128)1 << l;
-        extra.mask = size;
-        extra.shift = l;
-        extra.magic = (uint64_t)((((unsigned __int128)1 << 64) * (pow_l - size)) / size) + 1;
-        break;
-    }
-    case GD_FENCE_CHECK:
-        if (!pool->fault_counters || tenant >= pool->fault_slots) return GD_EINVAL;
-        variant = gd::V_CHECK;
-        extra.mask = size;
-        extra.faults = pool->fault_counters;
-        break;
-    default:
-        return GD_ENOKERNEL;
-    }
+    gd::FenceArgs extra;
+    const int rc = fence_args_for(pool, tenant, mode, &variant, &extra);
+    if (rc != GD_OK) return rc;
 
     alignas(16) unsigned char copy[64];                                      // parameter augmentation
     static_assert(sizeof(gd_args_gemm) <= sizeof(copy) && sizeof(gd_args_scatter) <= sizeof(copy), "args copy too small");
     std::memcpy(copy, args, args_bytes);
     const gd::Shape shape = {grid, block};
     return k.launch(copy, extra, variant, shape, static_cast<hipStream_t>(hip_stream));
+}
+
+int gd_launch_fenced(gd_pool *pool, int tenant, int kernel_id, const void *args, size_t args_bytes,
+                     const uint32_t grid[3], const uint32_t block[3], void *hip_stream, int mode)
+{
+    GD_ABI_GUARD(launch_fenced(pool, tenant, kernel_id, args, args_bytes, grid, block, hip_stream, mode))
 }
 
 const char *gd_strerror(int status)

@@ -93,12 +93,21 @@ struct Fence {
         else return true;
     }
 
-    // One violation: count it for the tenant.  The counter is manager-owned memory.
-    __device__ __forceinline__ void fault() const
+    // `count` violations (one per stopped logical thread): add them to the tenant's
+    // counter.  The counter is manager-owned memory.
+    __device__ __forceinline__ void fault(uint64_t count = 1) const
     {
         if constexpr (V == V_CHECK)
-            __hip_atomic_fetch_add((GD_GLOBAL unsigned long long *)(faults + 8 * (uint64_t)tenant), 1ULL,
-                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_fetch_add((GD_GLOBAL unsigned long long *)(faults + 8 * (uint64_t)tenant),
+                                   (unsigned long long)count, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+
+    // Address checking of a run of `bytes` consecutive bytes (an operand row): every
+    // 2-, 4-, ... byte element of it is inside the partition iff the run is.
+    __device__ __forceinline__ bool inside_run(uint64_t raw, uint64_t bytes) const
+    {
+        if constexpr (V == V_CHECK) return bytes <= mask && raw - base <= mask - bytes;
+        else return true;
     }
 
     // The fenced address of a W-byte access to `raw` (what the probe kernel reports).
@@ -123,6 +132,86 @@ struct Fence {
             const uint32_t hi = ((uint32_t)(raw >> 32) & (uint32_t)(mask >> 32)) | (uint32_t)(base >> 32);
             return ((uint64_t)hi << 32) | lo;
         }
+    }
+
+    // ---- scalar tile fence ------------------------------------------------------------
+    // A wavefront that accesses start + L, with `start` wave-uniform and the lane
+    // offsets L all below TILE, can take the fence once, on the scalar unit: if the
+    // fenced image of `start` has TILE bytes of the partition behind it, then adding L
+    // carries into no masked bit and fence(start + L) == fence(start) + L for every
+    // such L, exactly.  tile() tests that condition and gives the fenced start; when it
+    // does not hold (a tenant pointer that wraps at the partition end inside this tile)
+    // the caller takes its per-lane path.  `start` must be aligned to the width of the
+    // accesses made through the tile, so that the width rule clears nothing.
+    // The bitwise rules run Listing 1's two 64-bit instructions as they stand, on
+    // SGPR pairs; the accesses then use the "SGPR base + 32-bit VGPR offset"
+    // addressing mode with the lane offset as the offset (ld_tile / st_tile).
+    template <int TILE>
+    __device__ __forceinline__ uint64_t tile(uint64_t start, uint64_t &fenced) const
+    {
+        // Returns 0 if the tile is whole (see above), anything else if the fence splits it;
+        // a caller with several tiles ORs the results and tests once.
+        if constexpr (V == V_NONE) {
+            fenced = start;
+            return 0;
+        } else if constexpr (V == V_CHECK) {
+            fenced = start;
+            return !inside<TILE>(start);
+        } else if constexpr (V == V_MOD) {
+            fenced = address<1>(start);
+            return !(fenced - base <= mask - TILE);              // mask holds the size
+        } else {
+            asm("s_and_b64 %0, %1, %2\n\ts_or_b64 %0, %0, %3" : "=&s"(fenced) : "s"(start), "s"(mask), "s"(base) : "scc");
+            // offset + TILE - 1 <= mask, as "no bit above the mask" (scalar unit: no 64-bit ordered compare)
+            return ((start & mask) + (TILE - 1)) & ~mask;
+        }
+    }
+
+    // The lane's byte offset inside a tile of TILE bytes, confined below TILE by an AND
+    // with a constant (one instruction per kernel, not per access).
+    template <int TILE>
+    static __device__ __forceinline__ uint32_t tile_lane_offset(uint32_t off)
+    {
+        static_assert((TILE & (TILE - 1)) == 0, "tile size must be a power of two");
+        uint32_t r;
+        asm("v_and_b32 %0, %1, %2" : "=v"(r) : "n"(TILE - 1), "v"(off));
+        return r;
+    }
+
+    // 16-byte accesses through a tile: the instruction is written out, so that its
+    // form -- fenced SGPR pair as the base, the confined lane offset as the 32-bit
+    // offset -- does not depend on what the optimiser makes of the address
+    // arithmetic.  The compiler does not count these loads: tile_wait() must stand
+    // between a ld_tile16 and the first use of its result.
+    template <typename T, bool STREAM = false>
+    __device__ __forceinline__ T ld_tile16(uint64_t fenced, uint32_t lane_off) const
+    {
+        static_assert(sizeof(T) == 16, "one 16-byte vector per lane");
+        T v;
+        if constexpr (STREAM) asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "=v"(v) : "v"(lane_off), "s"(fenced) : "memory");
+        else asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(v) : "v"(lane_off), "s"(fenced) : "memory");
+        return v;
+    }
+
+    template <typename T, bool STREAM = false>
+    __device__ __forceinline__ void st_tile16(uint64_t fenced, uint32_t lane_off, T v) const
+    {
+        static_assert(sizeof(T) == 16, "one 16-byte vector per lane");
+        if constexpr (STREAM) asm volatile("global_store_dwordx4 %0, %1, %2 nt" : : "v"(lane_off), "v"(v), "s"(fenced) : "memory");
+        else asm volatile("global_store_dwordx4 %0, %1, %2" : : "v"(lane_off), "v"(v), "s"(fenced) : "memory");
+    }
+
+    // All ld_tile16 issued so far have landed; the values pass through so that no use
+    // of them can be scheduled in front of the wait.
+    template <typename T>
+    static __device__ __forceinline__ void tile_wait(T &a)
+    {
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(a) : : "memory");
+    }
+    template <typename T>
+    static __device__ __forceinline__ void tile_wait(T &a, T &b)
+    {
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(a), "+v"(b) : : "memory");
     }
 
     // STREAM = true marks data that is touched once (contiguous streams): the access
@@ -175,9 +264,10 @@ struct Fence {
     // bookkeeping: the caller owns the s_waitcnt vmcnt and the workgroup barrier
     // between the copy and the first read of its data.  `lds_addr` is the
     // wave-uniform LDS byte address lane 0 lands at; M0 carries it (one wait state
-    // between the write of M0 and the copy).  M0 is a reserved register the compiler
-    // does not track through inline asm: use this only in kernels where nothing else
-    // depends on M0 (no compiler-issued LDS copies, no indexed register moves).
+    // between the write of M0 and the copy).  M0 is a register the compiler reserves
+    // and does not track through inline asm (it rejects a clobber declaration for it):
+    // use this only in kernels where nothing else depends on M0 (no compiler-issued
+    // LDS copies, no indexed register moves).
     //
     // OFF (64) selects the second half of the 128-byte line the handle points into.
     // It is applied to the fenced address -- through the scalar base for the 32-bit
@@ -229,30 +319,5 @@ struct Fence {
         else *ptr = v;
     }
 };
-
-// Launch helper for kernels built for all five variants.
-#define GD_LAUNCH_VARIANT5(variant, KERNEL, grid, block, stream, ...)                           \
-    do {                                                                                        \
-        switch (variant) {                                                                      \
-        case gd::V_NONE:  hipLaunchKernelGGL((KERNEL<gd::V_NONE>), grid, block, 0, stream, __VA_ARGS__); break;  \
-        case gd::V_BIT32: hipLaunchKernelGGL((KERNEL<gd::V_BIT32>), grid, block, 0, stream, __VA_ARGS__); break; \
-        case gd::V_BIT64: hipLaunchKernelGGL((KERNEL<gd::V_BIT64>), grid, block, 0, stream, __VA_ARGS__); break; \
-        case gd::V_MOD:   hipLaunchKernelGGL((KERNEL<gd::V_MOD>), grid, block, 0, stream, __VA_ARGS__); break;   \
-        case gd::V_CHECK: hipLaunchKernelGGL((KERNEL<gd::V_CHECK>), grid, block, 0, stream, __VA_ARGS__); break; \
-        default: return GD_ENOKERNEL;                                                           \
-        }                                                                                       \
-    } while (0)
-
-// Launch helper: instantiate KERNEL for the variant chosen on the host (no checking build).
-#define GD_LAUNCH_VARIANT(variant, KERNEL, grid, block, stream, ...)                            \
-    do {                                                                                        \
-        switch (variant) {                                                                      \
-        case gd::V_NONE:  hipLaunchKernelGGL((KERNEL<gd::V_NONE>), grid, block, 0, stream, __VA_ARGS__); break;  \
-        case gd::V_BIT32: hipLaunchKernelGGL((KERNEL<gd::V_BIT32>), grid, block, 0, stream, __VA_ARGS__); break; \
-        case gd::V_BIT64: hipLaunchKernelGGL((KERNEL<gd::V_BIT64>), grid, block, 0, stream, __VA_ARGS__); break; \
-        case gd::V_MOD:   hipLaunchKernelGGL((KERNEL<gd::V_MOD>), grid, block, 0, stream, __VA_ARGS__); break;   \
-        default: return GD_ENOKERNEL;                                                           \
-        }                                                                                       \
-    } while (0)
 
 }  // namespace gd

@@ -42,7 +42,8 @@ __device__ __forceinline__ uint32_t gemm_f32_to_bf16(float f)
 }
 
 // ---- generic kernel: any shape, any alignment, either layout of B -------------------
-// One thread per entry of C, 2-byte accesses, fp32 accumulation in k order.
+// One thread per entry of C, 2-byte accesses, fp32 accumulation in k order.  Under
+// address checking the thread returns at its first refused access (counted once).
 template <int V>
 __global__ __launch_bounds__(256) void k_gemm_generic(gd_args_gemm p, FenceArgs fa)
 {
@@ -52,11 +53,16 @@ __global__ __launch_bounds__(256) void k_gemm_generic(gd_args_gemm p, FenceArgs 
     for (uint64_t e = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += stride) {
         const uint64_t m = e / p.N, n = e % p.N;
         float acc = 0.0f;
+        bool stopped = false;
         for (uint64_t k = 0; k < p.K; ++k) {
-            const uint32_t ha = F.template ld<uint16_t>(p.A + 2 * (m * p.K + k));
-            const uint32_t hb = F.template ld<uint16_t>(p.B + 2 * (p.b_is_nk ? n * p.K + k : k * p.N + n));
+            const uint64_t aa = p.A + 2 * (m * p.K + k);
+            const uint64_t ab = p.B + 2 * (p.b_is_nk ? n * p.K + k : k * p.N + n);
+            if (!F.template inside<2>(aa) || !F.template inside<2>(ab)) { stopped = true; break; }
+            const uint32_t ha = F.template ld<uint16_t>(aa);
+            const uint32_t hb = F.template ld<uint16_t>(ab);
             acc += __uint_as_float(ha << 16) * __uint_as_float(hb << 16);
         }
+        if (stopped || !F.template inside<2>(p.C + 2 * e)) { F.fault(); continue; }
         F.template st<uint16_t>(p.C + 2 * e, (uint16_t)gemm_f32_to_bf16(acc));
     }
 }
@@ -101,6 +107,17 @@ void k_gemm_nk256(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles
     const uint64_t row_step = 2 * 32 * (uint64_t)p.K;
     const uint32_t lds_w = lrow * 128 + ((lg ^ ((lrow >> 1) & 7)) << 4);
 
+    // Address checking: thread (m, n) of C stops unless row m of A and column n of B
+    // (a row of the N x K storage) are wholly inside the partition.  Rows that are not
+    // are never read (they stay zero in LDS); their threads are counted at the store.
+    const uint64_t run_bytes = 2 * (uint64_t)p.K;
+    uint32_t a_live = 0, b_live = 0;             // bit i: this thread's i-th row of A / of B may be read
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+        a_live |= (uint32_t)F.inside_run(p.A + (uint64_t)(m0 + lrow + 32 * i) * run_bytes, run_bytes) << i;
+        b_live |= (uint32_t)F.inside_run(p.B + (uint64_t)(n0 + lrow + 32 * i) * run_bytes, run_bytes) << i;
+    }
+
     u32x4 ra[LOADS], rb[LOADS];
     auto gload = [&](uint32_t k0) {
 #pragma unroll
@@ -109,8 +126,8 @@ void k_gemm_nk256(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles
                 ra[i] = (u32x4){0, 0, 0, 0};
                 rb[i] = (u32x4){0, 0, 0, 0};
                 const bool kin = k0 + lg * 8 < p.K;
-                if (kin && m0 + lrow + 32 * i < p.M) ra[i] = F.template ld<u32x4>(a_ptr + i * row_step + 2 * (uint64_t)k0);
-                if (kin && n0 + lrow + 32 * i < p.N) rb[i] = F.template ld<u32x4>(b_ptr + i * row_step + 2 * (uint64_t)k0);
+                if (kin && m0 + lrow + 32 * i < p.M && ((a_live >> i) & 1)) ra[i] = F.template ld<u32x4>(a_ptr + i * row_step + 2 * (uint64_t)k0);
+                if (kin && n0 + lrow + 32 * i < p.N && ((b_live >> i) & 1)) rb[i] = F.template ld<u32x4>(b_ptr + i * row_step + 2 * (uint64_t)k0);
             } else {
                 ra[i] = F.template ld<u32x4>(a_ptr + i * row_step + 2 * (uint64_t)k0);
                 rb[i] = F.template ld<u32x4>(b_ptr + i * row_step + 2 * (uint64_t)k0);
@@ -188,6 +205,14 @@ void k_gemm_nk256(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles
     __syncthreads();
     const uint32_t orow = lane >> 4, og = lane & 15;
     const bool vec_ok = !EDGE || (((p.C & 15) == 0) && ((p.N & 7) == 0));
+    // Address checking: which of this lane's eight columns of B are wholly inside.
+    uint32_t col_live = 0xff;
+    if (F.CHECKED) {
+        col_live = 0;
+        for (int e = 0; e < 8; ++e)
+            col_live |= (uint32_t)F.inside_run(p.B + (uint64_t)(n0 + wn * 128 + og * 8 + e) * run_bytes, run_bytes) << e;
+    }
+    uint32_t stopped = 0;
 #pragma unroll 4
     for (int it = 0; it < 32; ++it) {
         const uint32_t row = orow + 4 * it;
@@ -197,24 +222,26 @@ void k_gemm_nk256(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles
         if (!EDGE) {
             F.template st<u32x4>(dst, v);
         } else if (m < p.M && n < p.N) {
-            if (vec_ok && n + 8 <= p.N) {
+            const bool row_live = F.inside_run(p.A + (uint64_t)m * run_bytes, run_bytes);
+            if (vec_ok && n + 8 <= p.N && row_live && col_live == 0xff && F.template inside<16>(dst)) {
                 F.template st<u32x4>(dst, v);
             } else {
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
-                    if (n + e < p.N)
-                        F.template st<uint16_t>(dst + 2 * e, (uint16_t)(v[e >> 1] >> ((e & 1) * 16)));
+                    if (n + e < p.N) {
+                        if (row_live && ((col_live >> e) & 1) && F.template inside<2>(dst + 2 * e))
+                            F.template st<uint16_t>(dst + 2 * e, (uint16_t)(v[e >> 1] >> ((e & 1) * 16)));
+                        else
+                            ++stopped;
+                    }
             }
         }
     }
+    if (F.CHECKED && stopped) F.fault(stopped);
 }
 
 
-// ---- tiled MFMA kernel, global -> LDS direct ---------------------------------------------
-// Requirements (checked by the launcher): B stored N x K; M % 256 == 0, N % 256 == 0,
-// K % 64 == 0; A, B, C 16-byte aligned.
 #define GD_LDS __attribute__((address_space(3)))
-
 
 // ---- tiled MFMA kernel, five-stage ring of K=32 slices -----------------------------------------
 // 256 x 256 tile, 2 x 2 wavefronts of 128 x 128 each.  K advances in
@@ -705,33 +732,34 @@ int launch_gemm_bf16(const void *args, const FenceArgs &f, int variant, const Sh
     if (shape.grid || shape.block) return GD_EINVAL;
     if (p.M == 0 || p.N == 0) return GD_OK;
     const bool tiled = p.b_is_nk && p.K > 0 && (p.K % 8) == 0 && ((p.A | p.B) & 15) == 0;
+    int rc;
     if (tiled) {
         const uint32_t tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
         const uint64_t tiles = (uint64_t)tiles_m * tiles_n;
         if (tiles > 0x7fffffffull) return GD_ESHAPE;
         // the ring kernels keep per-lane byte offsets of up to 256 rows in 32 bits
         const bool edge = (p.M % BM) || (p.N % BN) || (p.K % BK) || (p.C & 15) || p.K > (1u << 22);
+        const bool ring = p.K % 128 == 0 && ((p.A | p.B) & 127) == 0;
         const dim3 grid((uint32_t)tiles), block(256);
-#define GD_GEMM_CASE(VAR)                                                                                         \
-    case VAR:                                                                                                     \
-        if (edge) hipLaunchKernelGGL((k_gemm_nk256<VAR, true>), grid, block, 0, stream, p, f, tiles_m, tiles_n);  \
-        else if (p.K % 128 == 0 && ((p.A | p.B) & 127) == 0) hipLaunchKernelGGL((k_gemm_ring<VAR>), grid, block, 0, stream, p, f, tiles_m, tiles_n); \
-        else hipLaunchKernelGGL((k_gemm_units<VAR>), grid, block, 0, stream, p, f, tiles_m, tiles_n);             \
-        break;
-        switch (variant) {
-            GD_GEMM_CASE(V_NONE)
-            GD_GEMM_CASE(V_BIT32)
-            GD_GEMM_CASE(V_BIT64)
-            GD_GEMM_CASE(V_MOD)
-        default: return GD_ENOKERNEL;
-        }
-#undef GD_GEMM_CASE
+        rc = with_variant(variant, [&](auto v) {
+            constexpr int V = decltype(v)::value;
+            // address checking needs predicated loads: the register-staged kernel has them
+            if (V == V_CHECK || edge) {
+                hipLaunchKernelGGL((k_gemm_nk256<V, true>), grid, block, 0, stream, p, f, tiles_m, tiles_n);
+            } else if constexpr (V != V_CHECK) {
+                if (ring) hipLaunchKernelGGL((k_gemm_ring<V>), grid, block, 0, stream, p, f, tiles_m, tiles_n);
+                else hipLaunchKernelGGL((k_gemm_units<V>), grid, block, 0, stream, p, f, tiles_m, tiles_n);
+            }
+        });
     } else {
         const uint64_t total = (uint64_t)p.M * p.N;
         uint64_t blocks = (total + 255) / 256;
         if (blocks > 65536) blocks = 65536;
-        GD_LAUNCH_VARIANT(variant, k_gemm_generic, dim3((uint32_t)blocks), dim3(256), stream, p, f);
+        rc = with_variant(variant, [&](auto v) {
+            hipLaunchKernelGGL((k_gemm_generic<decltype(v)::value>), dim3((uint32_t)blocks), dim3(256), 0, stream, p, f);
+        });
     }
+    if (rc != GD_OK) return rc;
     GD_CHECK_LAUNCH();
     return GD_OK;
 }

@@ -134,34 +134,51 @@ static uint64_t blocks_for(uint64_t n, uint32_t block)
     return (n + per_block - 1) / per_block;
 }
 
-#define GD_INDEXED_LAUNCHER(NAME, ARGS_T, KERNEL_EXPR)                                                   \
-    int NAME(const void *args, const FenceArgs &f, int variant, const Shape &shape, hipStream_t stream)  \
-    {                                                                                                    \
-        const ARGS_T &p = *(const ARGS_T *)args;                                                         \
-        const uint32_t b0 = shape.block ? shape.block[0] : 256;                                          \
-        uint32_t grid, block;                                                                            \
-        if (!pick_1d(shape, b0 ? blocks_for(p.n, b0) : 1, 256, &grid, &block)) return GD_EINVAL;         \
-        if (p.n == 0) return GD_OK;                                                                      \
-        switch (variant) {                                                                               \
-        case V_NONE:  hipLaunchKernelGGL((KERNEL_EXPR(V_NONE)), dim3(grid), dim3(block), 0, stream, p, f); break;  \
-        case V_BIT32: hipLaunchKernelGGL((KERNEL_EXPR(V_BIT32)), dim3(grid), dim3(block), 0, stream, p, f); break; \
-        case V_BIT64: hipLaunchKernelGGL((KERNEL_EXPR(V_BIT64)), dim3(grid), dim3(block), 0, stream, p, f); break; \
-        case V_MOD:   hipLaunchKernelGGL((KERNEL_EXPR(V_MOD)), dim3(grid), dim3(block), 0, stream, p, f); break;   \
-        case V_CHECK: hipLaunchKernelGGL((KERNEL_EXPR(V_CHECK)), dim3(grid), dim3(block), 0, stream, p, f); break; \
-        default: return GD_ENOKERNEL;                                                                    \
-        }                                                                                                \
-        GD_CHECK_LAUNCH();                                                                               \
-        return GD_OK;                                                                                    \
-    }
+// One launcher body for the four kernels: `launch(v, grid, block)` issues the
+// instance for fence variant decltype(v)::value.
+template <typename ARGS, typename L>
+static int launch_indexed(const ARGS &p, int variant, const Shape &shape, L &&launch)
+{
+    const uint32_t b0 = shape.block ? shape.block[0] : 256;
+    uint32_t grid, block;
+    if (!pick_1d(shape, b0 ? blocks_for(p.n, b0) : 1, 256, &grid, &block)) return GD_EINVAL;
+    if (p.n == 0) return GD_OK;
+    const int rc = with_variant(variant, [&](auto v) { launch(v, dim3(grid), dim3(block)); });
+    if (rc != GD_OK) return rc;
+    GD_CHECK_LAUNCH();
+    return GD_OK;
+}
 
-#define K_SAXPY(V) k_saxpy_idx<V>
-#define K_GATHER64(V) k_gather32<V, 1>
-#define K_GATHER32(V) k_gather32<V, 0>
-#define K_SCATTER(V) k_scatter_f32_i64<V>
+int launch_saxpy_idx(const void *args, const FenceArgs &f, int variant, const Shape &shape, hipStream_t stream)
+{
+    const gd_args_saxpy_idx &p = *(const gd_args_saxpy_idx *)args;
+    return launch_indexed(p, variant, shape, [&](auto v, dim3 g, dim3 b) {
+        hipLaunchKernelGGL((k_saxpy_idx<decltype(v)::value>), g, b, 0, stream, p, f);
+    });
+}
 
-GD_INDEXED_LAUNCHER(launch_saxpy_idx, gd_args_saxpy_idx, K_SAXPY)
-GD_INDEXED_LAUNCHER(launch_gather32_i64, gd_args_gather, K_GATHER64)
-GD_INDEXED_LAUNCHER(launch_gather32_i32, gd_args_gather, K_GATHER32)
-GD_INDEXED_LAUNCHER(launch_scatter_f32_i64, gd_args_scatter, K_SCATTER)
+int launch_gather32_i64(const void *args, const FenceArgs &f, int variant, const Shape &shape, hipStream_t stream)
+{
+    const gd_args_gather &p = *(const gd_args_gather *)args;
+    return launch_indexed(p, variant, shape, [&](auto v, dim3 g, dim3 b) {
+        hipLaunchKernelGGL((k_gather32<decltype(v)::value, 1>), g, b, 0, stream, p, f);
+    });
+}
+
+int launch_gather32_i32(const void *args, const FenceArgs &f, int variant, const Shape &shape, hipStream_t stream)
+{
+    const gd_args_gather &p = *(const gd_args_gather *)args;
+    return launch_indexed(p, variant, shape, [&](auto v, dim3 g, dim3 b) {
+        hipLaunchKernelGGL((k_gather32<decltype(v)::value, 0>), g, b, 0, stream, p, f);
+    });
+}
+
+int launch_scatter_f32_i64(const void *args, const FenceArgs &f, int variant, const Shape &shape, hipStream_t stream)
+{
+    const gd_args_scatter &p = *(const gd_args_scatter *)args;
+    return launch_indexed(p, variant, shape, [&](auto v, dim3 g, dim3 b) {
+        hipLaunchKernelGGL((k_scatter_f32_i64<decltype(v)::value>), g, b, 0, stream, p, f);
+    });
+}
 
 }  // namespace gd

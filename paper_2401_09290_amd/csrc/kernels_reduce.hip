@@ -45,6 +45,7 @@ __device__ __forceinline__ T block_sum(T v, T *lds)
 
 // ---- sum, pass 1: partials[block] = sum of this block's tiles ---------------------
 constexpr int SUM_UNROLL = 4;
+constexpr int SUM_TILE = 1024;         // bytes one wavefront covers with one 16-byte vector per lane
 
 template <int V>
 __global__ __launch_bounds__(WG) void k_sum_partial(gd_args_sum p, FenceArgs fa)
@@ -56,9 +57,29 @@ __global__ __launch_bounds__(WG) void k_sum_partial(gd_args_sum p, FenceArgs fa)
         const uint64_t n4 = p.n >> 2;
         const uint64_t tile = (uint64_t)WG * SUM_UNROLL;
         f32x4 a4 = {0.0f, 0.0f, 0.0f, 0.0f};
+        const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        const uint32_t lane_off = Fence<V>::template tile_lane_offset<SUM_TILE>(16 * (threadIdx.x & 63));
         for (uint64_t t0 = blockIdx.x * tile; t0 < n4; t0 += gridDim.x * tile) {
             const uint64_t i0 = t0 + threadIdx.x;
-            if (!F.CHECKED && t0 + tile <= n4) {
+            // Full tiles: each of a wavefront's SUM_UNROLL accesses covers one contiguous 1 KiB,
+            // fenced (or checked) once on the scalar unit.
+            uint64_t tf[SUM_UNROLL];
+            uint64_t split = t0 + tile <= n4 ? 0 : 1;
+            if (split == 0) {
+#pragma unroll
+                for (int u = 0; u < SUM_UNROLL; ++u)
+                    split |= F.template tile<SUM_TILE>(p.in + 16 * (t0 + (uint64_t)u * WG + 64 * wave), tf[u]);
+            }
+            if (split == 0) {
+                f32x4 v[SUM_UNROLL];
+#pragma unroll
+                for (int u = 0; u < SUM_UNROLL; ++u) v[u] = F.template ld_tile16<f32x4, true>(tf[u], lane_off);
+                static_assert(SUM_UNROLL == 4, "the wait below names four vectors");
+                F.tile_wait(v[0], v[1]);
+                F.tile_wait(v[2], v[3]);
+#pragma unroll
+                for (int u = 0; u < SUM_UNROLL; ++u) a4 += v[u];
+            } else if (!F.CHECKED && t0 + tile <= n4) {
                 f32x4 v[SUM_UNROLL];
 #pragma unroll
                 for (int u = 0; u < SUM_UNROLL; ++u) v[u] = F.template ld<f32x4, true>(p.in + 16 * (i0 + (uint64_t)u * WG));
@@ -143,6 +164,10 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 constexpr int RMS_WG = 512;
 constexpr int RMS_MAX_CHUNKS = 2;   // 16-byte chunks (8 values) per thread held in registers
 
+// Address checking (Sections 4.3, 4.4): the logical thread of y[r,j] reads all of row r,
+// then g[j], then stores, and returns at its first refused access.  A row of x that is
+// not wholly inside the partition therefore stops -- and counts -- all `cols` threads of
+// the row; a refused g[j] or y[r,j] stops that one thread.
 template <int V>
 __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, FenceArgs fa)
 {
@@ -152,6 +177,19 @@ __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, Fenc
     const uint64_t xrow = p.x + 2 * row * p.cols;
     const uint64_t yrow = p.y + 2 * row * p.cols;
     const float inv_cols = 1.0f / (float)p.cols;
+
+    if (F.CHECKED && !F.inside_run(xrow, 2 * (uint64_t)p.cols)) {       // workgroup-uniform
+        if (threadIdx.x == 0) F.fault(p.cols);
+        return;
+    }
+    // one output element under address checking: false = its thread stops (counted by the caller)
+    auto put = [&](uint32_t j, float x, float inv) -> bool {
+        if (!F.template inside<2>(p.g + 2 * (uint64_t)j)) return false;
+        const float g = bf16_lo(F.template ld<uint16_t>(p.g + 2 * (uint64_t)j));
+        if (!F.template inside<2>(yrow + 2 * (uint64_t)j)) return false;
+        F.template st<uint16_t>(yrow + 2 * (uint64_t)j, (uint16_t)f32_to_bf16(x * inv * g));
+        return true;
+    };
 
     const bool vec = ((p.x | p.y | p.g) & 15) == 0 && (p.cols & 7) == 0 &&
                      p.cols <= (uint32_t)(RMS_WG * 8 * RMS_MAX_CHUNKS);
@@ -174,25 +212,35 @@ __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, Fenc
         }
         // the gains do not depend on the row's sum: fetch them before the reduction's barriers
         u32x4 gv[RMS_MAX_CHUNKS];
+        bool whole[RMS_MAX_CHUNKS];          // address checking: gain and output chunk both wholly inside
 #pragma unroll
         for (int c = 0; c < RMS_MAX_CHUNKS; ++c) {
             const uint32_t q = threadIdx.x + c * RMS_WG;
-            if (q < chunks) gv[c] = F.template ld<u32x4>(p.g + 16 * (uint64_t)q);
+            whole[c] = F.template inside<16>(p.g + 16 * (uint64_t)q) && F.template inside<16>(yrow + 16 * (uint64_t)q);
+            if (q < chunks && whole[c]) gv[c] = F.template ld<u32x4>(p.g + 16 * (uint64_t)q);
         }
         ss = block_sum<RMS_WG / 64>(ss, lds);
         const float inv = 1.0f / sqrtf(ss * inv_cols + p.eps);
+        uint32_t stopped = 0;
 #pragma unroll
         for (int c = 0; c < RMS_MAX_CHUNKS; ++c) {
             const uint32_t q = threadIdx.x + c * RMS_WG;
-            if (q < chunks) {
+            if (q >= chunks) continue;
+            if (whole[c]) {
                 u32x4 o;
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
                     o[e] = pack_bf16(bf16_lo(xv[c][e]) * inv * bf16_lo(gv[c][e]),
                                      bf16_hi(xv[c][e]) * inv * bf16_hi(gv[c][e]));
                 F.template st<u32x4>(yrow + 16 * (uint64_t)q, o);
+            } else {
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t w = xv[c][e >> 1];
+                    stopped += !put(8 * q + e, (e & 1) ? bf16_hi(w) : bf16_lo(w), inv);
+                }
             }
         }
+        if (F.CHECKED && stopped) F.fault(stopped);
     } else {
         float ss = 0.0f;
         for (uint32_t j = threadIdx.x; j < p.cols; j += RMS_WG) {
@@ -201,11 +249,10 @@ __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, Fenc
         }
         ss = block_sum<RMS_WG / 64>(ss, lds);
         const float inv = 1.0f / sqrtf(ss * inv_cols + p.eps);
-        for (uint32_t j = threadIdx.x; j < p.cols; j += RMS_WG) {
-            const float a = bf16_lo(F.template ld<uint16_t>(xrow + 2 * (uint64_t)j));
-            const float g = bf16_lo(F.template ld<uint16_t>(p.g + 2 * (uint64_t)j));
-            F.template st<uint16_t>(yrow + 2 * (uint64_t)j, (uint16_t)f32_to_bf16(a * inv * g));
-        }
+        uint32_t stopped = 0;
+        for (uint32_t j = threadIdx.x; j < p.cols; j += RMS_WG)
+            stopped += !put(j, bf16_lo(F.template ld<uint16_t>(xrow + 2 * (uint64_t)j)), inv);
+        if (F.CHECKED && stopped) F.fault(stopped);
     }
 }
 
@@ -214,17 +261,28 @@ __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, Fenc
 constexpr uint32_t SUM_MAX_BLOCKS = 2048;
 static_assert(SUM_MAX_BLOCKS * 4 <= GD_SUM_WORKSPACE, "workspace too small for the partial sums");
 
+static uint32_t sum_blocks(uint64_t n)
+{
+    const uint64_t tile = (uint64_t)WG * SUM_UNROLL * 4;                 // elements per tile
+    uint64_t blocks = (n + tile - 1) / tile;
+    if (blocks == 0) blocks = 1;
+    return (uint32_t)(blocks > SUM_MAX_BLOCKS ? SUM_MAX_BLOCKS : blocks);
+}
+
 int launch_sum_f32(const void *args, const FenceArgs &f, int variant, const Shape &shape, hipStream_t stream)
 {
     const gd_args_sum &p = *(const gd_args_sum *)args;
     if (shape.grid || shape.block) return GD_EINVAL;
-    const uint64_t tile = (uint64_t)WG * SUM_UNROLL * 4;                 // elements per tile
-    uint64_t blocks = (p.n + tile - 1) / tile;
-    if (blocks == 0) blocks = 1;
-    if (blocks > SUM_MAX_BLOCKS) blocks = SUM_MAX_BLOCKS;
-    GD_LAUNCH_VARIANT5(variant, k_sum_partial, dim3((uint32_t)blocks), dim3(WG), stream, p, f);
+    const uint32_t blocks = sum_blocks(p.n);
+    int rc = with_variant(variant, [&](auto v) {
+        hipLaunchKernelGGL((k_sum_partial<decltype(v)::value>), dim3(blocks), dim3(WG), 0, stream, p, f);
+    });
+    if (rc != GD_OK) return rc;
     GD_CHECK_LAUNCH();
-    GD_LAUNCH_VARIANT5(variant, k_sum_final, dim3(1), dim3(WG), stream, p, (uint32_t)blocks, f);
+    rc = with_variant(variant, [&](auto v) {
+        hipLaunchKernelGGL((k_sum_final<decltype(v)::value>), dim3(1), dim3(WG), 0, stream, p, blocks, f);
+    });
+    if (rc != GD_OK) return rc;
     GD_CHECK_LAUNCH();
     return GD_OK;
 }
@@ -236,7 +294,10 @@ int launch_rmsnorm_bf16(const void *args, const FenceArgs &f, int variant, const
     if (shape.grid || shape.block) return GD_EINVAL;
     if (p.cols == 0 || p.rows > 0x7fffffffu) return GD_ESHAPE;
     if (p.rows == 0) return GD_OK;
-    GD_LAUNCH_VARIANT(variant, k_rmsnorm_bf16, dim3(p.rows), dim3(RMS_WG), stream, p, f);
+    const int rc = with_variant(variant, [&](auto v) {
+        hipLaunchKernelGGL((k_rmsnorm_bf16<decltype(v)::value>), dim3(p.rows), dim3(RMS_WG), 0, stream, p, f);
+    });
+    if (rc != GD_OK) return rc;
     GD_CHECK_LAUNCH();
     return GD_OK;
 }

@@ -1,9 +1,9 @@
 // Contiguous element-wise kernels: Listing 1's sample store, the fence probe,
 // STREAM copy and STREAM triad.  HBM-bound: 16 bytes per lane per access with
-// the nontemporal hint, all loads of a tile issued before its stores, one tile
-// of UNROLL * blockDim.x vectors per loop trip (measured best: one vector per
-// lane and a single-wavefront workgroup per 1 KiB tile).  The fence (fence.hpp) is applied to the final address
-// of every access; kernels are identical for every variant apart from it.
+// the nontemporal hint, one vector per lane and loop trip (measured best: a
+// single-wavefront workgroup per 1 KiB tile).  The fence (fence.hpp) is applied to
+// the final address of every access; kernels are identical for every variant apart
+// from it.
 #include "launchers.hpp"
 
 namespace gd {
@@ -11,7 +11,6 @@ namespace gd {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int UNROLL = 1;
 // Default workgroup of copy and triad: one wavefront, i.e. one 1 KiB tile per stream and
 // workgroup.  Measured against 128..1024 threads: +3 % for a kernel alone, +7 % for eight
 // tenants' kernels sharing the chip (the dispatcher interleaves them at a finer grain).
@@ -60,9 +59,15 @@ __global__ __launch_bounds__(1024) void k_fence_addrs(gd_args_fence_addrs p, Fen
 // OP 0: a = b.  OP 1: a = b + s*c (one fused multiply-add per element).
 // Vector path when all pointers are 16-byte aligned (then a 16-byte access equals
 // four fenced 4-byte accesses); otherwise every element is accessed on its own.
+// On the vector path a wavefront covers one contiguous 1 KiB tile of each array, so
+// the fence is taken once per tile and array on the scalar unit (Fence::tile) and
+// costs no vector instruction; a tile that the fence would split (a pointer that
+// wraps at the partition end inside it) is fenced per lane instead.
 // Under address checking a vector whose three 16-byte accesses are not all inside
 // the partition is redone element by element, so that exactly the offending
 // logical threads stop.
+constexpr int STREAM_TILE = 1024;      // bytes per wavefront and array: 64 lanes x 16 bytes
+
 template <int V, int OP>
 __global__ __launch_bounds__(1024) void k_stream(uint64_t pa, uint64_t pb, uint64_t pc, uint64_t n,
                                                  float s, uint32_t repeat, FenceArgs fa)
@@ -83,32 +88,46 @@ __global__ __launch_bounds__(1024) void k_stream(uint64_t pa, uint64_t pb, uint6
     const uint64_t ptr_bits = OP ? (pa | pb | pc) : (pa | pb);
     if ((ptr_bits & 15) == 0) {
         const uint64_t n4 = n >> 2;
-        const uint64_t tile = (uint64_t)blockDim.x * UNROLL;
-        for (uint64_t t0 = blockIdx.x * tile; t0 < n4; t0 += gridDim.x * tile) {
-            f32x4 vb[UNROLL], vc[UNROLL];
-            bool vec[UNROLL];
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                const uint64_t i = t0 + threadIdx.x + (uint64_t)u * blockDim.x;
-                vec[u] = i < n4;
-                if (F.CHECKED && vec[u] &&
+        const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        const uint32_t lane_off = Fence<V>::template tile_lane_offset<STREAM_TILE>(16 * (threadIdx.x & 63));
+        for (uint64_t t0 = (uint64_t)blockIdx.x * blockDim.x; t0 < n4; t0 += (uint64_t)gridDim.x * blockDim.x) {
+            const uint64_t w0 = t0 + 64 * wave;                  // first vector of this wavefront's tile
+            const uint64_t i = w0 + (threadIdx.x & 63);
+            uint64_t ta, tb, tc = 0;
+            uint64_t split = F.template tile<STREAM_TILE>(pb + 16 * w0, tb);
+            if (OP) split |= F.template tile<STREAM_TILE>(pc + 16 * w0, tc);
+            split |= F.template tile<STREAM_TILE>(pa + 16 * w0, ta);
+            if (split == 0) {
+                if (i < n4) {
+                    f32x4 vb = F.template ld_tile16<f32x4, true>(tb, lane_off);
+                    if (OP) {
+                        f32x4 vc = F.template ld_tile16<f32x4, true>(tc, lane_off);
+                        F.tile_wait(vb, vc);
+                        vb = vb + s * vc;
+                    } else {
+                        F.tile_wait(vb);
+                    }
+                    F.template st_tile16<f32x4, true>(ta, lane_off, vb);
+                }
+            } else if (i < n4) {
+                uint64_t i = w0 + (threadIdx.x & 63);
+                asm volatile("" : "+v"(i));          // keeps this path's address arithmetic inside the branch
+                if (F.CHECKED &&
                     !(F.template inside<16>(pb + 16 * i) && (!OP || F.template inside<16>(pc + 16 * i)) &&
                       F.template inside<16>(pa + 16 * i))) {
-                    vec[u] = false;
                     for (int e = 0; e < 4; ++e) element(4 * i + e);
+                } else {
+                    f32x4 v = F.template ld<f32x4, true>(pb + 16 * i);
+                    if (OP) v = v + s * F.template ld<f32x4, true>(pc + 16 * i);
+                    F.template st<f32x4, true>(pa + 16 * i, v);
                 }
-                if (vec[u]) {
-                    vb[u] = F.template ld<f32x4, true>(pb + 16 * i);
-                    if (OP) vc[u] = F.template ld<f32x4, true>(pc + 16 * i);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                const uint64_t i = t0 + threadIdx.x + (uint64_t)u * blockDim.x;
-                if (vec[u]) F.template st<f32x4, true>(pa + 16 * i, OP ? vb[u] + s * vc[u] : vb[u]);
             }
         }
-        if (blockIdx.x == 0 && threadIdx.x < (n & 3)) element(4 * n4 + threadIdx.x);   // at most three elements left
+        if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {          // at most three elements left
+            uint64_t i = 4 * n4 + threadIdx.x;
+            asm volatile("" : "+v"(i));              // as above: nothing of this is hoisted in front of the tiles
+            element(i);
+        }
     } else {
         const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
         for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) element(i);
@@ -125,7 +144,10 @@ int launch_store_tid(const void *args, const FenceArgs &f, int variant, const Sh
     uint32_t grid, block;
     if (!pick_1d(shape, (p.n + 255) / 256, 256, &grid, &block)) return GD_EINVAL;
     if (p.n == 0) return GD_OK;
-    GD_LAUNCH_VARIANT5(variant, k_store_tid, dim3(grid), dim3(block), stream, p, f);
+    const int rc = with_variant(variant, [&](auto v) {
+        hipLaunchKernelGGL((k_store_tid<decltype(v)::value>), dim3(grid), dim3(block), 0, stream, p, f);
+    });
+    if (rc != GD_OK) return rc;
     GD_CHECK_LAUNCH();
     return GD_OK;
 }
@@ -139,47 +161,43 @@ int launch_fence_addrs(const void *args, const FenceArgs &f, int variant, const 
     uint32_t grid, block;
     if (!pick_1d(shape, (p.n + 255) / 256, 256, &grid, &block)) return GD_EINVAL;
     if (p.n == 0) return GD_OK;
-    GD_LAUNCH_VARIANT5(variant, k_fence_addrs, dim3(grid), dim3(block), stream, p, f);
+    const int rc = with_variant(variant, [&](auto v) {
+        hipLaunchKernelGGL((k_fence_addrs<decltype(v)::value>), dim3(grid), dim3(block), 0, stream, p, f);
+    });
+    if (rc != GD_OK) return rc;
     GD_CHECK_LAUNCH();
     return GD_OK;
 }
 
-#define GD_STREAM_LAUNCH(variant, OP, grid, block, stream, ...)                                         \
-    do {                                                                                                \
-        switch (variant) {                                                                              \
-        case V_NONE:  hipLaunchKernelGGL((k_stream<V_NONE, OP>), grid, block, 0, stream, __VA_ARGS__); break;  \
-        case V_BIT32: hipLaunchKernelGGL((k_stream<V_BIT32, OP>), grid, block, 0, stream, __VA_ARGS__); break; \
-        case V_BIT64: hipLaunchKernelGGL((k_stream<V_BIT64, OP>), grid, block, 0, stream, __VA_ARGS__); break; \
-        case V_MOD:   hipLaunchKernelGGL((k_stream<V_MOD, OP>), grid, block, 0, stream, __VA_ARGS__); break;   \
-        case V_CHECK: hipLaunchKernelGGL((k_stream<V_CHECK, OP>), grid, block, 0, stream, __VA_ARGS__); break; \
-        default: return GD_ENOKERNEL;                                                                   \
-        }                                                                                               \
-    } while (0)
+static uint64_t stream_tiles(uint64_t n, uint32_t block) { return ((n >> 2) + block - 1) / block; }
 
-static uint64_t stream_tiles(uint64_t n, uint32_t block) { return ((n >> 2) + (uint64_t)block * UNROLL - 1) / ((uint64_t)block * UNROLL); }
+template <int OP>
+static int launch_stream(uint64_t a, uint64_t b, uint64_t c, uint64_t n, float s, uint32_t repeat,
+                         const FenceArgs &f, int variant, const Shape &shape, hipStream_t stream)
+{
+    const uint32_t b0 = shape.block ? shape.block[0] : STREAM_BLOCK;
+    uint32_t grid, block;
+    if (!pick_1d(shape, b0 ? stream_tiles(n, b0) : 1, STREAM_BLOCK, &grid, &block)) return GD_EINVAL;
+    if (n == 0) return GD_OK;
+    const int rc = with_variant(variant, [&](auto v) {
+        hipLaunchKernelGGL((k_stream<decltype(v)::value, OP>), dim3(grid), dim3(block), 0, stream, a, b, c, n, s,
+                           repeat ? repeat : 1u, f);
+    });
+    if (rc != GD_OK) return rc;
+    GD_CHECK_LAUNCH();
+    return GD_OK;
+}
 
 int launch_copy(const void *args, const FenceArgs &f, int variant, const Shape &shape, hipStream_t stream)
 {
     const gd_args_copy &p = *(const gd_args_copy *)args;
-    const uint32_t b0 = shape.block ? shape.block[0] : STREAM_BLOCK;
-    uint32_t grid, block;
-    if (!pick_1d(shape, b0 ? stream_tiles(p.n, b0) : 1, STREAM_BLOCK, &grid, &block)) return GD_EINVAL;
-    if (p.n == 0) return GD_OK;
-    GD_STREAM_LAUNCH(variant, 0, dim3(grid), dim3(block), stream, p.a, p.b, (uint64_t)0, p.n, 0.0f, 1u, f);
-    GD_CHECK_LAUNCH();
-    return GD_OK;
+    return launch_stream<0>(p.a, p.b, 0, p.n, 0.0f, 1, f, variant, shape, stream);
 }
 
 int launch_triad(const void *args, const FenceArgs &f, int variant, const Shape &shape, hipStream_t stream)
 {
     const gd_args_triad &p = *(const gd_args_triad *)args;
-    const uint32_t b0 = shape.block ? shape.block[0] : STREAM_BLOCK;
-    uint32_t grid, block;
-    if (!pick_1d(shape, b0 ? stream_tiles(p.n, b0) : 1, STREAM_BLOCK, &grid, &block)) return GD_EINVAL;
-    if (p.n == 0) return GD_OK;
-    GD_STREAM_LAUNCH(variant, 1, dim3(grid), dim3(block), stream, p.a, p.b, p.c, p.n, p.s, p.repeat ? p.repeat : 1u, f);
-    GD_CHECK_LAUNCH();
-    return GD_OK;
+    return launch_stream<1>(p.a, p.b, p.c, p.n, p.s, p.repeat, f, variant, shape, stream);
 }
 
 }  // namespace gd

@@ -4,6 +4,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "../../include/guardian.h"
 #include "fence.hpp"
 
@@ -49,6 +51,22 @@ inline bool pick_1d(const Shape &s, uint64_t tiles, uint32_t default_block, uint
     *grid = (uint32_t)g;
     *block = b;
     return true;
+}
+
+// The one switch from the fence variant chosen on the host to a template instance:
+// calls launch(std::integral_constant<int, V>{}), e.g.
+//     with_variant(variant, [&](auto v) { hipLaunchKernelGGL((k<decltype(v)::value>), ...); });
+template <typename F>
+inline int with_variant(int variant, F &&launch)
+{
+    switch (variant) {
+    case V_NONE:  launch(std::integral_constant<int, V_NONE>{});  return GD_OK;
+    case V_BIT32: launch(std::integral_constant<int, V_BIT32>{}); return GD_OK;
+    case V_BIT64: launch(std::integral_constant<int, V_BIT64>{}); return GD_OK;
+    case V_MOD:   launch(std::integral_constant<int, V_MOD>{});   return GD_OK;
+    case V_CHECK: launch(std::integral_constant<int, V_CHECK>{}); return GD_OK;
+    default: return GD_ENOKERNEL;
+    }
 }
 
 // Last HIP error seen by a launcher on this thread (0 = hipSuccess).

@@ -157,6 +157,16 @@ int partition_info(const Pool *p, int tenant, uint64_t *base, uint64_t *size, ui
     return GD_OK;
 }
 
+int launch_row(const Pool *p, int tenant, LaunchRow *out)
+{
+    if (!p || !out) return GD_EINVAL;
+    std::lock_guard<std::mutex> g(p->mu);
+    const Partition *r = row_of(const_cast<Pool *>(p), tenant);
+    if (!r) return GD_ENOTENANT;
+    *out = LaunchRow{r->base, r->size, p->flex, p->fault_counters, p->fault_slots};
+    return GD_OK;
+}
+
 int alloc(Pool *p, int tenant, uint64_t bytes, uint64_t align, uint64_t *dptr_out)
 {
     if (!p || !dptr_out || bytes == 0 || !is_pow2(align)) return GD_EINVAL;

@@ -41,6 +41,15 @@ int set_fault_counters(Pool *p, uint64_t dev_counters, int slots);
 int tenant_attach(Pool *p, uint64_t bytes, int *tenant_out);
 int tenant_detach(Pool *p, int tenant);
 int partition_info(const Pool *p, int tenant, uint64_t *base, uint64_t *size, uint64_t *mask);
+
+// Everything a launch needs from the pool, read in one go under the pool's lock.
+struct LaunchRow {
+    uint64_t base, size;
+    bool flex;
+    uint64_t fault_counters;
+    int fault_slots;
+};
+int launch_row(const Pool *p, int tenant, LaunchRow *out);
 int alloc(Pool *p, int tenant, uint64_t bytes, uint64_t align, uint64_t *dptr_out);
 int free_(Pool *p, int tenant, uint64_t dptr);
 int check_copy(const Pool *p, int tenant, uint64_t dptr, uint64_t bytes);

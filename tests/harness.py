@@ -105,3 +105,31 @@ def rel_frobenius(got, ref):
     got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
     den = np.linalg.norm(ref)
     return np.linalg.norm(got - ref) / (den if den else 1.0)
+
+
+def bf16_bits_to_f64(h):
+    return (np.ascontiguousarray(h, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def assert_bf16_close(got_bits, want_bits, abs_tol=0.0, flip_budget=0.02, frobenius=True, what=""):
+    """bf16 output against the oracle's bf16 output, element by element.
+
+    The kernel accumulates in fp32 and the oracle in fp64, so a result that falls next
+    to a rounding boundary may land on the neighbouring bf16 value: every element must
+    be within ONE bf16 unit in the last place of the oracle's value (2^-7 relative)
+    plus `abs_tol` (the fp32 accumulation error, which matters for entries near zero),
+    at most `flip_budget` of the elements may differ at all, and the relative
+    Frobenius error stays within 1e-3 (`frobenius=False` when the caller passes only
+    the elements that differ, whose norm says nothing)."""
+    got, want = bf16_bits_to_f64(got_bits).reshape(-1), bf16_bits_to_f64(want_bits).reshape(-1)
+    assert got.shape == want.shape
+    if got.size == 0:
+        return
+    err = np.abs(got - want)
+    bound = 2.0 ** -7 * np.abs(want) + abs_tol
+    worst = int(np.argmax(err - bound))
+    assert err[worst] <= bound[worst], f"{what}: element {worst}: got {got[worst]!r}, oracle {want[worst]!r}"
+    flips = float(np.mean(np.asarray(got_bits).reshape(-1) != np.asarray(want_bits).reshape(-1)))
+    assert flips <= flip_budget, f"{what}: {flips:.4f} of the elements differ from the oracle"
+    if frobenius:
+        assert rel_frobenius(got, want) <= 1e-3, what

@@ -11,7 +11,7 @@ import torch
 
 import paper_2401_09290_amd as gd
 import synth_inputs as si
-from harness import GiB, MiB, Rig, rel_frobenius
+from harness import assert_bf16_close, GiB, MiB, Rig, rel_frobenius
 from oracle import kernels as ok
 
 pytestmark = pytest.mark.gpu
@@ -178,16 +178,38 @@ def test_config4_gemm_8192_sampled_entries_and_slab():
         sim = ok.SimPool(base, 2 * 2 * M * K, 0)
         sim.view(A, np.uint16, M * K)[:] = Ab
         sim.view(B, np.uint16, K * N)[:] = Bb
+        # Stratified sample: 8 entries in each of the 32 x 32 workgroup tiles (256 x 256), chosen so that
+        # every accumulator slot of the kernel -- wavefront (2 x 2), MFMA tile (8 x 8), lane group (4),
+        # register (4): 4096 classes -- is hit twice over the matrix; the lane's row inside its 16 is random.
         g = np.random.Generator(np.random.PCG64(44))
-        ms = np.concatenate([g.integers(0, M, 1500), [0, 0, M - 1, M - 1, 127, 128, 255, 256]])
-        ns = np.concatenate([g.integers(0, N, 1500), [0, N - 1, 0, N - 1, 128, 127, 256, 255]])
+        ms, ns = [], []
+        for tile in range(1024):
+            tm, tn = divmod(tile, 32)
+            for k in range(8):
+                slot = (8 * tile + k) % 4096
+                wave, i, j, lg, reg = slot >> 10, (slot >> 7) & 7, (slot >> 4) & 7, (slot >> 2) & 3, slot & 3
+                ms.append(256 * tm + 128 * (wave >> 1) + 16 * i + int(g.integers(0, 16)))
+                ns.append(256 * tn + 128 * (wave & 1) + 16 * j + 4 * lg + reg)
+        ms = np.concatenate([ms, [0, 0, M - 1, M - 1, 127, 128, 255, 256]])
+        ns = np.concatenate([ns, [0, N - 1, 0, N - 1, 128, 127, 256, 255]])
         exact = np.array([sim.run("gemm_bf16_entry", (base, size), ok.MODE_BITWISE, A, B, N, K, 1, int(m), int(n))
                           for m, n in zip(ms, ns)])
         assert sim.last[0] == 0
-        want = np.array([ok.lib().gdo_bf16_to_double(ok.lib().gdo_double_to_bf16(float(e))) for e in exact])
+        want_bits = np.array([ok.lib().gdo_double_to_bf16(float(e)) for e in exact], dtype=np.uint16)
+        assert_bf16_close(got[ms, ns], want_bits, abs_tol=3e-5, what="gemm 8192^3, stratified sample")
         have = si.bf16_bits_to_f32(got[ms, ns]).astype(np.float64)
-        assert rel_frobenius(have, want) <= BF16_TOL
         assert np.all(np.abs(have - exact) <= 2.0**-8 * np.abs(exact) * 1.01 + 1e-4)   # within one rounding of exact
+        # The whole matrix against the second reference: NumPy's fp64 matmul of the same bf16 values,
+        # rounded to bf16 (float64 -> float32 -> bf16; the double rounding can move a tie by one unit,
+        # which the one-unit bound covers).  Every one of the 67 M entries is checked.
+        ref = si.bf16_bits_to_f32(Ab).reshape(M, K).astype(np.float64) @ si.bf16_bits_to_f32(Bb).reshape(N, K).astype(np.float64).T
+        ref_bits = si.f32_to_bf16_bits(ref.astype(np.float32).reshape(-1))
+        assert np.mean(ref_bits.reshape(M, N)[ms, ns] != want_bits) < 0.01      # the two references agree on the sample
+        del ref
+        for r0 in range(0, M, 1024):                                              # in slabs: keeps the temporaries small
+            assert_bf16_close(got[r0:r0 + 1024], ref_bits.reshape(M, N)[r0:r0 + 1024], abs_tol=3e-5,
+                              what=f"gemm 8192^3 vs NumPy, rows {r0}..")
+        del ref_bits
         # a slab of whole rows, computed entry by entry by the oracle's kernel
         rows = (0, 4097)
         for m0 in rows:

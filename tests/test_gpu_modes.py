@@ -9,7 +9,7 @@ import torch
 
 import paper_2401_09290_amd as gd
 import synth_inputs as si
-from harness import KiB, MiB, Rig, rel_frobenius
+from harness import KiB, MiB, Rig, assert_bf16_close, rel_frobenius
 from oracle import host_model as hm
 from oracle import kernels as ok
 
@@ -149,7 +149,7 @@ def test_modulo_mode_rmsnorm_and_gemm_match_the_oracle():
         gd.gd_launch_fenced(r.pool, 0, gd.GD_K_RMSNORM_BF16, gd.gd_args_rmsnorm(y + size, x - size, gain, rows, cols, 1e-6, 0), mode=gd.GD_FENCE_MODULO)
         r.sim.run("rmsnorm_bf16", (base, size), ok.MODE_MODULO, y + size, x - size, gain, rows, cols, 1e-6)
         got, want = r.download(y, np.uint16, rows * cols), r.sim.view(y, np.uint16, rows * cols)
-        assert rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want)) <= 1e-3
+        assert_bf16_close(got, want, what="modulo rmsnorm")
         for (M, N, K) in ((256, 256, 128), (100, 72, 40)):
             A, B, Cc = r.alloc(0, 2 * M * K), r.alloc(0, 2 * K * N), r.alloc(0, 2 * M * N)
             r.upload(0, A, si.f32_to_bf16_bits(si.normal_f32(g, M * K) * np.float32(K ** -0.5)))
@@ -157,7 +157,7 @@ def test_modulo_mode_rmsnorm_and_gemm_match_the_oracle():
             gd.gd_launch_fenced(r.pool, 0, gd.GD_K_GEMM_BF16, gd.gd_args_gemm(Cc, A + size, B - 2 * size, M, N, K, 1), mode=gd.GD_FENCE_MODULO)
             r.sim.run("gemm_bf16", (base, size), ok.MODE_MODULO, Cc, A + size, B - 2 * size, M, N, K, 1, 0, M, 0, N)
             got, want = r.download(Cc, np.uint16, M * N), r.sim.view(Cc, np.uint16, M * N)
-            assert rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want)) <= 1e-3
+            assert_bf16_close(got, want, abs_tol=3e-5, what=f"modulo gemm {M}x{N}x{K}")
         # nothing outside tenant 0's partition changed
         lo = r.table[1][0] - r.base
         assert np.all(r.dev[lo:].cpu().numpy() == 0xA5)
@@ -276,11 +276,95 @@ def test_checking_on_indexed_kernels_and_sum(checked):
     assert faults(counters, 0) == 0
 
 
-def test_checking_is_not_built_for_rmsnorm_and_gemm(checked):
-    r, _ = checked
-    base, _ = r.row(0)
-    for kid, args in ((gd.GD_K_RMSNORM_BF16, gd.gd_args_rmsnorm(base, base + 4096, base + 8192, 1, 64, 1e-6, 0)),
-                      (gd.GD_K_GEMM_BF16, gd.gd_args_gemm(base, base + 65536, base + 131072, 16, 16, 16, 1))):
-        with pytest.raises(gd.GuardianError) as e:
-            r.launch(0, kid, args, mode=gd.GD_FENCE_CHECK)
-        assert e.value.status == gd.GD_ENOKERNEL
+def test_checking_rmsnorm_stops_rows_and_elements_and_counts_them(checked):
+    """Thread (r, j) reads all of row r, then g[j], then stores y[r,j] (Sections 4.3, 4.4): a row of x
+    that is not wholly inside stops all of its threads, a gain or an output outside stops one thread."""
+    r, counters = checked
+    t = 0
+    base, size = r.row(t)
+    end = base + size
+    g = si.rng(6, 90)
+    total = 0
+    for rows, cols, shift in ((12, 2048, 0), (5, 8192, 0), (9, 1000, 0), (7, 520, 2)):
+        nbytes = 2 * rows * cols
+        xin = r.alloc(t, nbytes + 64) + shift
+        gain_in = r.alloc(t, 2 * cols + 64) + shift
+        yin = r.alloc(t, nbytes + 64) + shift
+        r.upload(t, xin, si.f32_to_bf16_bits(si.normal_f32(g, rows * cols)))
+        r.upload(t, gain_in, si.f32_to_bf16_bits(si.uniform_f32(g, cols, 0.5, 1.5)))
+        # the last bytes of the partition: free of allocations in this rig (4 MiB, a few hundred KiB in use)
+        r.upload(t, end - 2 * cols, si.f32_to_bf16_bits(si.uniform_f32(g, cols, 0.5, 1.5)))
+        r.upload(t, end - 4 * cols - nbytes, si.f32_to_bf16_bits(si.normal_f32(g, rows * cols + cols)))
+        cases = [
+            (yin, xin, gain_in),                                         # everything inside
+            (yin, xin, end - 2 * (cols - 37)),                           # the last 37 gains are outside
+            (yin, end - nbytes + 2 * (cols // 3), gain_in),              # the last third of x's last row is outside
+            (end - nbytes + 2 * (2 * cols + 21), xin, gain_in),          # y leaves the partition in row rows-3
+            (yin, base - 2 * (cols + 5), gain_in),                       # x starts in front: rows 0 and 1 are refused
+        ]
+        for (y, x, gain) in cases:
+            r.dview(yin - shift, np.uint8, nbytes + 64).fill_(0x33)
+            r.sim.view(yin - shift, np.uint8, nbytes + 64)[:] = 0x33
+            r.launch(t, gd.GD_K_RMSNORM_BF16, gd.gd_args_rmsnorm(y, x, gain, rows, cols, 1e-6, 0), mode=gd.GD_FENCE_CHECK)
+            r.oracle("rmsnorm_bf16", t, y, x, gain, rows, cols, 1e-6, mode=ok.MODE_CHECK)
+            total += r.sim.last[1]
+            assert faults(counters, t) == total, (rows, cols, shift, hex(y), hex(x), hex(gain), r.sim.last)
+            got, want = r.image(), r.sim.mem
+            # bf16 outputs may differ by a unit in the last place; every byte the oracle left alone is left alone
+            changed = got != want
+            if changed.any():
+                pos = np.flatnonzero(changed) // 2 * 2
+                pos = np.unique(pos)
+                gb = got[pos].astype(np.uint16) | (got[pos + 1].astype(np.uint16) << 8)
+                wb = want[pos].astype(np.uint16) | (want[pos + 1].astype(np.uint16) << 8)
+                assert_bf16_close(gb, wb, flip_budget=1.0, frobenius=False, what="checked rmsnorm")
+                assert pos.size <= 0.02 * rows * cols + 2
+            # same bits on both sides again before the next case reads what this one wrote
+            r.dview(base, np.uint8, size).copy_(torch.from_numpy(r.sim.view(base, np.uint8, size)))
+        assert total > 0
+        for p in (xin - shift, gain_in - shift, yin - shift):
+            r.free(t, p)
+    assert faults(counters, 1) == 0
+
+
+def test_checking_gemm_stops_threads_with_a_refused_operand_row_or_column(checked):
+    """Thread (m, n) needs row m of A, column n of B and C[m,n]; tile-multiple, ragged and generic shapes."""
+    r, counters = checked
+    t = 1
+    base, size = r.row(t)
+    end = base + size
+    g = si.rng(6, 91)
+    total = 0
+    for (M, N, K, b_is_nk) in ((256, 256, 128, 1), (300, 200, 72, 1), (64, 40, 24, 0), (50, 70, 33, 1)):
+        A_in, B_in, C_in = r.alloc(t, 2 * M * K), r.alloc(t, 2 * K * N), r.alloc(t, 2 * M * N)
+        a_bits = si.f32_to_bf16_bits(si.normal_f32(g, M * K) * np.float32(K ** -0.5))
+        b_bits = si.f32_to_bf16_bits(si.normal_f32(g, K * N))
+        r.upload(t, A_in, a_bits)
+        r.upload(t, B_in, b_bits)
+        # a copy of A that runs over the end of the partition
+        a_cut = 2 * (K * (M - M // 3) + 16)
+        r.upload(t, end - a_cut, a_bits[: a_cut // 2])
+        A_over = end - a_cut                                            # rows from about 2M/3 on are not wholly inside
+        cases = [(C_in, A_in, B_in),
+                 (C_in, A_over, B_in),
+                 (end - 2 * (N * (M // 2) + N // 4), A_in, B_in),       # C leaves the partition in its middle row
+                 (C_in, A_in, base - 2 * (3 * K + 8) if b_is_nk else base - 2 * 5)]   # B starts in front of the partition
+        for (Cc, A, B) in cases:
+            r.dview(C_in, np.uint8, 2 * M * N).fill_(0x33)
+            r.sim.view(C_in, np.uint8, 2 * M * N)[:] = 0x33
+            r.launch(t, gd.GD_K_GEMM_BF16, gd.gd_args_gemm(Cc, A, B, M, N, K, b_is_nk), mode=gd.GD_FENCE_CHECK)
+            r.oracle("gemm_bf16", t, Cc, A, B, M, N, K, b_is_nk, 0, M, 0, N, mode=ok.MODE_CHECK)
+            total += r.sim.last[1]
+            assert faults(counters, t) == total, (M, N, K, b_is_nk, hex(Cc), hex(A), hex(B), r.sim.last)
+            got, want = r.image(), r.sim.mem
+            changed = got != want
+            if changed.any():
+                pos = np.unique(np.flatnonzero(changed) // 2 * 2)
+                gb = got[pos].astype(np.uint16) | (got[pos + 1].astype(np.uint16) << 8)
+                wb = want[pos].astype(np.uint16) | (want[pos + 1].astype(np.uint16) << 8)
+                assert_bf16_close(gb, wb, abs_tol=3e-5, flip_budget=1.0, frobenius=False, what="checked gemm")
+                assert pos.size <= 0.02 * M * N + 2
+            r.dview(base, np.uint8, size).copy_(torch.from_numpy(r.sim.view(base, np.uint8, size)))
+        for p in (A_in, B_in, C_in):
+            r.free(t, p)
+    assert total > 0 and faults(counters, 0) == 0

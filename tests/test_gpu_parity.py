@@ -13,13 +13,16 @@ import torch
 
 import paper_2401_09290_amd as gd
 import synth_inputs as si
-from harness import GiB, KiB, MiB, Rig, rel_frobenius
+from harness import GiB, KiB, MiB, Rig, assert_bf16_close, rel_frobenius
 from oracle import kernels as ok
 
 pytestmark = pytest.mark.gpu
 
 FP32_TOL = 1e-5
 BF16_TOL = 1e-3
+# fp32 accumulation of K products of magnitude ~1/sqrt(K) each (entries of C ~ N(0,1)): a few 1e-6
+# absolute for K up to 8192; it decides the bf16 rounding only for entries that close to zero.
+GEMM_ABS_TOL = 3e-5
 
 
 @pytest.fixture()
@@ -167,6 +170,108 @@ def test_triad_through_out_of_partition_pointers_wraps_into_own_partition(rig2):
     a1 = a0 - b0 + b1
     assert rel_frobenius(r.download(a1, np.float32, n), r.sim.view(a1, np.float32, n)) <= FP32_TOL
     r.assert_images_equal(skip=[(a1, 4 * n)], what="foreign-pointer triad")
+
+
+@pytest.mark.parametrize("repeat", [2, 7])
+@pytest.mark.parametrize("mode", [gd.GD_FENCE_NONE, gd.GD_FENCE_BITWISE, gd.GD_FENCE_MODULO, gd.GD_FENCE_CHECK])
+def test_triad_repeat_field_gives_the_single_pass_image(mode, repeat):
+    """The triad's `repeat` field performs the same pass several times inside one launch (the
+    cache-resident regime the benchmark times); the image must be that of one pass, in every
+    fence variant, for aligned and misaligned pointers and for caller-chosen launch shapes."""
+    r = Rig([4 * MiB, 4 * MiB])
+    try:
+        counters = torch.zeros(4, dtype=torch.int64, device="cuda")
+        gd.gd_pool_set_fault_counters(r.pool, counters.data_ptr(), 4)
+        omode = {gd.GD_FENCE_NONE: ok.MODE_NONE, gd.GD_FENCE_BITWISE: ok.MODE_BITWISE,
+                 gd.GD_FENCE_MODULO: ok.MODE_MODULO, gd.GD_FENCE_CHECK: ok.MODE_CHECK}[mode]
+        g = si.rng(0, 43)
+        for n, shift, shape in ((100003, 0, {}), (30001, 4, {}), (65536, 0, dict(grid=(3, 1, 1), block=(256, 1, 1)))):
+            a = r.alloc(0, 4 * n + 64) + shift
+            b = r.alloc(0, 4 * n + 64) + shift
+            c = r.alloc(0, 4 * n + 64) + (shift and 12)
+            r.upload(0, b, si.uniform_f32(g, n))
+            r.upload(0, c, si.uniform_f32(g, n))
+            r.launch(0, gd.GD_K_TRIAD, gd.gd_args_triad(a, b, c, n, -0.625, repeat), mode=mode, **shape)
+            r.oracle("triad", 0, a, b, c, -0.625, n, mode=omode)
+            assert rel_frobenius(r.download(a, np.float32, n), r.sim.view(a, np.float32, n)) <= FP32_TOL
+            r.assert_images_equal(skip=[(a, 4 * n)], what=f"triad repeat={repeat} mode={mode} n={n}")
+            once = r.download(a, np.uint32, n).copy()
+            r.dview(a, np.uint8, 4 * n).fill_(0)
+            r.launch(0, gd.GD_K_TRIAD, gd.gd_args_triad(a, b, c, n, -0.625, 0), mode=mode, **shape)
+            assert np.array_equal(r.download(a, np.uint32, n), once)       # bit-identical to the single pass
+        torch.cuda.synchronize()
+        assert int(counters.sum().item()) == 0
+    finally:
+        r.close()
+
+
+@pytest.mark.parametrize("mode", [gd.GD_FENCE_BITWISE, gd.GD_FENCE_MODULO])
+def test_copy_triad_with_a_wavefront_tile_split_by_the_partition_end(rig2, mode):
+    """16-byte aligned arrays that run over the end of the partition in the middle of a wavefront's
+    1 KiB tile: the scalar fence of that tile does not apply, its lanes are fenced one by one, and
+    the whole image still equals the oracle's (tiles before and after take the scalar path)."""
+    r = rig2
+    omode = ok.MODE_BITWISE if mode == gd.GD_FENCE_BITWISE else ok.MODE_MODULO
+    base, size = r.row(1)
+    g = si.rng(0, 44)
+    n = 6000
+    for cut in (16, 1024 - 16, 400 * 4, 1024 * 3 + 528):          # bytes of the array in front of the partition end
+        lo = r.alloc(1, 64 * KiB)                                  # keeps the partition's first bytes free of inputs
+        b, c = r.alloc(1, 4 * n), r.alloc(1, 4 * n)
+        r.upload(1, b, si.uniform_f32(g, n))
+        r.upload(1, c, si.uniform_f32(g, n))
+        a = base + size - cut                                      # output wraps to the partition's first bytes
+        r.launch(1, gd.GD_K_TRIAD, gd.gd_args_triad(a, b, c, n, 0.5, 0), mode=mode)
+        r.oracle("triad", 1, a, b, c, 0.5, n, mode=omode)
+        assert r.sim.last[2] == n - cut // 4
+        head, tail = r.download(a, np.float32, cut // 4), r.download(base, np.float32, n - cut // 4)
+        want = np.concatenate([r.sim.view(a, np.float32, cut // 4), r.sim.view(base, np.float32, n - cut // 4)])
+        assert rel_frobenius(np.concatenate([head, tail]), want) <= FP32_TOL
+        r.assert_images_equal(skip=[(a, cut), (base, 4 * n - cut)], what=f"split tile, cut={cut}")
+        # a split tile on the input side: copy the wrapped array out again, through aliases one partition off
+        r.upload(1, a, r.sim.view(a, np.float32, cut // 4).copy())             # same bits on both sides first
+        r.upload(1, base, r.sim.view(base, np.float32, n - cut // 4).copy())
+        dst = r.alloc(1, 4 * n)
+        r.launch(1, gd.GD_K_COPY, gd.gd_args_copy(dst + size, a - size, n), mode=mode)
+        r.oracle("copy", 1, dst + size, a - size, n, mode=omode)
+        r.assert_images_equal(what=f"split tile copy, cut={cut}")
+        for p in (lo, b, c, dst):
+            r.free(1, p)
+
+
+def test_triad_tile_split_on_a_partition_larger_than_4gib():
+    """The same on the 64-bit rule (8 GiB partition): values from the oracle on the in-bounds twin of the
+    launch, locations from the oracle's fence."""
+    r = Rig([8 * GiB], fill=None, simulate=False)
+    try:
+        base, size = r.row(0)
+        g = si.rng(0, 45)
+        n = 5000
+        cut = 1024 * 2 + 272
+        r.alloc(0, 5 * GiB)
+        b, c = r.alloc(0, 4 * n), r.alloc(0, 4 * n)
+        assert b - base > 4 * GiB
+        vb, vc = si.uniform_f32(g, n), si.uniform_f32(g, n)
+        r.upload(0, b, vb)
+        r.upload(0, c, vc)
+        a = base + size - cut
+        r.dview(base, np.uint8, 4 * n).fill_(0x5A)
+        r.dview(a - 4096, np.uint8, 4096 + cut).fill_(0x5A)
+        r.launch(0, gd.GD_K_TRIAD, gd.gd_args_triad(a, b + size, c - size, n, 0.5, 0))
+        sim = ok.SimPool(1 << 30, 3 * 4 * n, 0)                   # in-bounds twin: plain addresses, same values
+        sa, sb_, sc = sim.pool_base, sim.pool_base + 4 * n, sim.pool_base + 8 * n
+        sim.view(sb_, np.float32, n)[:] = vb
+        sim.view(sc, np.float32, n)[:] = vc
+        sim.run("triad", (sim.pool_base, 1 << 30), ok.MODE_BITWISE, sa, sb_, sc, 0.5, n)
+        where = ok.fence_array(base, size, np.uint64(a) + 4 * np.arange(n, dtype=np.uint64), 4)
+        assert np.array_equal(where[: cut // 4], a + 4 * np.arange(cut // 4, dtype=np.uint64))
+        assert np.array_equal(where[cut // 4:], base + 4 * np.arange(n - cut // 4, dtype=np.uint64))
+        got = np.concatenate([r.download(a, np.float32, cut // 4), r.download(base, np.float32, n - cut // 4)])
+        assert rel_frobenius(got, sim.view(sa, np.float32, n)) <= FP32_TOL
+        assert np.all(r.download(a - 4096, np.uint8, 4096) == 0x5A)                       # nothing in front of the output
+        assert np.all(r.download(base + 4 * n - cut, np.uint8, cut) == 0x5A)              # nothing behind its wrapped part
+    finally:
+        r.close()
 
 
 # ---------------------------------------------------------------------------
@@ -419,7 +524,10 @@ def test_rmsnorm_against_oracle(rows, cols, shift):
                                            (256, 256, 256, 1), (256, 256, 384, 1), (256, 512, 512, 1), (256, 256, 640, 1),
                                            (512, 256, 768, 1), (256, 256, 896, 1), (256, 256, 1280, 1),
                                            # K % 128 = 64: the ring of K = 64 blocks, every way it can end (K/64 mod 5)
-                                           (256, 256, 320, 1), (256, 512, 448, 1), (256, 256, 576, 1)])
+                                           (256, 256, 320, 1), (256, 512, 448, 1), (256, 256, 576, 1),
+                                           # a multiple of 8 workgroup tiles (the renumbering over the 8 XCDs is on) and
+                                           # more tile rows than one band of GROUP_M = 4, the last band ragged
+                                           (2048, 1024, 128, 1), (1280, 2048, 256, 1), (2304, 768, 64, 1)])
 def test_gemm_against_oracle(M, N, K, b_is_nk):
     r = Rig([8 * MiB, 4 * MiB])
     try:
@@ -434,6 +542,7 @@ def test_gemm_against_oracle(M, N, K, b_is_nk):
         got = r.download(Cc, np.uint16, M * N)
         want = r.sim.view(Cc, np.uint16, M * N)
         assert rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want)) <= BF16_TOL
+        assert_bf16_close(got, want, abs_tol=GEMM_ABS_TOL, what=f"gemm {M}x{N}x{K}")
         r.assert_images_equal(skip=[(Cc, 2 * M * N)], what="gemm")
         r.dview(Cc, np.uint8, 2 * M * N).fill_(0)
         r.launch(0, gd.GD_K_GEMM_BF16, args, mode=gd.GD_FENCE_NONE)
@@ -457,7 +566,7 @@ def test_gemm_with_wrapping_operand_pointers():
         r.launch(t, gd.GD_K_GEMM_BF16, gd.gd_args_gemm(Cc + size, A - size, B - size, M, N, K, 1))
         r.oracle("gemm_bf16", t, Cc + size, A - size, B - size, M, N, K, 1, 0, M, 0, N)
         got, want = r.download(Cc, np.uint16, M * N), r.sim.view(Cc, np.uint16, M * N)
-        assert rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want)) <= BF16_TOL
+        assert_bf16_close(got, want, abs_tol=GEMM_ABS_TOL, what="gemm wrapped")
         r.assert_images_equal(skip=[(Cc, 2 * M * N)], what="gemm wrapped")
     finally:
         r.close()
@@ -479,7 +588,7 @@ def test_gemm_operands_aligned_to_16_bytes_only():
         r.oracle("gemm_bf16", 0, Cc, A, B, M, N, K, 1, 0, M, 0, N)
         got = r.download(Cc, np.uint16, M * N)
         want = r.sim.view(Cc, np.uint16, M * N)
-        assert rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want)) <= BF16_TOL
+        assert_bf16_close(got, want, abs_tol=GEMM_ABS_TOL, what="gemm, 16-byte aligned operands")
         r.assert_images_equal(skip=[(Cc, 2 * M * N)], what="gemm, 16-byte aligned operands")
     finally:
         r.close()
@@ -508,7 +617,7 @@ def test_gemm_tile_kernel_with_an_operand_running_past_the_partition_end():
         r.launch(t, gd.GD_K_GEMM_BF16, args)
         r.oracle("gemm_bf16", t, Cc - size, A, B + size, M, N, K, 1, 0, M, 0, N)
         got, want = r.download(Cc, np.uint16, M * N), r.sim.view(Cc, np.uint16, M * N)
-        assert rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want)) <= BF16_TOL
+        assert_bf16_close(got, want, abs_tol=GEMM_ABS_TOL, what="gemm wrapped at the partition end")
         r.assert_images_equal(skip=[(Cc, 2 * M * N)], what="gemm wrapped at the partition end")
         # and it is the product of the matrix as uploaded
         ref = si.bf16_bits_to_f32(a_bits).reshape(M, K).astype(np.float64) @ \

@@ -16,8 +16,9 @@ def test_every_global_access_of_the_fenced_kernels_is_fenced():
     # all five variants of the element-wise kernels, three fence variants + modulo of the rest
     for v in range(5):
         assert f"k_stream<{v}, 1>" in names and f"k_gather32<{v}, 1>" in names and f"k_sum_partial<{v}>" in names
+        assert f"k_rmsnorm_bf16<{v}>" in names and f"k_gemm_nk256<{v}, true>" in names
     for v in range(4):
-        assert f"k_gemm_ring<{v}>" in names and f"k_rmsnorm_bf16<{v}>" in names
+        assert f"k_gemm_ring<{v}>" in names
     fenced = [r for r in rows if r[1] in (1, 2) and (r[2] + r[3]) > 0]
     assert fenced and all(r[4] > 0 for r in fenced if r[1] == 1)        # the 32-bit fence shows up as v_and_b32
     # the fence costs at most a handful of registers (the paper: up to two at -O3)
@@ -25,3 +26,59 @@ def test_every_global_access_of_the_fenced_kernels_is_fenced():
     for r in rows:
         if r[1] == 1 and r[0].replace("<1", "<0", 1) in base and "gemm" not in r[0]:
             assert r[5] - base[r[0].replace("<1", "<0", 1)][5] <= 4, r
+
+
+
+# ---- the audit itself, on hand-made assembly: a planted mistake must be reported ----------
+
+GOOD_TILE = """
+    s_load_dwordx4 s[4:7], s[0:1], 0x0
+    v_and_b32 v1, 0x3ff, v0
+    s_cmp_eq_u32 s2, 0
+    s_cbranch_scc1 .LBB0_2
+    s_and_b64 s[8:9], s[4:5], s[6:7]
+    s_or_b64 s[8:9], s[8:9], s[10:11]
+    s_branch .LBB0_3
+.LBB0_2:
+    s_and_b64 s[8:9], s[12:13], s[6:7]
+    s_or_b64 s[8:9], s[8:9], s[10:11]
+.LBB0_3:
+    global_load_dwordx4 v[2:5], v1, s[8:9] nt
+    s_endpgm
+"""
+
+
+def lint_text(text, variant):
+    body = [ln.split(";")[0].rstrip() for ln in text.strip().splitlines()]
+    return isa_lint.lint_kernel("k", "k_test<%d>" % variant, body, variant)[0]
+
+
+def test_audit_follows_every_path_to_an_access():
+    assert lint_text(GOOD_TILE, 2) == []
+    # one of the two paths forgets the OR with the base: the base pair then has an unfenced definition
+    bad = GOOD_TILE.replace("    s_and_b64 s[8:9], s[12:13], s[6:7]\n    s_or_b64 s[8:9], s[8:9], s[10:11]\n",
+                            "    s_and_b64 s[8:9], s[12:13], s[6:7]\n")
+    assert bad != GOOD_TILE
+    assert any("base also defined" in p for p in lint_text(bad, 2))
+    # a lane offset that is not confined below the tile size
+    assert any("offset defined by" in p for p in lint_text(GOOD_TILE.replace("v_and_b32 v1, 0x3ff, v0", "v_lshlrev_b32 v1, 4, v0"), 2))
+    # per-lane rules: an offset that skips the AND on one path (32-bit rule), a high word without the OR (64-bit rule)
+    lane32 = """
+    v_lshlrev_b32 v1, 2, v0
+    s_cbranch_scc1 .LBB0_2
+    v_and_b32 v1, s6, v1
+.LBB0_2:
+    global_store_dword v1, v2, s[4:5]
+    s_endpgm
+"""
+    assert any("defined by `v_lshlrev_b32" in p for p in lint_text(lane32, 1))
+    assert lint_text(lane32.replace("    s_cbranch_scc1 .LBB0_2\n", ""), 1) == []
+    lane64 = """
+    v_and_b32 v3, s7, v3
+    v_or_b32 v3, s5, v3
+    global_load_dword v4, v[2:3], off
+    s_endpgm
+"""
+    assert lint_text(lane64, 2) == []
+    assert lint_text(lane64.replace("    v_or_b32 v3, s5, v3\n", ""), 2)
+    assert any("flat access" in p for p in lint_text("    flat_load_dword v1, v[2:3]\n    s_endpgm", 0))
