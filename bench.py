@@ -115,8 +115,9 @@ def timed_rounds(torch, streams, launch_round, steps, warmup):
         e.record(s)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    dev = max(go.elapsed_time(e) for e in ends) * 1e-3
-    return dev, wall
+    per_stream = [go.elapsed_time(e) * 1e-3 for e in ends]
+    timed_rounds.per_stream = per_stream           # seconds from the release to each stream's end event
+    return max(per_stream), wall
 
 
 def solo_avg_seconds(torch, stream, launch, reps, warmup=2):
@@ -441,9 +442,28 @@ def run_c5(torch, gd, si, args):
         for t, (kind, kid, kargs, nbytes, _) in work.items():
             gd.gd_launch_fenced(dp.pool, t, kid, kargs, stream=streams[t].cuda_stream, mode=gd.GD_FENCE_BITWISE)
 
+    def breakdown(dev):
+        """Per kind of kernel in the mixed rounds: tenants, their share of the bytes, and when their
+        streams finished (all streams start together, so a kind that ends late is what the round waits for)."""
+        out = {}
+        for kind in kinds:
+            ts = [t for t in work if work[t][0] == kind]
+            if not ts:
+                continue
+            end = [timed_rounds.per_stream[t] for t in ts]
+            nbytes = sum(work[t][3] for t in ts) * args.steps
+            out[kind] = {"tenants": len(ts), "bytes_share": round(sum(work[t][3] for t in ts) / sum(w[3] for w in work.values()), 3),
+                         "last_stream_done_at_frac_of_round": round(max(end) / dev, 3),
+                         "GBps_until_its_last_stream_ends": round(nbytes / max(end) / 1e9, 1)}
+        return out
+
     bytes_round = sum(w[3] for w in work.values())
     dev, _ = timed_rounds(torch, streams, mixed_round, args.steps, args.warmup)
     res["mixed_fenced_GBps_before_recarve"] = bytes_round * args.steps / dev / 1e9
+    res["mixed_breakdown_before_recarve"] = breakdown(dev)
+    # what the same launches would take one after the other at their solo rates: the mixed round is bound by the
+    # gathers (line traffic, see the solo figures), which take most of the time while moving a small share of the bytes
+    res["mixed_serial_estimate_GBps"] = round(bytes_round / sum(w[3] / (res[f"{w[0]}_fenced_GBps"] * 1e9) for w in work.values()) / 1e9, 1)
 
     # re-carve: four tenants free everything, detach, and come back with another size
     t0 = time.perf_counter()
@@ -472,6 +492,8 @@ def run_c5(torch, gd, si, args):
     bytes_round = sum(w[3] for w in work.values())
     dev, _ = timed_rounds(torch, streams, mixed_round, args.steps, args.warmup)
     res["mixed_fenced_GBps_after_recarve"] = bytes_round * args.steps / dev / 1e9
+    res["mixed_breakdown_after_recarve"] = breakdown(dev)
+    res["assignment_after_recarve"] = {int(t): work[t][0] for t in sorted(work)}
     log(f"[c5] mixed 16-stream rounds: {res['mixed_fenced_GBps_before_recarve']:.1f} GB/s before, {res['mixed_fenced_GBps_after_recarve']:.1f} GB/s after the re-carve")
     dp.close()
     return res
@@ -492,7 +514,7 @@ def run_modes(torch, gd, si, args):
     st = torch.cuda.Stream()
     g = si.rng(6, 0)
     modes = (("none", gd.GD_FENCE_NONE), ("bitwise", gd.GD_FENCE_BITWISE), ("modulo", gd.GD_FENCE_MODULO), ("check", gd.GD_FENCE_CHECK))
-    res = {"workload": "1 tenant, 4 GiB partition, all accesses in bounds: fp32 triad 2^26 (HBM resident), triad 2^22 repeated 200 times inside one launch (each workgroup re-reads its own 3 KiB: cache resident), gather 2^24 with int64 indices"}
+    res = {"workload": "1 tenant, 4 GiB partition, all accesses in bounds: fp32 triad 2^26 (HBM resident); triad repeated inside one launch over working sets resident in L1, L2 and the Infinity Cache (each workgroup re-reads its own 3 KiB); gather 2^24 with int64 indices"}
 
     def sweep(label, kid, kargs, nbytes, reps):
         out = {}
@@ -513,8 +535,20 @@ def run_modes(torch, gd, si, args):
         si.fill_chunked(host, 6, part, "uniform", threads=16)
         dp.upload(0, ptr, host)
     sweep("triad_hbm_2^26", gd.GD_K_TRIAD, gd.gd_args_triad(a, b, c, n, 0.5, 0), 12 * n, args.steps)
-    small, repeat = 1 << 22, 200                                    # 48 MiB working set, swept 200 times per launch
-    sweep("triad_cache_resident_2^22_x200", gd.GD_K_TRIAD, gd.gd_args_triad(a, b, c, small, 0.5, repeat), 12 * small * repeat, args.steps)
+    # Section 7.4 / Fig. 5: what the fence costs when the data sit in a cache.  The triad's repeat field re-runs
+    # the pass inside one launch (no nontemporal hint then); every workgroup re-reads its own 3 KiB, so the grid
+    # decides which cache holds the working set.
+    #   L1: 2048 single-wavefront workgroups, 8 per compute unit = 24 KiB per 32 KiB vector cache
+    #   L2: 24 MiB over 8 XCDs = 3 MiB per 4 MiB L2, 32 workgroups (96 KiB) per compute unit, so L1 misses
+    #   Infinity Cache: 48 MiB
+    regimes = (("triad_L1_resident_2^19_x4000", 1 << 19, 4000, 0), ("triad_L2_resident_2^21_x1000", 1 << 21, 1000, 0),
+               ("triad_infinity_cache_resident_2^22_x200", 1 << 22, 200, 0),
+               # the same L1 regime through pointers that are not 16-byte aligned: 4-byte accesses, each fenced per lane
+               # -- the per-access cost the paper's 8-cycles-against-28 model is about
+               ("triad_L1_resident_per_lane_fence_2^19_x1000", 1 << 19, 1000, 4))
+    for label, small, repeat, shift in regimes:
+        sweep(label, gd.GD_K_TRIAD, gd.gd_args_triad(a + shift, b + shift, c + shift, small, 0.5, repeat), 12 * small * repeat,
+              max(3, args.steps // 4))
     ng = 1 << 24
     idx = dp.alloc(0, 8 * ng)
     dp.upload(0, idx, g.integers(0, n, size=ng, dtype=np.int64))
@@ -545,26 +579,91 @@ def run_modes(torch, gd, si, args):
 
 
 # ---------------------------------------------------------------------------------
-# CPU baseline: the oracle as it stands, one tenant's share of a round
+# CPU baseline: the oracle as it stands (its OpenMP build) on the host cores of this machine
 # ---------------------------------------------------------------------------------
 
 def cpu_baseline(si):
+    """Times the oracle on bounded samples of every configuration's kernels.  `value` is the leg
+    that corresponds to the headline (configuration 3: copy + triad); the others are under `legs`."""
     from oracle import kernels as ok
+    L = ok.lib(openmp=True)
+    cores = int(L.gdo_threads())
+    log(f"[cpu] timing the oracle (plain C, OpenMP build, {cores} threads; os.cpu_count() = {os.cpu_count()})")
+    legs = {}
+
+    def timed(fn):
+        t0 = time.perf_counter()
+        fn()
+        return time.perf_counter() - t0
+
+    def run(sim, row, name, *a):
+        sim.run(name, row, ok.MODE_BITWISE, *a, openmp=True)
+        assert sim.last[0] == 0 and sim.last[1] == 0
+
+    # configuration 3: one tenant's copy + triad at full size (1/8 of a round), seeded scalar
     n = 1 << 28
     base, size = 1 << 40, 16 * GiB
-    log("[cpu] timing the oracle (plain C, 1 thread) on copy + triad, 2^28 elements")
     sim = ok.SimPool(base, 3 * 4 * n, 0)
     a, b, c = base, base + 4 * n, base + 8 * n
     si.fill_chunked(sim.view(b, np.float32, n), 3, 101, "uniform", threads=8)
     si.fill_chunked(sim.view(c, np.float32, n), 3, 201, "uniform", threads=8)
-    t0 = time.perf_counter()
-    sim.run("copy", (base, size), ok.MODE_BITWISE, a, b, n)
-    sim.run("triad", (base, size), ok.MODE_BITWISE, a, b, c, 0.5, n)
-    sec = time.perf_counter() - t0
-    assert sim.last[0] == 0
-    return {"value": (8 + 12) * n / sec / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": "fenced copy + triad of one tenant (2^28 fp32 elements per array): 1/8 of a round",
-            "seconds": sec}
+    s_val = float(si.uniform_f32(si.rng(3, 0), 1)[0])
+    sec = timed(lambda: (run(sim, (base, size), "copy", a, b, n), run(sim, (base, size), "triad", a, b, c, s_val, n)))
+    legs["c3_copy_triad"] = {"value": (8 + 12) * n / sec / 1e9, "unit": "GB/s", "seconds": sec,
+                             "sample": "fenced copy + triad of one tenant, 2^28 fp32 elements per array: 1/8 of a round"}
+    # configuration 5: the sum on the same array
+    sec = timed(lambda: run(sim, (base, size), "sum_f32", a, b, 1 << 27))
+    legs["c5_sum"] = {"value": 4 * (1 << 27) / sec / 1e9, "unit": "GB/s", "seconds": sec, "sample": "fp32 sum of 2^27 values (full size)"}
+    del sim
+
+    # configuration 2: gather then scatter over the full 2^26 table, first 2^25 of the 2^26 indices, in bounds
+    tab_n, m = 1 << 26, 1 << 25
+    base, size = 1 << 40, GiB
+    sim = ok.SimPool(base, size, 0)
+    tab, idx, out = base, base + 4 * tab_n, base + 4 * tab_n + 8 * tab_n
+    si.fill_chunked(sim.view(tab, np.float32, tab_n), 2, 1, "normal", threads=8)
+    sim.view(idx, np.int64, m)[:] = si.rng(2, 0).integers(0, tab_n, size=m, dtype=np.int64)
+    sec_g = timed(lambda: run(sim, (base, size), "gather32_i64", out, tab, idx, m))
+    sec_s = timed(lambda: run(sim, (base, size), "scatter_f32_i64", tab, out, idx, -1.0, m))
+    legs["c2_gather"] = {"value": 16 * m / sec_g / 1e9, "unit": "GB/s", "seconds": sec_g, "sample": "table 2^26, the first 2^25 of 2^26 int64 indices (in bounds)"}
+    legs["c2_scatter"] = {"value": 16 * m / sec_s / 1e9, "unit": "GB/s", "seconds": sec_s, "sample": "same indices, scatter back into the table"}
+    # configuration 5: int32 gather (2^24 indices, full size) on the same table
+    ng = 1 << 24
+    sim.view(idx, np.int32, ng)[:] = si.rng(5, 1).integers(0, ng, size=ng, dtype=np.int64).astype(np.int32)
+    sec = timed(lambda: run(sim, (base, size), "gather32_i32", out, tab, idx, ng))
+    legs["c5_gather_i32"] = {"value": 12 * ng / sec / 1e9, "unit": "GB/s", "seconds": sec, "sample": "2^24 int32 indices over a 2^24 table (full size, in bounds)"}
+    # configuration 5: RMSNorm 4096 x 8192 (full size)
+    rows, cols = 4096, 8192
+    x, y, gain = base, base + 2 * rows * cols, base + 4 * rows * cols
+    g5 = si.rng(5, 2)
+    sim.view(x, np.uint16, rows * cols)[:] = si.f32_to_bf16_bits(si.normal_f32(g5, rows * cols))
+    sim.view(gain, np.uint16, cols)[:] = si.f32_to_bf16_bits(si.uniform_f32(g5, cols, 0.5, 1.5))
+    sec = timed(lambda: run(sim, (base, size), "rmsnorm_bf16", y, x, gain, rows, cols, 1e-6))
+    legs["c5_rmsnorm"] = {"value": 4 * rows * cols / sec / 1e9, "unit": "GB/s", "seconds": sec, "sample": "bf16 4096 x 8192 (full size)"}
+    # configuration 4: a slab of rows of the 8192^3 product with the oracle's triple loop, scaled up; and the
+    # whole product with NumPy's fp64 matmul (a library routine, labelled as such)
+    M = N = K = 8192
+    slab = 64
+    A, B, Cc = base, base + 2 * M * K, base + 4 * M * K
+    g4 = si.rng(4, 3)
+    sim.view(A, np.uint16, slab * K)[:] = si.f32_to_bf16_bits(si.normal_f32(g4, slab * K) * np.float32(K ** -0.5))
+    sim.view(B, np.uint16, N * K)[:] = si.f32_to_bf16_bits(si.normal_f32(g4, N * K))
+    sec = timed(lambda: run(sim, (base, size), "gemm_bf16", Cc, A, B, M, N, K, 1, 0, slab, 0, N))
+    legs["c4_gemm_oracle"] = {"value": 2.0 * slab * N * K / sec / 1e12, "unit": "TFLOP/s", "seconds": sec, "kind": "extrapolated",
+                              "sample": f"rows 0..{slab} of C (1/{M // slab} of the product); the whole product would take {sec * M / slab:.0f} s"}
+    Bf = si.bf16_bits_to_f32(sim.view(B, np.uint16, N * K)).reshape(N, K).astype(np.float64)
+    Af = np.ascontiguousarray(np.tile(si.bf16_bits_to_f32(sim.view(A, np.uint16, slab * K)).reshape(slab, K), (2048 // slab, 1)).astype(np.float64))
+    sec = timed(lambda: Af @ Bf.T)
+    legs["c4_gemm_numpy_fp64"] = {"value": 2.0 * Af.shape[0] * N * K / sec / 1e12, "unit": "TFLOP/s", "seconds": sec, "kind": "library-backed",
+                                  "sample": "NumPy fp64 matmul of a 2048 x 8192 by 8192 x 8192 product (1/4 of the rows)"}
+    del sim, Af, Bf
+    for k, v in legs.items():
+        v["value"] = round(v["value"], 4)
+        v["seconds"] = round(v["seconds"], 3)
+        log(f"[cpu] {k}: {v['value']} {v['unit']} ({v['seconds']} s)")
+    head = legs["c3_copy_triad"]
+    return {"value": head["value"], "unit": "GB/s", "cores": cores, "kind": "oracle", "sample": head["sample"],
+            "seconds": head["seconds"], "host_cpu_count": os.cpu_count(), "legs": legs}
 
 
 def read_traffic():
@@ -615,13 +714,14 @@ def main():
         out["value"] = round(c3["fenced_GBps"], 1)
         out["ms_per_step"] = round(c3["ms_per_round_fenced"], 4)
         tri = c3["solo"]["triad_fenced"]
-        out["roofline"] = {"bound": "hbm", "kernel": "k_stream<V_BIT64, triad>", "achieved": round(tri["GBps"], 1),
+        out["roofline"] = {"bound": "hbm", "kernel": "k_stream<V_BIT64, triad, nontemporal>", "achieved": round(tri["GBps"], 1),
                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(tri["GBps"] / HBM_PEAK_GBPS, 4),
                            "avg_launch_ms": round(tri["avg_launch_ms"], 4), "bytes_per_launch": c3["triad_bytes_per_launch"],
                            "traffic": read_traffic()}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(si)
-    print(json.dumps(out))
+    print(json.dumps(out), flush=True)
+    log(f"[bench] done at {time.time():.3f}")
 
 
 if __name__ == "__main__":

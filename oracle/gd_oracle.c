@@ -5,6 +5,13 @@
  * HIP library.  Plain C, one sequential loop per logical element, floating
  * point in fp64, no blocking, no vectorisation, no threads.
  *
+ * Timing twin.  Compiled with -fopenmp the same file spreads the loops whose
+ * iterations are independent on in-bounds inputs over the host cores (the
+ * `GDO_PARALLEL_FOR` lines); that build exists only so that the benchmark can
+ * report the oracle's speed on all cores.  Every check uses the sequential build:
+ * with out-of-bounds inputs the order of wrapped accesses matters, and the
+ * parallel sum adds in another order.
+ *
  * Model.  Device memory is a byte array `mem` standing for the address range
  * [pool_base, pool_base + pool_bytes).  A kernel is launched for one tenant and
  * sees only that tenant's row of the partition bounds table (Section 4.2.3):
@@ -39,6 +46,20 @@
 #include <stdint.h>
 #include <string.h>
 
+#ifdef _OPENMP
+#include <omp.h>
+#define GDO_PRAGMA(x) _Pragma(#x)
+#define GDO_PARALLEL_FOR GDO_PRAGMA(omp parallel for schedule(static))
+#define GDO_PARALLEL_SUM(v) GDO_PRAGMA(omp parallel for schedule(static) reduction(+ : v))
+#define GDO_COUNT(field) do { GDO_PRAGMA(omp atomic) (field)++; } while (0)
+int gdo_threads(void) { return omp_get_max_threads(); }
+#else
+#define GDO_PARALLEL_FOR
+#define GDO_PARALLEL_SUM(v)
+#define GDO_COUNT(field) ((field)++)
+int gdo_threads(void) { return 1; }
+#endif
+
 typedef struct {
     uint8_t *mem;          /* simulated device memory                          */
     uint64_t pool_base;    /* device address of mem[0]                         */
@@ -71,7 +92,7 @@ static int effective(gdo_ctx *c, uint64_t raw, uint32_t width, uint64_t *eff)
         break;
     case 3:
         if (raw < base || raw + (width - 1) < raw || raw + (width - 1) > base + size - 1) {
-            c->violations++;
+            GDO_COUNT(c->violations);
             return 0;
         }
         *eff = raw;
@@ -79,7 +100,7 @@ static int effective(gdo_ctx *c, uint64_t raw, uint32_t width, uint64_t *eff)
     default:
         *eff = raw;
     }
-    if (*eff != raw) c->wrapped++;
+    if (*eff != raw) GDO_COUNT(c->wrapped);
     return 1;
 }
 
@@ -108,7 +129,7 @@ static int ld(gdo_ctx *c, uint64_t raw, uint32_t width, void *dst)
     memset(dst, 0, width);
     if (!effective(c, raw, width, &a)) return 0;
     if (a < c->pool_base || a - c->pool_base > c->pool_bytes - width || c->pool_bytes < width) {
-        c->escaped++;
+        GDO_COUNT(c->escaped);
         return 1;
     }
     memcpy(dst, c->mem + (a - c->pool_base), width);
@@ -120,7 +141,7 @@ static int st(gdo_ctx *c, uint64_t raw, uint32_t width, const void *src)
     uint64_t a;
     if (!effective(c, raw, width, &a)) return 0;
     if (a < c->pool_base || a - c->pool_base > c->pool_bytes - width || c->pool_bytes < width) {
-        c->escaped++;
+        GDO_COUNT(c->escaped);
         return 1;
     }
     memcpy(c->mem + (a - c->pool_base), src, width);
@@ -188,6 +209,7 @@ void gdo_fence_addrs(gdo_ctx *c, uint64_t out, uint64_t in, uint32_t width, uint
 /* STREAM copy: a[i] = b[i], 4-byte elements moved bit for bit. */
 void gdo_copy(gdo_ctx *c, uint64_t a, uint64_t b, uint64_t n)
 {
+    GDO_PARALLEL_FOR
     for (uint64_t i = 0; i < n; i++) {
         uint32_t v;
         if (!ld(c, b + 4 * i, 4, &v)) continue;
@@ -198,6 +220,7 @@ void gdo_copy(gdo_ctx *c, uint64_t a, uint64_t b, uint64_t n)
 /* STREAM triad: a[i] = b[i] + s * c[i]. */
 void gdo_triad(gdo_ctx *c, uint64_t a, uint64_t b, uint64_t cc, double s, uint64_t n)
 {
+    GDO_PARALLEL_FOR
     for (uint64_t i = 0; i < n; i++) {
         float vb, vc, r;
         if (!ld(c, b + 4 * i, 4, &vb)) continue;
@@ -226,6 +249,7 @@ void gdo_saxpy_idx(gdo_ctx *c, uint64_t x, uint64_t y, uint64_t off, double alph
 /* Gather of 4-byte values with 64-bit indices: out[i] = tab[idx[i]]. */
 void gdo_gather32_i64(gdo_ctx *c, uint64_t out, uint64_t tab, uint64_t idx, uint64_t n)
 {
+    GDO_PARALLEL_FOR
     for (uint64_t i = 0; i < n; i++) {
         uint64_t k;
         uint32_t v;
@@ -238,6 +262,7 @@ void gdo_gather32_i64(gdo_ctx *c, uint64_t out, uint64_t tab, uint64_t idx, uint
 /* Gather of 4-byte values with signed 32-bit indices: out[i] = tab[idx[i]]. */
 void gdo_gather32_i32(gdo_ctx *c, uint64_t out, uint64_t tab, uint64_t idx, uint64_t n)
 {
+    GDO_PARALLEL_FOR
     for (uint64_t i = 0; i < n; i++) {
         int32_t k;
         uint32_t v;
@@ -250,6 +275,7 @@ void gdo_gather32_i32(gdo_ctx *c, uint64_t out, uint64_t tab, uint64_t idx, uint
 /* Scatter of fp32 values with 64-bit indices: dst[idx[i]] = scale * src[i]. */
 void gdo_scatter_f32_i64(gdo_ctx *c, uint64_t dst, uint64_t src, uint64_t idx, double scale, uint64_t n)
 {
+    GDO_PARALLEL_FOR
     for (uint64_t i = 0; i < n; i++) {
         uint64_t k;
         float v, r;
@@ -264,6 +290,7 @@ void gdo_scatter_f32_i64(gdo_ctx *c, uint64_t dst, uint64_t src, uint64_t idx, d
 void gdo_sum_f32(gdo_ctx *c, uint64_t out, uint64_t in, uint64_t n)
 {
     double acc = 0.0;
+    GDO_PARALLEL_SUM(acc)
     for (uint64_t i = 0; i < n; i++) {
         float v;
         if (!ld(c, in + 4 * i, 4, &v)) continue;
@@ -277,6 +304,7 @@ void gdo_sum_f32(gdo_ctx *c, uint64_t out, uint64_t in, uint64_t n)
 double gdo_sum_f32_exact(gdo_ctx *c, uint64_t in, uint64_t n)
 {
     double acc = 0.0;
+    GDO_PARALLEL_SUM(acc)
     for (uint64_t i = 0; i < n; i++) {
         float v;
         if (!ld(c, in + 4 * i, 4, &v)) continue;
@@ -297,6 +325,7 @@ double gdo_sum_f32_exact(gdo_ctx *c, uint64_t in, uint64_t n)
 void gdo_rmsnorm_bf16(gdo_ctx *c, uint64_t y, uint64_t x, uint64_t g,
                       uint64_t rows, uint64_t cols, double eps)
 {
+    GDO_PARALLEL_FOR
     for (uint64_t r = 0; r < rows; r++) {
         double ss = 0.0;
         int row_read = 1;
@@ -335,6 +364,7 @@ void gdo_gemm_bf16(gdo_ctx *c, uint64_t C, uint64_t A, uint64_t B,
                    uint64_t m0, uint64_t m1, uint64_t n0, uint64_t n1)
 {
     (void)M;
+    GDO_PARALLEL_FOR
     for (uint64_t m = m0; m < m1; m++) {
         for (uint64_t n = n0; n < n1; n++) {
             double acc = 0.0;

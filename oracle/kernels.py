@@ -13,17 +13,20 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gd_oracle.c")
 _LIB = os.path.join(_HERE, "libgd_oracle.so")
+_LIB_OMP = os.path.join(_HERE, "libgd_oracle_omp.so")     # the same file with -fopenmp: timing only
 
 MODE_NONE, MODE_BITWISE, MODE_MODULO, MODE_CHECK = 0, 1, 2, 3
 
 
-def build(force=False):
-    """Compile the oracle (plain gcc, -O2, no OpenMP, no fast-math)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+def build(force=False, openmp=False):
+    """Compile the oracle (plain gcc, -O2, no fast-math).  openmp=False: the sequential
+    build every check uses.  openmp=True: its timing twin (see the header of the C file)."""
+    out = _LIB_OMP if openmp else _LIB
+    if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(_SRC):
         subprocess.check_call(
-            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fno-fast-math",
-             "-ffp-contract=off", "-o", _LIB, _SRC, "-lm"])
-    return _LIB
+            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fno-fast-math", "-ffp-contract=off"]
+            + (["-fopenmp"] if openmp else []) + ["-o", out, _SRC, "-lm"])
+    return out
 
 
 class _Ctx(C.Structure):
@@ -33,15 +36,15 @@ class _Ctx(C.Structure):
                 ("escaped", C.c_uint64), ("violations", C.c_uint64), ("wrapped", C.c_uint64)]
 
 
-_lib = None
+_libs = {}
 
 
-def lib():
-    global _lib
-    if _lib is None:
-        L = C.CDLL(build())
+def lib(openmp=False):
+    if openmp not in _libs:
+        L = C.CDLL(build(openmp=openmp))
         u64, u32, i32, dbl, ctx = C.c_uint64, C.c_uint32, C.c_int32, C.c_double, C.POINTER(_Ctx)
         sigs = {
+            "gdo_threads": (C.c_int, []),
             "gdo_fence": (u64, [u64, u64, u64, u32, i32]),
             "gdo_fence_array": (None, [u64, u64, C.c_void_p, u64, u32, i32, C.c_void_p]),
             "gdo_double_to_bf16": (C.c_uint16, [dbl]),
@@ -63,8 +66,8 @@ def lib():
         for name, (res, args) in sigs.items():
             f = getattr(L, name)
             f.restype, f.argtypes = res, args
-        _lib = L
-    return _lib
+        _libs[openmp] = L
+    return _libs[openmp]
 
 
 def fence(base, size, addr, width=1, mode=MODE_BITWISE):
@@ -98,8 +101,8 @@ class SimPool:
         assert 0 <= off and off + count * dtype.itemsize <= self.pool_bytes
         return self.mem[off:off + count * dtype.itemsize].view(dtype)
 
-    def run(self, name, row, mode, *args):
+    def run(self, name, row, mode, *args, openmp=False):
         ctx = _Ctx(self.mem.ctypes.data, self.pool_base, self.pool_bytes, row[0], row[1], mode, 0, 0, 0, 0)
-        res = getattr(lib(), "gdo_" + name)(C.byref(ctx), *args)
+        res = getattr(lib(openmp), "gdo_" + name)(C.byref(ctx), *args)
         self.last = (ctx.escaped, ctx.violations, ctx.wrapped)
         return res if res is not None else self.last

@@ -68,7 +68,9 @@ __global__ __launch_bounds__(1024) void k_fence_addrs(gd_args_fence_addrs p, Fen
 // logical threads stop.
 constexpr int STREAM_TILE = 1024;      // bytes per wavefront and array: 64 lanes x 16 bytes
 
-template <int V, int OP>
+// NT: the vector accesses carry the nontemporal hint (data touched once).  A launch that
+// repeats its pass keeps the hint off, so that the caches may hold its working set.
+template <int V, int OP, bool NT>
 __global__ __launch_bounds__(1024) void k_stream(uint64_t pa, uint64_t pb, uint64_t pc, uint64_t n,
                                                  float s, uint32_t repeat, FenceArgs fa)
 {
@@ -99,15 +101,15 @@ __global__ __launch_bounds__(1024) void k_stream(uint64_t pa, uint64_t pb, uint6
             split |= F.template tile<STREAM_TILE>(pa + 16 * w0, ta);
             if (split == 0) {
                 if (i < n4) {
-                    f32x4 vb = F.template ld_tile16<f32x4, true>(tb, lane_off);
+                    f32x4 vb = F.template ld_tile16<f32x4, NT>(tb, lane_off);
                     if (OP) {
-                        f32x4 vc = F.template ld_tile16<f32x4, true>(tc, lane_off);
+                        f32x4 vc = F.template ld_tile16<f32x4, NT>(tc, lane_off);
                         F.tile_wait(vb, vc);
                         vb = vb + s * vc;
                     } else {
                         F.tile_wait(vb);
                     }
-                    F.template st_tile16<f32x4, true>(ta, lane_off, vb);
+                    F.template st_tile16<f32x4, NT>(ta, lane_off, vb);
                 }
             } else if (i < n4) {
                 uint64_t i = w0 + (threadIdx.x & 63);
@@ -117,9 +119,9 @@ __global__ __launch_bounds__(1024) void k_stream(uint64_t pa, uint64_t pb, uint6
                       F.template inside<16>(pa + 16 * i))) {
                     for (int e = 0; e < 4; ++e) element(4 * i + e);
                 } else {
-                    f32x4 v = F.template ld<f32x4, true>(pb + 16 * i);
-                    if (OP) v = v + s * F.template ld<f32x4, true>(pc + 16 * i);
-                    F.template st<f32x4, true>(pa + 16 * i, v);
+                    f32x4 v = F.template ld<f32x4, NT>(pb + 16 * i);
+                    if (OP) v = v + s * F.template ld<f32x4, NT>(pc + 16 * i);
+                    F.template st<f32x4, NT>(pa + 16 * i, v);
                 }
             }
         }
@@ -180,8 +182,9 @@ static int launch_stream(uint64_t a, uint64_t b, uint64_t c, uint64_t n, float s
     if (!pick_1d(shape, b0 ? stream_tiles(n, b0) : 1, STREAM_BLOCK, &grid, &block)) return GD_EINVAL;
     if (n == 0) return GD_OK;
     const int rc = with_variant(variant, [&](auto v) {
-        hipLaunchKernelGGL((k_stream<decltype(v)::value, OP>), dim3(grid), dim3(block), 0, stream, a, b, c, n, s,
-                           repeat ? repeat : 1u, f);
+        constexpr int V = decltype(v)::value;
+        if (repeat > 1) hipLaunchKernelGGL((k_stream<V, OP, false>), dim3(grid), dim3(block), 0, stream, a, b, c, n, s, repeat, f);
+        else hipLaunchKernelGGL((k_stream<V, OP, true>), dim3(grid), dim3(block), 0, stream, a, b, c, n, s, 1u, f);
     });
     if (rc != GD_OK) return rc;
     GD_CHECK_LAUNCH();

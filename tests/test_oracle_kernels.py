@@ -547,3 +547,40 @@ def test_checking_mode_rmsnorm_row_and_element_refusals():
         diff = np.flatnonzero(pool.mem != want)
         assert diff.size <= 2, diff                                    # summation order: at most a last-bit tie
         assert np.array_equal(pool.mem[size:], before[size:])
+
+
+# ---------------------------------------------------------------------------
+# the OpenMP build (timing only) computes what the sequential build computes
+# ---------------------------------------------------------------------------
+
+def test_openmp_twin_equals_the_sequential_oracle_on_in_bounds_inputs():
+    g = si.rng(0, 10)
+    n, rows, cols, M, N, K = 200003, 33, 256, 40, 24, 64
+    images = []
+    for openmp in (False, True):
+        pool, table = make_pool([4 << 20, 4 << 20], fill=0xA5)
+        row = table[0]
+        g = si.rng(0, 10)
+        p = [row[0] + k * (1 << 20) // 2 * 1 for k in range(8)]        # eight 512 KiB slots
+        pool.view(p[0], np.float32, 100000)[:] = si.uniform_f32(g, 100000)
+        pool.view(p[1], np.float32, 100000)[:] = si.uniform_f32(g, 100000)
+        idx = g.integers(0, 100000, size=60000, dtype=np.int64)
+        pool.view(p[2], np.int64, 60000)[:] = idx
+        run = lambda name, *a: pool.run(name, row, ok.MODE_BITWISE, *a, openmp=openmp)
+        run("triad", p[3], p[0], p[1], 0.3, 100000)
+        run("copy", p[4], p[3], 100000)
+        run("gather32_i64", p[5], p[0], p[2], 60000)
+        pool.view(p[2], np.int64, 60000)[:] = g.permutation(60000)
+        run("scatter_f32_i64", p[6], p[1], p[2], -1.0, 60000)
+        run("sum_f32", p[7], p[0], 100000)
+        xb = si.f32_to_bf16_bits(si.normal_f32(g, rows * cols))
+        pool.view(p[7] + 4096, np.uint16, rows * cols)[:] = xb
+        pool.view(p[7] + 65536, np.uint16, cols)[:] = si.f32_to_bf16_bits(si.uniform_f32(g, cols, 0.5, 1.5))
+        run("rmsnorm_bf16", p[7] + 131072, p[7] + 4096, p[7] + 65536, rows, cols, 1e-6)
+        run("gemm_bf16", p[7] + 262144, p[7] + 4096, p[7] + 4096 + 2 * M * K, M, N, K, 1, 0, M, 0, N)
+        assert pool.last == (0, 0, 0)
+        images.append(pool.mem.copy())
+    diff = np.flatnonzero(images[0] != images[1])
+    # only the sum may differ (another order of additions), and only in its last bits
+    assert diff.size <= 2 and all(0 <= d - (p[7] - pool.pool_base) < 4 for d in diff)
+    assert ok.lib(True).gdo_threads() >= 1 and ok.lib(False).gdo_threads() == 1
