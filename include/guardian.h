@@ -180,6 +180,25 @@ int gd_launch_fenced(gd_pool *pool, int tenant, int kernel_id, const void *args,
                      size_t args_bytes, const uint32_t grid[3], const uint32_t block[3],
                      void *hip_stream, int mode);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the fp32 sum of
+ * GD_K_SUM_F32 without a workspace argument.  The per-workgroup partial sums go
+ * to a file-scope device array of the library (GD_SUM_NOALLOC_SCRATCH bytes, held
+ * by every GPU the library runs on until the process ends) instead of tenant
+ * memory; that array is manager-owned, outside every pool, and its accesses are
+ * not fenced.  `out` and `in` are tenant addresses and are fenced as in
+ * gd_launch_fenced with the same `mode`; the result equals that of GD_K_SUM_F32
+ * bit for bit.  The call allocates nothing and synchronises nothing.  The first
+ * call on a device looks the array's address up (hipGetSymbolAddress): make one
+ * call outside any capture first.  n above GD_SUM_NOALLOC_MAX_N: GD_ESHAPE,
+ * nothing launched.  All calls on one GPU share the one array: calls that can
+ * overlap in time on the same GPU (different streams without an ordering
+ * between them) race on it and must be serialised by the caller. */
+#define GD_SUM_NOALLOC_MAX_N (1ull << 32)   /* elements */
+#define GD_SUM_NOALLOC_SCRATCH 8192u        /* bytes */
+int gd_sum_f32_noalloc(gd_pool *pool, int tenant, uint64_t out, uint64_t in, uint64_t n,
+                       void *hip_stream, int mode);
+
 /* Kernel registry (the analogue of the paper's pointerToSymbol map). */
 int gd_kernel_count(void);
 const char *gd_kernel_name(int kernel_id);         /* NULL if unknown */

@@ -20,6 +20,7 @@ GD_FENCE_NONE, GD_FENCE_BITWISE, GD_FENCE_MODULO, GD_FENCE_CHECK = range(4)
 GD_MIN_PARTITION = 4096
 GD_GRANULE = 256
 GD_SUM_WORKSPACE = 16384
+GD_SUM_NOALLOC_MAX_N = 1 << 32
 
 _u64, _u32, _f32 = C.c_uint64, C.c_uint32, C.c_float
 
@@ -52,6 +53,7 @@ EXPORTS = {
     "gd_check_copy": (C.c_int, [C.c_void_p, C.c_int, _u64, _u64]),
     "gd_launch_fenced": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_size_t,
                                    C.POINTER(_u32), C.POINTER(_u32), C.c_void_p, C.c_int]),
+    "gd_sum_f32_noalloc": (C.c_int, [C.c_void_p, C.c_int, _u64, _u64, _u64, C.c_void_p, C.c_int]),
     "gd_kernel_count": (C.c_int, []),
     "gd_kernel_name": (C.c_char_p, [C.c_int]),
     "gd_kernel_args_bytes": (C.c_size_t, [C.c_int]),
@@ -152,6 +154,10 @@ def gd_launch_fenced(pool, tenant, kernel_id, args, stream=None, mode=GD_FENCE_B
     b = (_u32 * 3)(*block) if block is not None else None
     _ok(lib().gd_launch_fenced(pool, tenant, kernel_id, C.byref(args), C.sizeof(args), g, b,
                                C.c_void_p(stream or 0), mode), "gd_launch_fenced")
+
+
+def gd_sum_f32_noalloc(pool, tenant, out, in_, n, stream=None, mode=GD_FENCE_BITWISE):
+    _ok(lib().gd_sum_f32_noalloc(pool, tenant, out, in_, n, C.c_void_p(stream or 0), mode), "gd_sum_f32_noalloc")
 
 
 def gd_fence_host(base, size, addr, width=1, mode=GD_FENCE_BITWISE):

@@ -181,10 +181,26 @@ static int launch_fenced(gd_pool *pool, int tenant, int kernel_id, const void *a
     return k.launch(copy, extra, variant, shape, static_cast<hipStream_t>(hip_stream));
 }
 
+static int sum_noalloc(gd_pool *pool, int tenant, uint64_t out, uint64_t in, uint64_t n, void *hip_stream, int mode)
+{
+    if (!pool) return GD_EINVAL;
+    if (n > GD_SUM_NOALLOC_MAX_N) return GD_ESHAPE;
+    int variant;
+    gd::FenceArgs extra;
+    const int rc = fence_args_for(pool, tenant, mode, &variant, &extra);
+    if (rc != GD_OK) return rc;
+    return gd::launch_sum_f32_noalloc(out, in, n, extra, variant, static_cast<hipStream_t>(hip_stream));
+}
+
 int gd_launch_fenced(gd_pool *pool, int tenant, int kernel_id, const void *args, size_t args_bytes,
                      const uint32_t grid[3], const uint32_t block[3], void *hip_stream, int mode)
 {
     GD_ABI_GUARD(launch_fenced(pool, tenant, kernel_id, args, args_bytes, grid, block, hip_stream, mode))
+}
+
+int gd_sum_f32_noalloc(gd_pool *pool, int tenant, uint64_t out, uint64_t in, uint64_t n, void *hip_stream, int mode)
+{
+    GD_ABI_GUARD(sum_noalloc(pool, tenant, out, in, n, hip_stream, mode))
 }
 
 const char *gd_strerror(int status)

@@ -5,6 +5,8 @@
 // reductions use cross-lane shuffles, workgroup reductions a few LDS words; LDS
 // is not tenant-addressable and is not fenced.  Every global access, including
 // those to the workspace, carries the fence on its final address.
+#include <mutex>
+
 #include "launchers.hpp"
 
 namespace gd {
@@ -47,7 +49,9 @@ __device__ __forceinline__ T block_sum(T v, T *lds)
 constexpr int SUM_UNROLL = 4;
 constexpr int SUM_TILE = 1024;         // bytes one wavefront covers with one 16-byte vector per lane
 
-template <int V>
+// OWN_WS: `partials` is the library's own device array (not tenant-addressable, like the
+// fault counters), so the accesses to it are not fenced.
+template <int V, bool OWN_WS = false>
 __global__ __launch_bounds__(WG) void k_sum_partial(gd_args_sum p, FenceArgs fa)
 {
     const Fence<V> F(fa);
@@ -118,13 +122,14 @@ __global__ __launch_bounds__(WG) void k_sum_partial(gd_args_sum p, FenceArgs fa)
     // the workspace and the result are tenant memory too; a refused access to them is counted and dropped
     if (threadIdx.x == 0) {
         const uint64_t a = p.partials + 4 * (uint64_t)blockIdx.x;
-        if (F.template inside<4>(a)) F.template st<float>(a, total);
+        if constexpr (OWN_WS) *(GD_GLOBAL float *)a = total;
+        else if (F.template inside<4>(a)) F.template st<float>(a, total);
         else F.fault();
     }
 }
 
 // ---- sum, pass 2: out[0] = sum of the partials (added in fp64) ---------------------
-template <int V>
+template <int V, bool OWN_WS = false>
 __global__ __launch_bounds__(WG) void k_sum_final(gd_args_sum p, uint32_t n_partials, FenceArgs fa)
 {
     const Fence<V> F(fa);
@@ -132,7 +137,8 @@ __global__ __launch_bounds__(WG) void k_sum_final(gd_args_sum p, uint32_t n_part
     double acc = 0.0;
     for (uint32_t i = threadIdx.x; i < n_partials; i += WG) {
         const uint64_t a = p.partials + 4 * (uint64_t)i;
-        if (F.template inside<4>(a)) acc += (double)F.template ld<float>(a);
+        if constexpr (OWN_WS) acc += (double)*(const GD_GLOBAL float *)a;
+        else if (F.template inside<4>(a)) acc += (double)F.template ld<float>(a);
         else F.fault();
     }
     const double total = block_sum(acc, lds);
@@ -269,22 +275,67 @@ static uint32_t sum_blocks(uint64_t n)
     return (uint32_t)(blocks > SUM_MAX_BLOCKS ? SUM_MAX_BLOCKS : blocks);
 }
 
-int launch_sum_f32(const void *args, const FenceArgs &f, int variant, const Shape &shape, hipStream_t stream)
+template <bool OWN_WS>
+static int launch_sum(const gd_args_sum &p, const FenceArgs &f, int variant, hipStream_t stream)
 {
-    const gd_args_sum &p = *(const gd_args_sum *)args;
-    if (shape.grid || shape.block) return GD_EINVAL;
     const uint32_t blocks = sum_blocks(p.n);
     int rc = with_variant(variant, [&](auto v) {
-        hipLaunchKernelGGL((k_sum_partial<decltype(v)::value>), dim3(blocks), dim3(WG), 0, stream, p, f);
+        hipLaunchKernelGGL((k_sum_partial<decltype(v)::value, OWN_WS>), dim3(blocks), dim3(WG), 0, stream, p, f);
     });
     if (rc != GD_OK) return rc;
     GD_CHECK_LAUNCH();
     rc = with_variant(variant, [&](auto v) {
-        hipLaunchKernelGGL((k_sum_final<decltype(v)::value>), dim3(1), dim3(WG), 0, stream, p, blocks, f);
+        hipLaunchKernelGGL((k_sum_final<decltype(v)::value, OWN_WS>), dim3(1), dim3(WG), 0, stream, p, blocks, f);
     });
     if (rc != GD_OK) return rc;
     GD_CHECK_LAUNCH();
     return GD_OK;
+}
+
+int launch_sum_f32(const void *args, const FenceArgs &f, int variant, const Shape &shape, hipStream_t stream)
+{
+    if (shape.grid || shape.block) return GD_EINVAL;
+    return launch_sum<false>(*(const gd_args_sum *)args, f, variant, stream);
+}
+
+// ---- the sum without a workspace argument ---------------------------------------------
+// The partial sums live in this file-scope device array.  Every GPU the library runs on
+// holds its own copy at its own address; in host code the array's name is only a handle
+// for hipGetSymbolAddress, never an address to pass to a kernel.  The address is looked
+// up once per device, with that device current, and kept.  Nothing in the array has to
+// start at zero: pass 1 writes partials[0 .. blocks) before pass 2 reads exactly those.
+static_assert(SUM_MAX_BLOCKS * 4 == GD_SUM_NOALLOC_SCRATCH, "header and kernel disagree on the scratch size");
+static __device__ __align__(256) float scratch[SUM_MAX_BLOCKS];
+
+constexpr int MAX_DEVICES = 64;
+static std::mutex g_scratch_mu;
+static void *g_scratch_ptr[MAX_DEVICES];      // device address of `scratch` per device, null = not looked up yet
+
+int launch_sum_f32_noalloc(uint64_t out, uint64_t in, uint64_t n, const FenceArgs &f, int variant,
+                           hipStream_t stream)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= MAX_DEVICES) {
+        note_hip_error(e != hipSuccess ? e : hipErrorInvalidDevice);
+        return GD_EHIP;
+    }
+    void *ws;
+    {
+        std::lock_guard<std::mutex> g(g_scratch_mu);
+        if (!g_scratch_ptr[dev]) {
+            void *ptr = nullptr;
+            e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !ptr) {
+                note_hip_error(e != hipSuccess ? e : hipErrorInvalidSymbol);
+                return GD_EHIP;
+            }
+            g_scratch_ptr[dev] = ptr;
+        }
+        ws = g_scratch_ptr[dev];
+    }
+    const gd_args_sum p = {out, in, (uint64_t)(uintptr_t)ws, n};
+    return launch_sum<true>(p, f, variant, stream);
 }
 
 int launch_rmsnorm_bf16(const void *args, const FenceArgs &f, int variant, const Shape &shape,

@@ -32,6 +32,10 @@ int launch_sum_f32(const void *, const FenceArgs &, int, const Shape &, hipStrea
 int launch_rmsnorm_bf16(const void *, const FenceArgs &, int, const Shape &, hipStream_t);
 int launch_gemm_bf16(const void *, const FenceArgs &, int, const Shape &, hipStream_t);
 
+// The sum with its partial results in a file-scope device array of the library
+// instead of a tenant workspace (gd_sum_f32_noalloc).
+int launch_sum_f32_noalloc(uint64_t out, uint64_t in, uint64_t n, const FenceArgs &, int variant, hipStream_t);
+
 // 1-D launch shape of an element-wise kernel that loops over `tiles` tiles.
 // Returns false if the caller's shape is unusable.
 inline bool pick_1d(const Shape &s, uint64_t tiles, uint32_t default_block, uint32_t *grid,

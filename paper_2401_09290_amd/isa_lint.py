@@ -19,6 +19,8 @@ the same guarantee is checked after the fact, on the assembly text produced by
 * in both, an access through the scalar tile fence uses an SGPR pair last written
   by the fence's ``s_or_b64`` as its base and a lane offset confined by an AND with a
   constant below 4096 (or zero) as its offset;
+* the sum kernels that keep their partial sums in the library's own device array
+  access that array unfenced (manager memory), and nothing else;
 * per kernel: loads, stores, fence instructions, VGPR/SGPR counts and the
   register delta against the unfenced build of the same kernel.
 
@@ -176,7 +178,8 @@ ZERO_S = re.compile(r"^s_mov_b(32|64)\s+s(\d+|\[\d+:\d+\]),\s*0$")
 
 def lint_kernel(name, pretty, body, variant):
     problems, loads, stores, fences = [], 0, 0, 0
-    tiles = 0
+    tiles = own_ws_seen = 0
+    own_ws = bool(re.search(r"k_sum_\w+<\d, (true|1)>", pretty))
     flow = Flow(body)
     for i, ln in enumerate(body):
         op = ln.strip().split()[0] if ln.strip() else ""
@@ -194,6 +197,9 @@ def lint_kernel(name, pretty, body, variant):
         loads += (not is_store) and not inst.startswith("global_atomic")
         stores += is_store
         if inst in UNFENCED_OK or variant not in (1, 2):
+            continue
+        if own_ws and ((is_store and "k_sum_partial" in pretty) or (not is_store and "k_sum_final" in pretty)):
+            own_ws_seen += 1          # the library's own partial-sum array: manager memory, unfenced by design
             continue
         if inst.startswith("global_load_lds"):
             addr, base = ops[0], ops[1] if len(ops) > 1 else ""
@@ -233,6 +239,8 @@ def lint_kernel(name, pretty, body, variant):
             for d in flow.reaching(i, "v", va[2]):
                 if not FENCE_OR32.match(d):
                     problems.append(f"{pretty}: high word v{va[2]} of `{what}` defined by `{d}`")
+    if own_ws and variant in (1, 2) and own_ws_seen == 0:
+        problems.append(f"{pretty}: expected an access to the library's own partial-sum array")
     return problems, loads, stores, fences
 
 

@@ -15,7 +15,7 @@ def test_every_global_access_of_the_fenced_kernels_is_fenced():
     names = {r[0] for r in rows}
     # all five variants of the element-wise kernels, three fence variants + modulo of the rest
     for v in range(5):
-        assert f"k_stream<{v}, 1, true>" in names and f"k_stream<{v}, 1, false>" in names and f"k_gather32<{v}, 1>" in names and f"k_sum_partial<{v}>" in names
+        assert f"k_stream<{v}, 1, true>" in names and f"k_stream<{v}, 1, false>" in names and f"k_gather32<{v}, 1>" in names and f"k_sum_partial<{v}, false>" in names
         assert f"k_rmsnorm_bf16<{v}>" in names and f"k_gemm_nk256<{v}, true>" in names
     for v in range(4):
         assert f"k_gemm_ring<{v}>" in names
