@@ -37,8 +37,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--configs", default="c3,c4,c2,c1,c5,modes",
-                    help="comma list out of c1..c5 (c3 is the headline) and modes (the paper's three rules side by side)")
+    ap.add_argument("--configs", default="c3,c4,power,c2,c1,c5,modes",
+                    help="comma list out of c1..c5 (c3 is the headline), power (GEMM against the chip's power limit) "
+                         "and modes (the paper's three rules side by side)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--prewarm-ms", type=float, default=250.0,
                     help="untimed launches in front of every measurement until this much GPU time has passed "
@@ -500,6 +501,122 @@ def run_c5(torch, gd, si, args):
 
 
 # ---------------------------------------------------------------------------------
+# the GEMM against the power limit: matrix instructions alone, and the GEMM on zero operands
+# ---------------------------------------------------------------------------------
+
+class PowerSampler:
+    """Socket power (W) and shader clock (MHz) of GPU 0 from the amdgpu hwmon files, sampled by a thread."""
+
+    def __init__(self):
+        import glob
+        def first(pattern):
+            hits = sorted(glob.glob(pattern))
+            return hits[0] if hits else None
+        self.power = first("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input") or \
+            first("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average")
+        self.clock = first("/sys/class/drm/card*/device/hwmon/hwmon*/freq1_input")
+        self.dpm = None if self.clock else first("/sys/class/drm/card*/device/pp_dpm_sclk")   # "1: 1870Mhz *" marks the current level
+
+    @staticmethod
+    def _read(path):
+        try:
+            with open(path) as f:
+                return float(f.read().split()[0])
+        except (OSError, ValueError, IndexError):
+            return None
+
+    def run(self, seconds, skip):
+        """Sample for `seconds`, drop what was read in the first `skip` seconds; returns (watts, MHz) means or None."""
+        t0 = time.perf_counter()
+        watts, mhz = [], []
+        while time.perf_counter() - t0 < seconds:
+            if time.perf_counter() - t0 >= skip:
+                w = self._read(self.power) if self.power else None
+                c = self._read(self.clock) if self.clock else None
+                if w is not None:
+                    watts.append(w * 1e-6)
+                if c is not None:
+                    mhz.append(c * 1e-6)
+                elif self.dpm:
+                    try:
+                        cur = [ln for ln in open(self.dpm).read().splitlines() if ln.rstrip().endswith("*")]
+                        mhz.append(float(cur[0].split(":")[1].lower().replace("mhz", "").replace("*", "").strip()))
+                    except (OSError, ValueError, IndexError):
+                        pass
+            time.sleep(0.01)
+        mean = lambda v: round(sum(v) / len(v), 1) if v else None
+        return mean(watts), mean(mhz)
+
+
+def run_power(torch, gd, si, args):
+    """Is the GEMM held back by the kernel or by the chip's power limit?  Same instrument for five loops of about
+    a second each: the matrix instructions alone (operands in registers) on N(0,1) and on zero data, and the GEMM
+    on N(0,1) (fenced, unfenced) and on zero operands.  Rate from HIP events over the whole loop, power and clock
+    from the driver's hwmon files while it runs."""
+    import threading
+    log("[power] matrix pipe alone vs GEMM, N(0,1) vs zero operands")
+    M = N = K = 8192
+    dp = DevPool(torch, gd, [4 * GiB])
+    A, B, Cc = (dp.alloc(0, 2 * M * K) for _ in range(3))
+    host = np.empty(M * K, np.float32)
+    si.fill_chunked(host, 4, 1, "normal", threads=16)
+    a_bits = si.f32_to_bf16_bits(host * np.float32(K ** -0.5))
+    si.fill_chunked(host, 4, 2, "normal", threads=16)
+    b_bits = si.f32_to_bf16_bits(host)
+    del host
+    st = torch.cuda.Stream()
+    blocks = 1024
+    ops = torch.empty(16 * 256 * 8, dtype=torch.int16, device="cuda")
+    sums = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
+    sampler = PowerSampler()
+    res = {"workload": "8192^3 bf16 GEMM and a loop of its matrix instructions alone (1024 workgroups x 4 wavefronts, operands in registers), ~1 s each",
+           "power_file": sampler.power, "clock_file": sampler.clock or sampler.dpm, "power_cap_note": "hwmon power1_input is the socket power the driver reports"}
+
+    def loop(label, launch, flop_per_launch, seconds=1.2):
+        prewarm(torch, launch)
+        n = 0
+        got = {}
+        th = threading.Thread(target=lambda: got.update(zip(("watts", "mhz"), sampler.run(seconds, 0.3))))
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        th.start()
+        a.record(st)
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < seconds:
+            for _ in range(20):
+                launch()
+            n += 20
+            torch.cuda.synchronize()
+        b.record(st)
+        torch.cuda.synchronize()
+        th.join()
+        tf = flop_per_launch * n / (a.elapsed_time(b) * 1e-3) / 1e12
+        res[label] = {"TFLOPs": round(tf, 1), "socket_watts": got.get("watts"), "shader_MHz": got.get("mhz"),
+                      "frac_of_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4)}
+        log(f"[power] {label}: {tf:.1f} TFLOP/s, {got.get('watts')} W, {got.get('mhz')} MHz")
+
+    iters = 2048
+    probe_flop = blocks * 4 * iters * float(1 << 20)
+    frag = np.concatenate([a_bits[: 8 * 256 * 8], b_bits[: 8 * 256 * 8]])
+    ops.copy_(torch.from_numpy(frag.view(np.int16)))
+    loop("mfma_only_normal_operands", lambda: gd.gd_probe_mfma(ops.data_ptr(), sums.data_ptr(), blocks, iters, stream=st.cuda_stream), probe_flop)
+    ops.zero_()
+    loop("mfma_only_zero_operands", lambda: gd.gd_probe_mfma(ops.data_ptr(), sums.data_ptr(), blocks, iters, stream=st.cuda_stream), probe_flop)
+    kargs = gd.gd_args_gemm(Cc, A, B, M, N, K, 1)
+    flop = 2.0 * M * N * K
+    dp.upload(0, A, a_bits)
+    dp.upload(0, B, b_bits)
+    for name, mode in (("gemm_fenced_normal_operands", gd.GD_FENCE_BITWISE), ("gemm_unfenced_normal_operands", gd.GD_FENCE_NONE)):
+        loop(name, lambda: gd.gd_launch_fenced(dp.pool, 0, gd.GD_K_GEMM_BF16, kargs, stream=st.cuda_stream, mode=mode), flop)
+    dp.view(A, 2 * M * K).zero_()
+    dp.view(B, 2 * M * K).zero_()
+    loop("gemm_fenced_zero_operands", lambda: gd.gd_launch_fenced(dp.pool, 0, gd.GD_K_GEMM_BF16, kargs, stream=st.cuda_stream, mode=gd.GD_FENCE_BITWISE), flop)
+    g, m = res["gemm_fenced_normal_operands"]["TFLOPs"], res["mfma_only_normal_operands"]["TFLOPs"]
+    res["gemm_frac_of_mfma_only_rate_same_data"] = round(g / m, 4) if m else None
+    dp.close()
+    return res
+
+
+# ---------------------------------------------------------------------------------
 # the paper's three bounds-checking rules side by side; cache-resident regime; host path
 # ---------------------------------------------------------------------------------
 
@@ -694,7 +811,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
-    runners = {"c1": run_c1, "c2": run_c2, "c3": run_c3, "c4": run_c4, "c5": run_c5, "modes": run_modes}
+    runners = {"c1": run_c1, "c2": run_c2, "c3": run_c3, "c4": run_c4, "c5": run_c5, "modes": run_modes, "power": run_power}
     wanted = [c.strip() for c in args.configs.split(",") if c.strip()]
     per = {}
     for c in wanted:

@@ -213,6 +213,17 @@ size_t gd_kernel_args_bytes(int kernel_id);        /* 0 if unknown */
  * in mode CHECK, for an access that is not inside. */
 uint64_t gd_fence_host(uint64_t base, uint64_t size, uint64_t addr, uint32_t width, int mode);
 
+/* Measurement aid, not part of the fenced path (no pool, no tenant, no fence): a
+ * kernel that does nothing but the GEMM's matrix instructions (v_mfma_f32_16x16x32_bf16,
+ * 64 per wavefront and iteration, 256 accumulators per lane) on operands it holds in
+ * registers.  Its rate on N(0,1) operands is what the matrix pipe sustains under the
+ * chip's power limit -- the ceiling the GEMM of Section-4-style fenced tile loads is
+ * measured against.  operands: device address of 64 KiB of bfloat16 values (16-byte
+ * aligned; 16 fragments x 256 threads x 8 values); out: device address of blocks*256
+ * floats (a checksum per thread, so that the loop cannot be optimised away).  Both are
+ * caller-owned plain device memory.  flop per launch = blocks * 4 * iters * 2^20. */
+int gd_probe_mfma(uint64_t operands, uint64_t out, uint32_t blocks, uint32_t iters, void *hip_stream);
+
 const char *gd_strerror(int status);
 int gd_last_hip_error(void);   /* hipError_t of the last failed HIP call on this thread */
 

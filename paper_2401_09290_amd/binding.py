@@ -54,6 +54,7 @@ EXPORTS = {
     "gd_launch_fenced": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_size_t,
                                    C.POINTER(_u32), C.POINTER(_u32), C.c_void_p, C.c_int]),
     "gd_sum_f32_noalloc": (C.c_int, [C.c_void_p, C.c_int, _u64, _u64, _u64, C.c_void_p, C.c_int]),
+    "gd_probe_mfma": (C.c_int, [_u64, _u64, _u32, _u32, C.c_void_p]),
     "gd_kernel_count": (C.c_int, []),
     "gd_kernel_name": (C.c_char_p, [C.c_int]),
     "gd_kernel_args_bytes": (C.c_size_t, [C.c_int]),
@@ -158,6 +159,10 @@ def gd_launch_fenced(pool, tenant, kernel_id, args, stream=None, mode=GD_FENCE_B
 
 def gd_sum_f32_noalloc(pool, tenant, out, in_, n, stream=None, mode=GD_FENCE_BITWISE):
     _ok(lib().gd_sum_f32_noalloc(pool, tenant, out, in_, n, C.c_void_p(stream or 0), mode), "gd_sum_f32_noalloc")
+
+
+def gd_probe_mfma(operands, out, blocks, iters, stream=None):
+    _ok(lib().gd_probe_mfma(operands, out, blocks, iters, C.c_void_p(stream or 0)), "gd_probe_mfma")
 
 
 def gd_fence_host(base, size, addr, width=1, mode=GD_FENCE_BITWISE):

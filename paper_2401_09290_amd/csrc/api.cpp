@@ -203,6 +203,11 @@ int gd_sum_f32_noalloc(gd_pool *pool, int tenant, uint64_t out, uint64_t in, uin
     GD_ABI_GUARD(sum_noalloc(pool, tenant, out, in, n, hip_stream, mode))
 }
 
+int gd_probe_mfma(uint64_t operands, uint64_t out, uint32_t blocks, uint32_t iters, void *hip_stream)
+{
+    GD_ABI_GUARD(gd::launch_mfma_probe(operands, out, blocks, iters, static_cast<hipStream_t>(hip_stream)))
+}
+
 const char *gd_strerror(int status)
 {
     switch (status) {

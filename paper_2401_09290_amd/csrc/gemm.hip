@@ -723,6 +723,56 @@ void k_gemm_units(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles
     }
 }
 
+// ---- measurement aid: what the matrix pipe sustains with no data movement at all ---------------
+// The wavefront layout and MFMA order of the ring kernel (8 x 8 tiles of 16x16x32, 256
+// accumulators per lane, one wavefront per SIMD) with both operands held in registers:
+// no LDS, no global traffic inside the loop.  Under the chip's power limit the rate of
+// this loop on N(0,1) operands is the ceiling any GEMM on such data can approach.
+// `operands`: 16 fragments x 256 threads x 16 bytes of bf16 (64 KiB), caller-owned.
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void k_mfma_probe(const u32x4 *operands, float *out, uint32_t iters)
+{
+    bf16x8 fa[RT], fb[RT];
+#pragma unroll
+    for (int i = 0; i < RT; ++i) {
+        fa[i] = __builtin_bit_cast(bf16x8, operands[threadIdx.x + 256 * i]);
+        fb[i] = __builtin_bit_cast(bf16x8, operands[threadIdx.x + 256 * (RT + i)]);
+    }
+    f32x4 acc[RT][RT];
+#pragma unroll
+    for (int i = 0; i < RT; ++i)
+#pragma unroll
+        for (int j = 0; j < RT; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0f;
+    for (uint32_t it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int e = 0; e < RT * RT; ++e)
+            acc[e / RT][e % RT] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[e % RT], fa[e / RT], acc[e / RT][e % RT], 0, 0, 0);
+        const bf16x8 t = fa[0];                 // rotate, so that successive passes multiply other data
+#pragma unroll
+        for (int i = 0; i + 1 < RT; ++i) fa[i] = fa[i + 1];
+        fa[RT - 1] = t;
+    }
+    float sum = 0.0f;
+#pragma unroll
+    for (int i = 0; i < RT; ++i)
+#pragma unroll
+        for (int j = 0; j < RT; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) sum += acc[i][j][r];
+    out[(uint64_t)blockIdx.x * 256 + threadIdx.x] = sum;
+}
+
+int launch_mfma_probe(uint64_t operands, uint64_t out, uint32_t blocks, uint32_t iters, hipStream_t stream)
+{
+    if (!operands || !out || (operands & 15) || (out & 3) || blocks == 0 || blocks > 65536) return GD_EINVAL;
+    hipLaunchKernelGGL(k_mfma_probe, dim3(blocks), dim3(256), 0, stream, (const u32x4 *)(uintptr_t)operands,
+                       (float *)(uintptr_t)out, iters);
+    GD_CHECK_LAUNCH();
+    return GD_OK;
+}
+
 // ---- launcher ---------------------------------------------------------------------------
 
 int launch_gemm_bf16(const void *args, const FenceArgs &f, int variant, const Shape &shape,

@@ -36,6 +36,9 @@ int launch_gemm_bf16(const void *, const FenceArgs &, int, const Shape &, hipStr
 // instead of a tenant workspace (gd_sum_f32_noalloc).
 int launch_sum_f32_noalloc(uint64_t out, uint64_t in, uint64_t n, const FenceArgs &, int variant, hipStream_t);
 
+// Matrix-pipe probe (gd_probe_mfma): no tenant, no fence.
+int launch_mfma_probe(uint64_t operands, uint64_t out, uint32_t blocks, uint32_t iters, hipStream_t);
+
 // 1-D launch shape of an element-wise kernel that loops over `tiles` tiles.
 // Returns false if the caller's shape is unusable.
 inline bool pick_1d(const Shape &s, uint64_t tiles, uint32_t default_block, uint32_t *grid,
