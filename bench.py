@@ -624,14 +624,15 @@ def run_modes(torch, gd, si, args):
     """Section 4.4 / 7.2 ordering (native < bitwise < modulo < checking) and the
     Section 7.4 question (what the fence costs when data sit in cache), on one
     tenant with a 4 GiB partition; Section 7.6's host-side costs per call."""
-    log("[modes] none / bitwise / modulo / checking on one tenant")
-    dp = DevPool(torch, gd, [4 * GiB])
+    log("[modes] none / bitwise / modulo / checking / hardware checking on one tenant")
+    dp = DevPool(torch, gd, [2 * GiB])                 # below 4 GiB: the hardware-checked rule addresses it with 32 bits
     counters = torch.zeros(4, dtype=torch.int64, device="cuda")
     gd.gd_pool_set_fault_counters(dp.pool, counters.data_ptr(), 4)
     st = torch.cuda.Stream()
     g = si.rng(6, 0)
-    modes = (("none", gd.GD_FENCE_NONE), ("bitwise", gd.GD_FENCE_BITWISE), ("modulo", gd.GD_FENCE_MODULO), ("check", gd.GD_FENCE_CHECK))
-    res = {"workload": "1 tenant, 4 GiB partition, all accesses in bounds: fp32 triad 2^26 (HBM resident); triad repeated inside one launch over working sets resident in L1, L2 and the Infinity Cache (each workgroup re-reads its own 3 KiB); gather 2^24 with int64 indices"}
+    modes = (("none", gd.GD_FENCE_NONE), ("bitwise", gd.GD_FENCE_BITWISE), ("modulo", gd.GD_FENCE_MODULO), ("check", gd.GD_FENCE_CHECK),
+             ("hwcheck", gd.GD_FENCE_HWCHECK))
+    res = {"workload": "1 tenant, 2 GiB partition, all accesses in bounds: fp32 triad 2^26 (HBM resident); triad repeated inside one launch over working sets resident in L1, L2 and the Infinity Cache (each workgroup re-reads its own 3 KiB); gather 2^24 with int64 indices"}
 
     def sweep(label, kid, kargs, nbytes, reps):
         out = {}

@@ -52,10 +52,16 @@ typedef enum {
     GD_FENCE_NONE = 0,     /* native kernel: tenant runs alone, protection off (Section 4.2.3) */
     GD_FENCE_BITWISE = 1,  /* AND with mask, OR with base (Listing 1); needs size-aligned pow2 partitions */
     GD_FENCE_MODULO = 2,   /* base + (addr - base) % size (Section 4.4); any size, any alignment */
-    GD_FENCE_CHECK = 3     /* compare against base/end; an offending logical thread stops and is counted
+    GD_FENCE_CHECK = 3,    /* compare against base/end; an offending logical thread stops and is counted
                               (Sections 4.3, 4.4).  A logical thread is the computation of one output
                               element: in RMSNorm and GEMM it reads a whole operand row (and column), so
                               an operand row that is not wholly inside stops every thread that needs it */
+    GD_FENCE_HWCHECK = 4   /* address checking by the memory pipeline (an addition: the GPU's buffer
+                              instructions compare every access with the partition's size, Section 4.4's
+                              conditional check without instructions): offset = lo32(addr - base) with
+                              the low log2(width) bits cleared; an access outside reads 0 / is dropped,
+                              the thread goes on, nothing is counted.  Partitions below 4 GiB, any size
+                              and alignment (GD_ESHAPE otherwise) */
 } gd_fence_mode;
 
 /* ---- pool and partition bounds table (Section 4.2.1) ---------------------- */
@@ -210,7 +216,7 @@ size_t gd_kernel_args_bytes(int kernel_id);        /* 0 if unknown */
  * the address a `width`-byte access (1, 2, 4, 8 or 16) to addr is redirected to.
  * For BITWISE the low log2(width) bits are cleared as well, so that the whole
  * access lies inside the partition.  Returns UINT64_MAX for bad arguments or,
- * in mode CHECK, for an access that is not inside. */
+ * in mode CHECK or HWCHECK, for an access that is not inside. */
 uint64_t gd_fence_host(uint64_t base, uint64_t size, uint64_t addr, uint32_t width, int mode);
 
 /* Measurement aid, not part of the fenced path (no pool, no tenant, no fence): a

@@ -33,6 +33,11 @@
  *   3  check     Section 4.4: the access proceeds only if it lies inside the
  *                partition; otherwise the logical thread stops (Section 4.3,
  *                last sentence) and the violation is counted
+ *   4  hwcheck   address checking as a GPU's buffer addressing does it (this
+ *                build's addition to Section 4.4's list): the access goes to
+ *                base + off with off = (addr - base) mod 2^32, low log2(width)
+ *                bits cleared, if off + width <= size; otherwise a load reads 0
+ *                and a store is dropped, and the thread goes on
  *
  * An access that leaves the simulated pool altogether (possible only in mode 0)
  * is dropped and counted in `escaped`: on a real GPU it would be a fault.
@@ -97,6 +102,15 @@ static int effective(gdo_ctx *c, uint64_t raw, uint32_t width, uint64_t *eff)
         }
         *eff = raw;
         break;
+    case 4: {
+        uint64_t off = ((raw - base) & 0xffffffffu) & ~(uint64_t)(width - 1);
+        if (off + width > size) {
+            GDO_COUNT(c->violations);
+            return 0;
+        }
+        *eff = base + off;
+        break;
+    }
     default:
         *eff = raw;
     }
@@ -122,12 +136,13 @@ void gdo_fence_array(uint64_t base, uint64_t size, const uint64_t *addr, uint64_
 
 /* ---- memory accesses ------------------------------------------------------ */
 
-/* 1 = done, 0 = the logical thread must stop (mode 3). A dropped access reads 0. */
+/* 1 = done, 0 = the logical thread must stop (mode 3).  A refused access reads 0;
+ * in mode 4 the thread goes on with that value. */
 static int ld(gdo_ctx *c, uint64_t raw, uint32_t width, void *dst)
 {
     uint64_t a;
     memset(dst, 0, width);
-    if (!effective(c, raw, width, &a)) return 0;
+    if (!effective(c, raw, width, &a)) return c->mode == 4;
     if (a < c->pool_base || a - c->pool_base > c->pool_bytes - width || c->pool_bytes < width) {
         GDO_COUNT(c->escaped);
         return 1;
@@ -139,7 +154,7 @@ static int ld(gdo_ctx *c, uint64_t raw, uint32_t width, void *dst)
 static int st(gdo_ctx *c, uint64_t raw, uint32_t width, const void *src)
 {
     uint64_t a;
-    if (!effective(c, raw, width, &a)) return 0;
+    if (!effective(c, raw, width, &a)) return c->mode == 4;      /* mode 4: dropped, the thread goes on */
     if (a < c->pool_base || a - c->pool_base > c->pool_bytes - width || c->pool_bytes < width) {
         GDO_COUNT(c->escaped);
         return 1;

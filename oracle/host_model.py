@@ -136,6 +136,17 @@ def check_access(addr, base, size, width=1):
     return base <= addr and addr + width - 1 <= partition_end(base, size)
 
 
+def fence_hwcheck(addr, base, size, width=1):
+    """Address checking as a GPU's buffer addressing performs it (this build's addition to
+    Section 4.4's list of rules): the access is made at a 32-bit offset from the partition
+    base, ``(addr - base) mod 2^32`` with the low bits of the width cleared, and refused
+    (``None``) unless the whole access lies below the partition size.  Every access that is
+    made lies inside the partition; addresses 4 GiB apart are not told apart."""
+    assert width in ACCESS_WIDTHS and size < (1 << 32)
+    off = ((addr - base) & 0xFFFFFFFF) & ~(width - 1)
+    return base + off if off + width <= size else None
+
+
 # ---------------------------------------------------------------------------
 # Transfer range check (Section 4.2.2)
 # ---------------------------------------------------------------------------

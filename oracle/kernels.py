@@ -15,7 +15,7 @@ _SRC = os.path.join(_HERE, "gd_oracle.c")
 _LIB = os.path.join(_HERE, "libgd_oracle.so")
 _LIB_OMP = os.path.join(_HERE, "libgd_oracle_omp.so")     # the same file with -fopenmp: timing only
 
-MODE_NONE, MODE_BITWISE, MODE_MODULO, MODE_CHECK = 0, 1, 2, 3
+MODE_NONE, MODE_BITWISE, MODE_MODULO, MODE_CHECK, MODE_HWCHECK = 0, 1, 2, 3, 4
 
 
 def build(force=False, openmp=False):

@@ -13,7 +13,7 @@ LIB_PATH = os.path.join(_HERE, "libguardian.so")
 # ---- constants (mirror include/guardian.h) ----------------------------------------
 GD_OK, GD_EINVAL, GD_ENOTPOW2, GD_ENOMEM, GD_ERANGE, GD_ENOTENANT, GD_EBUSY, GD_EHIP, \
     GD_ENOKERNEL, GD_ESHAPE = range(10)
-GD_FENCE_NONE, GD_FENCE_BITWISE, GD_FENCE_MODULO, GD_FENCE_CHECK = range(4)
+GD_FENCE_NONE, GD_FENCE_BITWISE, GD_FENCE_MODULO, GD_FENCE_CHECK, GD_FENCE_HWCHECK = range(5)
 (GD_K_STORE_TID, GD_K_FENCE_ADDRS, GD_K_COPY, GD_K_TRIAD, GD_K_SAXPY_IDX, GD_K_GATHER32_I64,
  GD_K_SCATTER_F32_I64, GD_K_GATHER32_I32, GD_K_SUM_F32, GD_K_RMSNORM_BF16, GD_K_GEMM_BF16,
  GD_K_COUNT) = range(12)

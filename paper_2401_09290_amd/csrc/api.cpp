@@ -156,6 +156,12 @@ static int fence_args_for(gd_pool *pool, int tenant, int mode, int *variant, gd:
         extra->mask = size;
         extra->faults = row.fault_counters;
         return GD_OK;
+    case GD_FENCE_HWCHECK:
+        // the descriptor's num_records is a 32-bit byte count
+        if (size > 0xffffffffull) return GD_ESHAPE;
+        *variant = gd::V_BUF;
+        extra->mask = size;
+        return GD_OK;
     default:
         return GD_ENOKERNEL;
     }

@@ -22,6 +22,14 @@
 //   V_CHECK  Section 4.4's address checking: the access proceeds unchanged if it
 //            lies inside [base, base+size), otherwise the logical thread stops and
 //            the tenant's fault counter (manager-owned memory) is incremented.
+//   V_BUF    address checking done by the memory pipeline: every access is a buffer
+//            instruction through a descriptor {base, num_records = size} of the
+//            tenant's partition (below 4 GiB), with the 32-bit offset
+//            lo32(addr - base), low log2(W) bits cleared.  The hardware compares
+//            offset + W with num_records: an access outside returns 0 (load) or is
+//            dropped (store); nothing is counted and no thread stops.  Addresses
+//            4 GiB apart share an offset, so this rule confines (every access lands
+//            in the partition or nowhere) but does not detect every stray address.
 //
 // Width rule: an access of W bytes also clears the low log2(W) address bits, so
 // the whole access lies inside the partition (for naturally aligned addresses
@@ -44,7 +52,7 @@
 
 namespace gd {
 
-enum Variant : int { V_NONE = 0, V_BIT32 = 1, V_BIT64 = 2, V_MOD = 3, V_CHECK = 4, V_COUNT = 5 };
+enum Variant : int { V_NONE = 0, V_BIT32 = 1, V_BIT64 = 2, V_MOD = 3, V_CHECK = 4, V_BUF = 5, V_COUNT = 6 };
 
 // The extra kernel parameters.  Listing 1's two (base, mask) are all the bitwise
 // fence uses; the other rules of Section 4.4 reuse `mask` for the partition size
@@ -116,6 +124,9 @@ struct Fence {
     {
         if constexpr (V == V_NONE || V == V_CHECK) {
             return raw;
+        } else if constexpr (V == V_BUF) {
+            const uint64_t off = buf_offset<W>(raw);
+            return off + W <= mask ? base + off : ~(uint64_t)0;        // mask holds the size
         } else if constexpr (V == V_MOD) {
             // n mod d for any 64-bit n (Granlund-Montgomery division by an invariant):
             // q = (t + ((n - t) >> 1)) >> (shift - 1) with t = mulhi(magic, n).
@@ -154,6 +165,9 @@ struct Fence {
         if constexpr (V == V_NONE) {
             fenced = start;
             return 0;
+        } else if constexpr (V == V_BUF) {
+            fenced = buf_offset<16>(start);          // offsets wrap at 2^32 by definition: a tile is never split
+            return 0;
         } else if constexpr (V == V_CHECK) {
             fenced = start;
             return !inside<TILE>(start);
@@ -187,6 +201,7 @@ struct Fence {
     __device__ __forceinline__ T ld_tile16(uint64_t fenced, uint32_t lane_off) const
     {
         static_assert(sizeof(T) == 16, "one 16-byte vector per lane");
+        if constexpr (V == V_BUF) return buf_load<T, STREAM>((uint32_t)fenced + lane_off);
         T v;
         if constexpr (STREAM) asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "=v"(v) : "v"(lane_off), "s"(fenced) : "memory");
         else asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(v) : "v"(lane_off), "s"(fenced) : "memory");
@@ -197,6 +212,10 @@ struct Fence {
     __device__ __forceinline__ void st_tile16(uint64_t fenced, uint32_t lane_off, T v) const
     {
         static_assert(sizeof(T) == 16, "one 16-byte vector per lane");
+        if constexpr (V == V_BUF) {
+            buf_store<T, STREAM>((uint32_t)fenced + lane_off, v);
+            return;
+        }
         if constexpr (STREAM) asm volatile("global_store_dwordx4 %0, %1, %2 nt" : : "v"(lane_off), "v"(v), "s"(fenced) : "memory");
         else asm volatile("global_store_dwordx4 %0, %1, %2" : : "v"(lane_off), "v"(v), "s"(fenced) : "memory");
     }
@@ -214,11 +233,50 @@ struct Fence {
         asm volatile("s_waitcnt vmcnt(0)" : "+v"(a), "+v"(b) : : "memory");
     }
 
+    // ---- V_BUF: the partition as a raw buffer --------------------------------------------
+    // Descriptor words: base (48 bits), stride 0, num_records = size in bytes, and the
+    // gfx9-family data-format word for untyped accesses.  Wave-uniform: built on the
+    // scalar unit, once.
+    __device__ __forceinline__ __amdgpu_buffer_rsrc_t descriptor() const
+    {
+        return __builtin_amdgcn_make_buffer_rsrc((void *)(uintptr_t)base, 0, (uint32_t)mask, 0x00020000);
+    }
+    template <int W>
+    __device__ __forceinline__ uint32_t buf_offset(uint64_t raw) const
+    {
+        return ((uint32_t)raw - (uint32_t)base) & ~(uint32_t)(W - 1);
+    }
+    template <typename T, bool STREAM>
+    __device__ __forceinline__ T buf_load(uint32_t off) const
+    {
+        constexpr int AUX = STREAM ? 2 : 0;                    // bit 1: nontemporal
+        const __amdgpu_buffer_rsrc_t r = descriptor();
+        if constexpr (sizeof(T) == 1) return __builtin_bit_cast(T, (uint8_t)__builtin_amdgcn_raw_buffer_load_b8(r, off, 0, AUX));
+        else if constexpr (sizeof(T) == 2) return __builtin_bit_cast(T, (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(r, off, 0, AUX));
+        else if constexpr (sizeof(T) == 4) return __builtin_bit_cast(T, (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(r, off, 0, AUX));
+        else if constexpr (sizeof(T) == 8) return __builtin_bit_cast(T, __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, AUX));
+        else return __builtin_bit_cast(T, __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, AUX));
+    }
+    template <typename T, bool STREAM>
+    __device__ __forceinline__ void buf_store(uint32_t off, T v) const
+    {
+        constexpr int AUX = STREAM ? 2 : 0;
+        typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+        typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+        const __amdgpu_buffer_rsrc_t r = descriptor();
+        if constexpr (sizeof(T) == 1) __builtin_amdgcn_raw_buffer_store_b8(__builtin_bit_cast(uint8_t, v), r, off, 0, AUX);
+        else if constexpr (sizeof(T) == 2) __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(uint16_t, v), r, off, 0, AUX);
+        else if constexpr (sizeof(T) == 4) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, v), r, off, 0, AUX);
+        else if constexpr (sizeof(T) == 8) __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2_t, v), r, off, 0, AUX);
+        else __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v), r, off, 0, AUX);
+    }
+
     // STREAM = true marks data that is touched once (contiguous streams): the access
     // carries the nontemporal hint so that it does not displace reusable lines.
     template <typename T, bool STREAM = false>
     __device__ __forceinline__ T ld(uint64_t raw) const
     {
+        if constexpr (V == V_BUF) return buf_load<T, STREAM>(buf_offset<sizeof(T)>(raw));
         const GD_GLOBAL T *ptr;
         if constexpr (V == V_BIT32) {
             const uint32_t m = (uint32_t)mask & ~(uint32_t)(sizeof(T) - 1);
@@ -307,6 +365,10 @@ struct Fence {
     template <typename T, bool STREAM = false>
     __device__ __forceinline__ void st(uint64_t raw, T v) const
     {
+        if constexpr (V == V_BUF) {
+            buf_store<T, STREAM>(buf_offset<sizeof(T)>(raw), v);
+            return;
+        }
         GD_GLOBAL T *ptr;
         if constexpr (V == V_BIT32) {
             const uint32_t m = (uint32_t)mask & ~(uint32_t)(sizeof(T) - 1);

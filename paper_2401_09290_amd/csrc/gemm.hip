@@ -197,10 +197,13 @@ void k_gemm_nk256(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
+            for (int r = 0; r < 16; r += 2) {                 // rows r and r + 1 of the same column: one packed conversion
+                const f32x2 two = {acc[i][j][r], acc[i][j][r + 1]};
+                const uint32_t w = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2));
                 const uint32_t row = 32 * i + 8 * (r / 4) + 4 * fhalf + (r & 3);
                 const uint32_t col = 32 * j + frow;
-                *(uint16_t *)(park + row * 256 + col * 2) = (uint16_t)gemm_f32_to_bf16(acc[i][j][r]);
+                *(uint16_t *)(park + row * 256 + col * 2) = (uint16_t)w;
+                *(uint16_t *)(park + (row + 1) * 256 + col * 2) = (uint16_t)(w >> 16);
             }
     __syncthreads();
     const uint32_t orow = lane >> 4, og = lane & 15;
@@ -754,14 +757,12 @@ void k_mfma_probe(const u32x4 *operands, float *out, uint32_t iters)
         for (int i = 0; i + 1 < RT; ++i) fa[i] = fa[i + 1];
         fa[RT - 1] = t;
     }
-    float sum = 0.0f;
+    // every accumulator is "used" (so that no MFMA chain is dead code) without arithmetic on all 256
 #pragma unroll
     for (int i = 0; i < RT; ++i)
 #pragma unroll
-        for (int j = 0; j < RT; ++j)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) sum += acc[i][j][r];
-    out[(uint64_t)blockIdx.x * 256 + threadIdx.x] = sum;
+        for (int j = 0; j < RT; ++j) asm volatile("" : : "v"(acc[i][j]));
+    out[(uint64_t)blockIdx.x * 256 + threadIdx.x] = acc[0][0][0] + acc[RT - 1][RT - 1][3];
 }
 
 int launch_mfma_probe(uint64_t operands, uint64_t out, uint32_t blocks, uint32_t iters, hipStream_t stream)
@@ -793,10 +794,11 @@ int launch_gemm_bf16(const void *args, const FenceArgs &f, int variant, const Sh
         const dim3 grid((uint32_t)tiles), block(256);
         rc = with_variant(variant, [&](auto v) {
             constexpr int V = decltype(v)::value;
-            // address checking needs predicated loads: the register-staged kernel has them
-            if (V == V_CHECK || edge) {
+            // address checking needs predicated loads, and the hardware-checked rule buffer
+            // instructions: the register-staged kernel has both
+            if (V == V_CHECK || V == V_BUF || edge) {
                 hipLaunchKernelGGL((k_gemm_nk256<V, true>), grid, block, 0, stream, p, f, tiles_m, tiles_n);
-            } else if constexpr (V != V_CHECK) {
+            } else if constexpr (V != V_CHECK && V != V_BUF) {
                 if (ring) hipLaunchKernelGGL((k_gemm_ring<V>), grid, block, 0, stream, p, f, tiles_m, tiles_n);
                 else hipLaunchKernelGGL((k_gemm_units<V>), grid, block, 0, stream, p, f, tiles_m, tiles_n);
             }

@@ -72,6 +72,7 @@ inline int with_variant(int variant, F &&launch)
     case V_BIT64: launch(std::integral_constant<int, V_BIT64>{}); return GD_OK;
     case V_MOD:   launch(std::integral_constant<int, V_MOD>{});   return GD_OK;
     case V_CHECK: launch(std::integral_constant<int, V_CHECK>{}); return GD_OK;
+    case V_BUF:   launch(std::integral_constant<int, V_BUF>{});   return GD_OK;
     default: return GD_ENOKERNEL;
     }
 }

@@ -247,6 +247,11 @@ uint64_t fence_host(uint64_t base, uint64_t size, uint64_t addr, uint32_t width,
         if (addr < base || last < addr || last > base + (size - 1)) return bad;
         return addr;
     }
+    case GD_FENCE_HWCHECK: {
+        if (size > 0xffffffffull) return bad;
+        const uint64_t off = ((addr - base) & 0xffffffffull) & ~uint64_t(width - 1);
+        return off + width <= size ? base + off : bad;
+    }
     default:
         return bad;
     }

@@ -7,8 +7,8 @@ registers the fence costs (Section 7.3).  Here the kernels are written fenced, s
 the same guarantee is checked after the fact, on the assembly text produced by
 ``hipcc -S`` for each source file:
 
-* no kernel uses flat_* accesses, indirect branches (s_setpc / s_swappc) or --
-  outside the GEMM, which may spill a few registers to scratch -- scratch memory;
+* no kernel uses flat_* accesses, indirect branches (s_setpc / s_swappc) or scratch
+  memory;
 * in every kernel built with the 32-bit fence (variant 1) each global_load,
   global_store, global_atomic and global_load_lds addresses memory as
   "SGPR base + 32-bit VGPR offset", and the instruction that last wrote that
@@ -19,6 +19,9 @@ the same guarantee is checked after the fact, on the assembly text produced by
 * in both, an access through the scalar tile fence uses an SGPR pair last written
   by the fence's ``s_or_b64`` as its base and a lane offset confined by an AND with a
   constant below 4096 (or zero) as its offset;
+* in every kernel built for the hardware-checked rule (variant 5) all accesses to tenant
+  memory are buffer instructions with a VGPR offset and a zero SGPR offset (the range
+  check covers exactly that offset), and there is no global_* access;
 * the sum kernels that keep their partial sums in the library's own device array
   access that array unfenced (manager memory), and nothing else;
 * per kernel: loads, stores, fence instructions, VGPR/SGPR counts and the
@@ -39,6 +42,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-featu
          "-S", "--cuda-device-only", "-Wno-unused-command-line-argument"]
 
 MEM_RE = re.compile(r"^\s*(global_load_lds_\w+|global_load_\w+|global_store_\w+|global_atomic_\w+)\s+(.*)$")
+BUF_RE = re.compile(r"^\s*(buffer_load_\w+|buffer_store_\w+)\s+(.*)$")
 LABEL_RE = re.compile(r"^(\.L\w+):$")
 # the counters the checking variant bumps live in manager-owned memory and are not fenced by design
 UNFENCED_OK = ("global_atomic_add_x2",)
@@ -189,6 +193,14 @@ def lint_kernel(name, pretty, body, variant):
             problems.append(f"{pretty}: indirect branch: {ln.strip()}")
         if FENCE_AND32.match(ln.strip()) or TILE_OR64.match(ln.strip()):
             fences += 1
+        if variant == 5 and BUF_RE.match(ln):
+            is_st = "store" in ln.split()[0]
+            loads += not is_st
+            stores += is_st
+            fences += 1                                   # the descriptor's range check is the fence
+            if not re.search(r"\boffen\b", ln) or re.search(r",\s*s\d+\s+offen", ln):
+                problems.append(f"{pretty}: buffer access without a VGPR offset or with an SGPR offset: {ln.strip()}")
+            continue
         m = MEM_RE.match(ln)
         if not m:
             continue
@@ -196,6 +208,8 @@ def lint_kernel(name, pretty, body, variant):
         is_store = inst.startswith("global_store")
         loads += (not is_store) and not inst.startswith("global_atomic")
         stores += is_store
+        if variant == 5 and inst not in UNFENCED_OK and not own_ws:
+            problems.append(f"{pretty}: hardware-checked rule but a global access: {ln.strip()}")
         if inst in UNFENCED_OK or variant not in (1, 2):
             continue
         if own_ws and ((is_store and "k_sum_partial" in pretty) or (not is_store and "k_sum_final" in pretty)):
@@ -261,7 +275,7 @@ def run(verbose=True):
                 variant = int(v.group(1)) if v else -1
                 pr, ld, st, fc = lint_kernel(n, p, bodies[n], variant)
                 md = meta.get(n, {})
-                if md.get("scratch", 0) > 0 and "gemm" not in p:
+                if md.get("scratch", 0) > 0:
                     pr.append(f"{p}: uses {md['scratch']} bytes of scratch")
                 problems += pr
                 rows.append((p, variant, ld, st, fc, md.get("vgpr", -1), md.get("sgpr", -1), md.get("scratch", -1)))

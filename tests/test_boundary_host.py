@@ -215,6 +215,12 @@ def test_host_fence_equals_oracle_on_tiny_pool_and_random_addresses(width):
         ok = hm.check_access(a, b, s, width)
         assert gd.gd_fence_host(b, s, a, width, gd.GD_FENCE_CHECK) == (a if ok else hm.U64)
         assert gd.gd_fence_host(b, s, a, width, gd.GD_FENCE_NONE) == a
+        if s < (1 << 32):
+            assert gd.gd_fence_host(b, s, a, width, gd.GD_FENCE_HWCHECK) == (hm.fence_hwcheck(a, b, s, width) or hm.U64)
+            near = b + rnd.randint(-2 * s, 3 * s)
+            assert gd.gd_fence_host(b, s, near, width, gd.GD_FENCE_HWCHECK) == (hm.fence_hwcheck(near, b, s, width) or hm.U64)
+        else:
+            assert gd.gd_fence_host(b, s, a, width, gd.GD_FENCE_HWCHECK) == hm.U64     # the rule needs a size below 4 GiB
     assert gd.gd_fence_host(4096 + 256, 4096, 0, 4) == hm.U64           # base not size-aligned
     assert gd.gd_fence_host(4096, 4096, 0, 3) == hm.U64                 # not an access width
 
@@ -292,4 +298,10 @@ def test_launch_argument_errors_need_no_gpu():
     with pytest.raises(gd.GuardianError) as e:
         gd.gd_launch_fenced(pool, 0, gd.GD_K_COPY, args, mode=17)
     assert e.value.status == gd.GD_ENOKERNEL
+    gd.gd_pool_destroy(pool)
+    # the hardware-checked rule addresses a partition through a 32-bit byte count: 4 GiB and more are refused
+    pool = gd.gd_pool_create(1 << 40, 1 << 33, [1 << 32, 1 << 31])
+    with pytest.raises(gd.GuardianError) as e:
+        gd.gd_launch_fenced(pool, 0, gd.GD_K_COPY, gd.gd_args_copy(1 << 40, (1 << 40) + 4096, 16), mode=gd.GD_FENCE_HWCHECK)
+    assert e.value.status == gd.GD_ESHAPE
     gd.gd_pool_destroy(pool)

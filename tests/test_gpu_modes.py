@@ -368,3 +368,146 @@ def test_checking_gemm_stops_threads_with_a_refused_operand_row_or_column(checke
         for p in (A_in, B_in, C_in):
             r.free(t, p)
     assert total > 0 and faults(counters, 0) == 0
+
+
+# ---------------------------------------------------------------------------
+# address checking by the memory pipeline (buffer instructions)
+# ---------------------------------------------------------------------------
+
+def images_close_bf16(r, what, budget):
+    """Whole pool image against the oracle's: bytes equal, except bf16 outputs that differ by one unit."""
+    torch.cuda.synchronize()
+    got, want = r.dev.cpu().numpy(), r.sim.mem
+    changed = got != want
+    if changed.any():
+        pos = np.unique(np.flatnonzero(changed) // 2 * 2)
+        gb = got[pos].astype(np.uint16) | (got[pos + 1].astype(np.uint16) << 8)
+        wb = want[pos].astype(np.uint16) | (want[pos + 1].astype(np.uint16) << 8)
+        assert_bf16_close(gb, wb, abs_tol=3e-5, flip_budget=1.0, frobenius=False, what=what)
+        assert pos.size <= budget, (what, pos.size)
+
+
+def test_hwcheck_on_odd_sized_partitions_matches_the_oracle():
+    sizes = [3 * MiB + 256, 5 * MiB + 768, MiB + 256 * 17]
+    r = FlexRig(sizes)
+    try:
+        g = si.rng(6, 95)
+        mode, omode = gd.GD_FENCE_HWCHECK, ok.MODE_HWCHECK
+        for t, (base, size) in enumerate(r.table):
+            end = base + size
+            n = 20001
+            raw = random_addresses(g, n, base, size)
+            raw[n // 2: n // 2 + 2000] = np.uint64(base) + g.integers(0, size, size=2000, dtype=np.uint64) + np.uint64(3 << 32)
+            src, dst = r.alloc(t, 8 * n), r.alloc(t, 8 * n)
+            r.upload(t, src, raw)
+            for width in (1, 2, 4, 8, 16):
+                gd.gd_launch_fenced(r.pool, t, gd.GD_K_FENCE_ADDRS, gd.gd_args_fence_addrs(dst, src, n, width, 0), mode=mode)
+                r.sim.run("fence_addrs", (base, size), omode, dst, src, width, n)
+                got = r.download(dst, np.uint64, n)
+                want = ok.fence_array(base, size, raw, width, omode)
+                assert np.array_equal(got, want)
+                made = got != np.uint64(hm.U64)
+                assert made.any() and (~made).any()
+                assert got[made].min() >= base and got[made].max() + width <= end
+            # a store loop that starts in front of the partition and runs past its end: only the part inside is written
+            gd.gd_launch_fenced(r.pool, t, gd.GD_K_STORE_TID, gd.gd_args_store_tid(base - 1000 * 4, size // 4 + 3000, 40 + t, 0), mode=mode)
+            r.sim.run("store_tid", (base, size), omode, base - 1000 * 4, 40 + t, size // 4 + 3000)
+            assert r.sim.last[1] == 3000 and r.images_equal(), f"tenant {t}"
+        t = 1
+        base, size = r.table[t]
+        end = base + size
+        n = 100003
+        r.upload(t, base, si.uniform_f32(g, 50003))
+        for shift in (0, 4):                                     # 16-byte aligned: the tile path; misaligned: per element
+            a = end - 4 * 30000 + shift                          # the last 70003 stores fall outside
+            b = base + 512 * KiB + shift
+            c = base - 4 * 50000 + (shift and 12)                # the first 50000 loads of c lie in front of the partition: they read 0
+            r.upload(t, b, si.uniform_f32(g, n))
+            gd.gd_launch_fenced(r.pool, t, gd.GD_K_TRIAD, gd.gd_args_triad(a, b, c, n, 0.75, 0), mode=mode)
+            r.sim.run("triad", (base, size), omode, a, b, c, 0.75, n)
+            inb = 30000 - (1 if shift else 0)
+            assert r.sim.last[1] == (n - inb) + (50000 - (3 if shift else 0))
+            assert rel_frobenius(r.download(a, np.float32, inb), r.sim.view(a, np.float32, inb)) <= 1e-5
+            assert r.images_equal(skip=[(a, 4 * inb)])
+            r.upload(t, a, r.sim.view(a, np.float32, inb).copy())
+            gd.gd_launch_fenced(r.pool, t, gd.GD_K_COPY, gd.gd_args_copy(base + 2 * MiB + shift, a, n), mode=mode)
+            r.sim.run("copy", (base, size), omode, base + 2 * MiB + shift, a, n)
+            assert r.images_equal()
+        # gather with indices far outside (offsets wrap at 2^32: some land inside, most are refused)
+        tab, idx, out = base + 512 * KiB, base + MiB, base + 2 * MiB
+        m = 60001
+        ix, where = si.c2_indices(g, m, 100000, frac=0.02, oob_hi=1 << 40)
+        ix[where[::3]] *= -1
+        img = ok.fence_array(base, size, np.uint64(tab) + (4 * ix[where]).astype(np.uint64), 4, omode)
+        ix[where[(img >= out) & (img < out + 4 * m)]] = 5         # loads that would race with this launch's stores
+        r.upload(t, idx, ix)
+        gd.gd_launch_fenced(r.pool, t, gd.GD_K_GATHER32_I64, gd.gd_args_gather(out, tab, idx, m), mode=mode)
+        r.sim.run("gather32_i64", (base, size), omode, out, tab, idx, m)
+        assert r.sim.last[1] > 0.9 * len(where) and r.images_equal()
+        # scatter: indices outside are refused (offsets far beyond the size); duplicates may land in either order
+        ix2 = g.integers(0, 100000, size=m, dtype=np.int64)
+        ix2[::50] = (1 << 28) + np.arange(len(ix2[::50]))
+        ix2[7::50] = -(1 << 20) - np.arange(len(ix2[7::50]))
+        r.upload(t, idx, ix2)
+        dst = base + 3 * MiB
+        gd.gd_launch_fenced(r.pool, t, gd.GD_K_SCATTER_F32_I64, gd.gd_args_scatter(dst, out, idx, m, 2.0, 0), mode=mode)
+        r.sim.run("scatter_f32_i64", (base, size), omode, dst, out, idx, 2.0, m)
+        assert r.sim.last[1] == len(ix2[::50]) + len(ix2[7::50])
+        assert r.images_equal(skip=[(dst, 4 * 100000)])
+        inr = ix2[(ix2 >= 0) & (ix2 < 100000)]
+        once = np.flatnonzero(np.bincount(inr, minlength=100000) <= 1)
+        assert np.array_equal(r.download(dst, np.uint32, 100000)[once], r.sim.view(dst, np.uint32, 100000)[once])
+        ws, res = base + 4 * MiB, base + 4 * MiB + 64 * KiB
+        start = end - 4 * 30000
+        gd.gd_launch_fenced(r.pool, t, gd.GD_K_SUM_F32, gd.gd_args_sum(res, start, ws, 50000), mode=mode)
+        exact = r.sim.run("sum_f32_exact", (base, size), omode, start, 50000)
+        assert r.sim.last[1] == 20000
+        assert abs(float(r.download(res, np.float32, 1)[0]) - exact) <= 1e-5 * abs(exact)
+        # the neighbours never changed
+        for other in (0, 2):
+            ob, os_ = r.table[other]
+            assert np.array_equal(r.download(ob, np.uint8, os_), r.sim.view(ob, np.uint8, os_))
+    finally:
+        r.close()
+
+
+def test_hwcheck_rmsnorm_and_gemm_read_zero_outside_and_drop_stores():
+    r = Rig([4 * MiB, 4 * MiB])
+    try:
+        g = si.rng(6, 96)
+        mode, omode = gd.GD_FENCE_HWCHECK, ok.MODE_HWCHECK
+        t = 0
+        base, size = r.row(t)
+        end = base + size
+        rows, cols = 9, 2048
+        x, gain = r.alloc(t, 2 * rows * cols), r.alloc(t, 2 * cols)
+        r.upload(t, x, si.f32_to_bf16_bits(si.normal_f32(g, rows * cols)))
+        r.upload(t, gain, si.f32_to_bf16_bits(si.uniform_f32(g, cols, 0.5, 1.5)))
+        r.upload(t, end - 2 * rows * cols, si.f32_to_bf16_bits(si.normal_f32(g, rows * cols)))
+        for (y, xx) in ((end - 2 * (6 * cols + 104), x),                    # output leaves the partition in row 6 (16-byte aligned)
+                        (base + 2 * MiB, end - 2 * rows * cols + 2 * (cols + 304)),    # input: the end of the last rows reads zeros
+                        (base + 2 * MiB + 2, end - 2 * rows * cols + 2 * 77),         # the same through pointers that are not 16-byte aligned
+                        (end - 2 * (3 * cols + 101), x + 2)):
+            gd.gd_launch_fenced(r.pool, t, gd.GD_K_RMSNORM_BF16, gd.gd_args_rmsnorm(y, xx, gain, rows, cols, 1e-6, 0), mode=mode)
+            r.oracle("rmsnorm_bf16", t, y, xx, gain, rows, cols, 1e-6, mode=omode)
+            assert r.sim.last[1] > 0
+            images_close_bf16(r, "hwcheck rmsnorm", 0.02 * rows * cols + 2)
+            r.dview(base, np.uint8, size).copy_(torch.from_numpy(r.sim.view(base, np.uint8, size)))
+        for (M, N, K, b_is_nk) in ((256, 256, 128, 1), (300, 200, 72, 1), (50, 70, 33, 0)):
+            A, B, Cc = r.alloc(t, 2 * M * K), r.alloc(t, 2 * K * N), r.alloc(t, 2 * M * N)
+            a_bits = si.f32_to_bf16_bits(si.normal_f32(g, M * K) * np.float32(K ** -0.5))
+            r.upload(t, A, a_bits)
+            r.upload(t, B, si.f32_to_bf16_bits(si.normal_f32(g, K * N)))
+            a_cut = 2 * (K * (M - M // 3) + 16)
+            r.upload(t, end - a_cut, a_bits[: a_cut // 2])
+            for (cc, aa, bb) in ((Cc, A, B), (Cc, end - a_cut, B), (end - 2 * (N * (M // 2) + N // 4), A, B)):
+                gd.gd_launch_fenced(r.pool, t, gd.GD_K_GEMM_BF16, gd.gd_args_gemm(cc, aa, bb, M, N, K, b_is_nk), mode=mode)
+                r.oracle("gemm_bf16", t, cc, aa, bb, M, N, K, b_is_nk, 0, M, 0, N, mode=omode)
+                images_close_bf16(r, f"hwcheck gemm {M}x{N}x{K}", 0.02 * M * N + 2)
+                r.dview(base, np.uint8, size).copy_(torch.from_numpy(r.sim.view(base, np.uint8, size)))
+            for p in (A, B, Cc):
+                r.free(t, p)
+        b1, s1 = r.row(1)
+        assert np.all(r.download(b1, np.uint8, s1) == 0xA5)
+    finally:
+        r.close()

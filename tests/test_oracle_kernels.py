@@ -584,3 +584,59 @@ def test_openmp_twin_equals_the_sequential_oracle_on_in_bounds_inputs():
     # only the sum may differ (another order of additions), and only in its last bits
     assert diff.size <= 2 and all(0 <= d - (p[7] - pool.pool_base) < 4 for d in diff)
     assert ok.lib(True).gdo_threads() >= 1 and ok.lib(False).gdo_threads() == 1
+
+
+# ---------------------------------------------------------------------------
+# hardware-style address checking (mode 4)
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("width", hm.ACCESS_WIDTHS)
+def test_hwcheck_confines_or_refuses_every_address(width):
+    """Brute force around a tiny pool of odd-sized partitions: an access is either made wholly
+    inside the own partition, at the address the plain formula gives, or refused; in-partition
+    aligned addresses are unchanged; addresses 2^32 apart behave alike."""
+    for (base, size) in ((0x40000, 4096 + 256), (0x41100, 4096 + 3 * 256)):
+        for a in range(base - 2 * size - 7, base + 3 * size + 7):
+            got = ok.fence(base, size, a, width, ok.MODE_HWCHECK)
+            off = ((a - base) % (1 << 32)) // width * width
+            want = base + off if off + width <= size else hm.U64
+            assert got == want
+            assert (hm.fence_hwcheck(a, base, size, width) or hm.U64) == want
+            if got != hm.U64:
+                assert base <= got and got + width <= base + size
+            if base <= a and a + width <= base + size and a % width == 0:
+                assert got == a
+            assert ok.fence(base, size, a + (1 << 32), width, ok.MODE_HWCHECK) == got
+            assert ok.fence(base, size, a + (5 << 32), width, ok.MODE_HWCHECK) == got
+
+
+def test_hwcheck_kernels_read_zero_and_drop_stores_outside():
+    """Triad whose arrays run over the end of the partition: loads outside read 0, stores outside are
+    dropped, the loop goes on (no thread stops); the neighbour partition is untouched."""
+    sizes = [16 * KiB, 16 * KiB]
+    pool, table = make_pool(sizes, fill=0xA5, pool_base=1 << 20)
+    base, size = table[0]
+    end = base + size
+    n = 1000
+    g = si.rng(0, 11)
+    a, b, c = end - 4 * 700, base + 4 * KiB, end - 4 * 400        # a: 700 inside, c: 400 inside
+    vb, vc = si.uniform_f32(g, n), si.uniform_f32(g, 400)
+    pool.view(b, np.float32, n)[:] = vb
+    pool.view(c, np.float32, 400)[:] = vc
+    before = pool.mem.copy()
+    esc, vio, wrapped = pool.run("triad", table[0], ok.MODE_HWCHECK, a, b, c, 0.5, n)
+    assert esc == 0 and wrapped == 0 and vio == (n - 400) + (n - 700)
+    cc = np.concatenate([vc.astype(np.float64), np.zeros(n - 400)])
+    want = (vb.astype(np.float64) + 0.5 * cc).astype(np.float32)
+    # a's elements 300.. overwrite c's memory, but element j reads c[j] before anything stores there (j + 300 comes later)
+    image = before.copy()
+    image[a - pool.pool_base:a - pool.pool_base + 4 * 700] = want[:700].view(np.uint8)
+    assert np.array_equal(pool.mem, image)                         # stores 700.. dropped, neighbour untouched
+    # gather through indices far outside: value 0 where refused
+    idx = np.array([0, 5, 1 << 20, -2048, (1 << 30) + 7, 9], dtype=np.int64)    # (1<<30)+7: offset 4*(2^30+7) mod 2^32 = 28 -> inside
+    tab, idxp, out = base + 4 * KiB, base + 8 * KiB, base + 12 * KiB
+    pool.view(idxp, np.int64, idx.size)[:] = idx
+    pool.view(out, np.uint32, idx.size)[:] = 0x77777777
+    pool.run("gather32_i64", table[0], ok.MODE_HWCHECK, out, tab, idxp, idx.size)
+    t = pool.view(tab, np.uint32, 16).copy()
+    assert pool.view(out, np.uint32, idx.size).tolist() == [t[0], t[5], 0, 0, t[7], t[9]]
