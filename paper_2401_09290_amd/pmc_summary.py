@@ -1,88 +1,174 @@
-"""Turns the rocprofv3 --pmc runs listed in profiles/pmc_fence_overhead_and_traffic.md into that file.
+"""Summarise rocprofv3 ``--pmc`` runs of ``bench.py`` into the tables kept under ``profiles/``.
 
-Expects the counter CSVs the commands in the summary write (directories pmc_insts, pmc_fetch, pmc_write,
-pmc_l2, pmc_c2f, pmc_c2w under the directory given as argument), averages every counter
-per kernel and dispatch, calibrates FETCH_SIZE / WRITE_SIZE on the unfenced copy kernel (whose traffic is
-known) and prints the summary; bench.py reads the line `traffic_bytes_per_launch:` from it.
+Input: a directory with one sub-directory per counter run, each holding the
+``*_counter_collection.csv`` that ``rocprofv3 --pmc ... --output-format csv`` writes:
 
-usage: python -m paper_2401_09290_amd.pmc_summary DIR > profiles/pmc_fence_overhead_and_traffic.md
+    insts/   SQ_INSTS_VALU SQ_INSTS_SALU SQ_INSTS_VMEM SQ_INSTS_LDS SQ_WAVES
+             SQ_INSTS_VALU_MFMA_BF16 SQ_VALU_MFMA_BUSY_CYCLES GRBM_GUI_ACTIVE
+    fetch/   FETCH_SIZE          (KiB per dispatch, before calibration)
+    write/   WRITE_SIZE
+
+Counters are averaged per kernel over its dispatches.  The tables:
+
+* instructions per dispatch and per wavefront, and the fence's cost in vector
+  instructions per wavefront (each fenced kernel ``name<V, ...>`` against the unfenced
+  build ``name<0, ...>`` of the same kernel);
+* matrix-pipe utilisation of every kernel that issues MFMA instructions;
+* bytes past the L2 per dispatch, FETCH_SIZE and WRITE_SIZE each scaled by what the
+  same counter reads for the unfenced copy kernel, whose traffic is known
+  (``--copy-elems`` 4-byte elements read and written once), against the algorithmic
+  bytes of bench.py's default sizes.  The line ``traffic_bytes_per_launch:`` (the fenced
+  triad of the headline configuration) is what bench.py reports as ``roofline.traffic``.
+
+usage: python -m paper_2401_09290_amd.pmc_summary DIR [--copy-elems N]
 """
+import argparse
 import collections
 import csv
-import sys
+import glob
+import os
+import re
 
-ROOT = '.'
+XCDS = 8
+SIMDS = 1024                      # 256 compute units x 4
+VARIANTS = {0: "unfenced", 1: "bitwise, 32-bit offset", 2: "bitwise, 64-bit", 3: "modulo", 4: "checking",
+            5: "hardware checking (buffer)"}
+
+# algorithmic bytes per dispatch at bench.py's default sizes, by kernel (template arguments after the variant)
+GiB, MiB = 1 << 30, 1 << 20
+ALGORITHMIC = {
+    "k_stream<V, 0, true>": 2 * GiB, "k_stream<V, 1, true>": 3 * GiB,
+    "k_gather32<V, 1>": 16 << 26, "k_scatter_f32_i64<V>": 16 << 26, "k_gather32<V, 0>": 12 << 24,
+    "k_sum_partial<V, false>": 4 << 27, "k_rmsnorm_bf16<V>": 4 * 4096 * 8192, "k_gemm_ring<V>": 3 * 128 * MiB,
+}
 
 
-def load(d, pre, needle="gd::"):
-    d = f'{ROOT}/{d}'
-    rows = list(csv.DictReader(open(f'{d}/{pre}_counter_collection.csv')))
-    agg=collections.defaultdict(lambda: collections.defaultdict(list))
-    for r in rows:
-        if needle in r['Kernel_Name']:
-            k=r['Kernel_Name'].split('(')[0].replace('void gd::','')
-            agg[k][r['Counter_Name']].append(float(r['Counter_Value']))
-            agg[k]['dur_ns'].append(int(r['End_Timestamp'])-int(r['Start_Timestamp']))
-    return {k:{c:sum(x)/len(x) for c,x in v.items()} for k,v in agg.items()}
-def main(root):
-    global ROOT
-    ROOT = root
-    ins=load('pmc_insts','p')
-    fe=load('pmc_fetch','p'); wr=load('pmc_write','p')
-    cf=1048576.0/fe['k_stream<0, 0>']['FETCH_SIZE']; cw=1048576.0/wr['k_stream<0, 0>']['WRITE_SIZE']
-    out=[]
-    out.append("# Hardware counters: fenced vs unfenced instruction counts, MFMA utilisation, HBM traffic\n")
-    out.append("All runs on one MI355X box, from the repository root, counters averaged per dispatch; this file is the output of `python -m paper_2401_09290_amd.pmc_summary " + ROOT + "` after the commands below. Template arguments:")
-    out.append("first = fence variant (0 unfenced, 1 = 32-bit bitwise fence for partitions <= 4 GiB, 2 = 64-bit bitwise fence, 3 = modulo fence, 4 = address checking), second = op/index kind.\n")
-    out.append("## Instruction counts per dispatch\n")
-    out.append("Command:\n\n    rocprofv3 --pmc SQ_INSTS_VALU SQ_INSTS_SALU SQ_INSTS_VMEM SQ_INSTS_LDS SQ_WAVES SQ_INSTS_VALU_MFMA_BF16 SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES GRBM_GUI_ACTIVE --output-format csv -d " + ROOT + "/pmc_insts -o p -- python3 bench.py --configs c3,c4,c2,c1,c5 --steps 3 --warmup 1 --prewarm-ms 0 --no-cpu-baseline\n")
-    out.append("kernel | waves | VALU | of which MFMA | SALU | VMEM | LDS | VALU per wave | time us (serialised by the profiler)")
-    out.append("---|---|---|---|---|---|---|---|---")
-    for k,v in ins.items():
-        w=v.get('SQ_WAVES',0) or 1
-        out.append(f"{k} | {v['SQ_WAVES']:.0f} | {v['SQ_INSTS_VALU']:.0f} | {v['SQ_INSTS_VALU_MFMA_BF16']:.0f} | {v['SQ_INSTS_SALU']:.0f} | {v['SQ_INSTS_VMEM']:.0f} | {v['SQ_INSTS_LDS']:.0f} | {v['SQ_INSTS_VALU']/w:.1f} | {v['dur_ns']/1e3:.1f}")
-    out.append("\nFence cost in VALU instructions (fenced minus unfenced, per wave): " + ", ".join(
-        f"{a.split('<')[0]}{'/'+a.split(', ')[1].rstrip('>') if ', ' in a else ''}: {ins[a]['SQ_INSTS_VALU']/ins[a]['SQ_WAVES']-ins[b]['SQ_INSTS_VALU']/ins[b]['SQ_WAVES']:+.1f}"
-        for a,b in (("k_stream<2, 0>","k_stream<0, 0>"),("k_stream<2, 1>","k_stream<0, 1>"),("k_gemm_ring<1>","k_gemm_ring<0>"),("k_gather32<1, 1>","k_gather32<0, 1>"),("k_scatter_f32_i64<1>","k_scatter_f32_i64<0>"),("k_saxpy_idx<1>","k_saxpy_idx<0>")) if a in ins and b in ins) + ".\n")
-    out.append("## MFMA utilisation of the GEMM (8192^3, bf16)\n")
-    for k in ("k_gemm_ring<1>","k_gemm_ring<0>"):
-        v=ins[k]; cyc=v['GRBM_GUI_ACTIVE']/8
-        out.append(f"* {k}: SQ_VALU_MFMA_BUSY_CYCLES {v['SQ_VALU_MFMA_BUSY_CYCLES']:.0f} (= {v['SQ_INSTS_VALU_MFMA_BF16']:.0f} MFMA x {v['SQ_VALU_MFMA_BUSY_CYCLES']/v['SQ_INSTS_VALU_MFMA_BF16']:.0f} cycles) over {cyc:.0f} shader cycles x 1024 SIMDs = {100*v['SQ_VALU_MFMA_BUSY_CYCLES']/(cyc*1024):.1f} % of the matrix-pipe cycles; shader clock during the kernel {cyc/v['dur_ns']:.2f} GHz (GRBM_GUI_ACTIVE / 8 XCDs / duration), i.e. the chip runs well below its 2.4 GHz peak clock under this load (the counter run serialises dispatches and adds its own overhead; bench.py's timing is the reference for throughput).")
-    l2=load('pmc_l2','p')
-    out.append("\n## L2 requests and LDS bank conflicts of the GEMM (8192^3)\n")
-    out.append("Command:\n\n    rocprofv3 --pmc TCP_TCC_READ_REQ_sum TCP_TOTAL_CACHE_ACCESSES_sum TCC_REQ_sum TCC_HIT_sum TCC_MISS_sum TCC_EA0_RDREQ_sum SQ_LDS_BANK_CONFLICT SQ_ACTIVE_INST_LDS --output-format csv -d " + ROOT + "/pmc_l2 -o p -- python3 bench.py --configs c4 --steps 4 --warmup 1 --prewarm-ms 0 --no-cpu-baseline\n")
-    for k in ("k_gemm_ring<1>","k_gemm_ring<0>"):
-        v=l2[k]
-        out.append(f"* {k}: vector-cache accesses (64 B each) {v['TCP_TOTAL_CACHE_ACCESSES_sum']:.0f}; read requests to L2 {v['TCP_TCC_READ_REQ_sum']:.0f} = {v['TCP_TCC_READ_REQ_sum']/(1024*2*256*8192*2/128):.3f} per 128-byte line of operand data a tile reads (8 GiB over all tiles: the two 64-byte halves of a line, fetched by neighbouring DMA instructions, merge into one request); L2 requests {v['TCC_REQ_sum']:.0f}, hits {v['TCC_HIT_sum']:.0f} ({100*v['TCC_HIT_sum']/v['TCC_REQ_sum']:.1f} %), misses {v['TCC_MISS_sum']:.0f}; SQ_LDS_BANK_CONFLICT {v['SQ_LDS_BANK_CONFLICT']:.0f} cycles.")
-    gf=(fe['k_gemm_ring<1>']['FETCH_SIZE'], wr['k_gemm_ring<1>']['WRITE_SIZE'])
-    out.append("\n## HBM traffic of the streaming kernels (configuration 3 sizes: 2^28 fp32 elements per array)\n")
-    out.append("Commands (one counter group per run):\n\n    rocprofv3 --pmc FETCH_SIZE --output-format csv -d " + ROOT + "/pmc_fetch -o p -- python3 bench.py --configs c3,c4 --steps 4 --warmup 1 --prewarm-ms 0 --no-cpu-baseline\n    rocprofv3 --pmc WRITE_SIZE --output-format csv -d " + ROOT + "/pmc_write -o p -- python3 bench.py --configs c3,c4 --steps 4 --warmup 1 --prewarm-ms 0 --no-cpu-baseline\n")
-    cf=1048576.0/fe['k_stream<0, 0>']['FETCH_SIZE']; cw=1048576.0/wr['k_stream<0, 0>']['WRITE_SIZE']
-    out.append(f"Calibration on the plain copy kernel k_stream<0, 0> (reads 1 GiB = 1048576 KiB, writes 1 GiB): FETCH_SIZE reads {fe['k_stream<0, 0>']['FETCH_SIZE']:.1f}, WRITE_SIZE reads {wr['k_stream<0, 0>']['WRITE_SIZE']:.1f}; scale factors {cf:.5f} (fetch) and {cw:.5f} (write).\n")
-    out.append("kernel | FETCH_SIZE raw | WRITE_SIZE raw | HBM bytes per launch (scaled) | algorithmic bytes")
-    out.append("---|---|---|---|---")
-    alg={"k_stream<2, 0>":2<<30,"k_stream<2, 1>":3<<30,"k_stream<0, 0>":2<<30,"k_stream<0, 1>":3<<30}
-    tri=None
-    for k in alg:
-        b=(fe[k]['FETCH_SIZE']*cf+wr[k]['WRITE_SIZE']*cw)*1024
-        if k=="k_stream<2, 1>": tri=b
-        out.append(f"{k} | {fe[k]['FETCH_SIZE']:.1f} | {wr[k]['WRITE_SIZE']:.1f} | {b:.0f} | {alg[k]}")
-    out.append(f"\nThe fenced triad moves {tri/alg['k_stream<2, 1>']:.4f} x its algorithmic bytes: no re-reads.\n")
-    out.append(f"GEMM k_gemm_ring<1> (same runs): FETCH_SIZE {gf[0]:.1f}, WRITE_SIZE {gf[1]:.1f} -> {(gf[0]*cf+gf[1]*cw)*1024/2**20:.0f} MiB leave the L2 towards the last-level cache and HBM per launch, against 384 MiB of operands and result: each XCD works on 4 x 8 tiles at a time, so A is fetched 4 times (once per group of 8 tile columns) and B 8 times (once per XCD): 512 + 1024 MiB.\n")
-    c2f=load('pmc_c2f','p'); c2w=load('pmc_c2w','p')
-    out.append("## Fabric traffic of the indexed and reduction kernels (configurations 2 and 5)\n")
-    out.append("Commands (same calibration factors as above):\n\n    rocprofv3 --pmc FETCH_SIZE --output-format csv -d " + ROOT + "/pmc_c2f -o p -- python3 bench.py --configs c2,c5 --steps 4 --warmup 1 --prewarm-ms 0 --no-cpu-baseline\n    rocprofv3 --pmc WRITE_SIZE --output-format csv -d " + ROOT + "/pmc_c2w -o p -- python3 bench.py --configs c2,c5 --steps 4 --warmup 1 --prewarm-ms 0 --no-cpu-baseline\n")
-    out.append("kernel | FETCH_SIZE raw | WRITE_SIZE raw | bytes per launch past the L2 (scaled) | algorithmic bytes | duration us | traffic rate TB/s")
-    out.append("---|---|---|---|---|---|---")
-    algo={"k_gather32<1, 1>":16*2**26,"k_gather32<0, 1>":16*2**26,"k_scatter_f32_i64<1>":16*2**26,"k_scatter_f32_i64<0>":16*2**26,"k_gather32<0, 0>":12*2**24,"k_sum_partial<0>":4*2**27,"k_rmsnorm_bf16<0>":4*4096*8192}
-    for k,ab in algo.items():
-        if k in c2f and k in c2w:
-            b=(c2f[k]['FETCH_SIZE']*cf+c2w[k]['WRITE_SIZE']*cw)*1024
-            out.append(f"{k} | {c2f[k]['FETCH_SIZE']:.0f} | {c2w[k]['WRITE_SIZE']:.0f} | {b:.0f} | {ab} | {c2f[k]['dur_ns']/1e3:.1f} | {b/c2f[k]['dur_ns']/1e3:.2f}")
-    out.append("\nThe gathers issue one fabric read per random 4-byte access (FETCH_SIZE counts requests; the calibration on the copy kernel says a request is a 128-byte line): 2^26 gathers move 8.8 GiB, 8.4 times their algorithmic bytes, at 7.1 TB/s = 89 % of the HBM peak -- the random-access kernels are bound by line traffic, not by the fence. The scatter writes 32 bytes per random 4-byte store. Sum and RMSNorm move exactly their algorithmic bytes (unfenced rows shown: their fenced launches in this command share the GPU with other tenants' kernels, which stretches the begin-to-end times).\n")
-    out.append(f"traffic_bytes_per_launch: {tri:.0f}")
-    print("\n".join(out))
+def short_name(kernel_name):
+    name = kernel_name.split("(")[0].replace("void ", "").replace("gd::", "")
+    return name.strip()
+
+
+def variant_of(name):
+    m = re.search(r"<(\d+)", name)
+    return int(m.group(1)) if m else None
+
+
+def generic(name):
+    """k_stream<2, 1, true> -> k_stream<V, 1, true> (the key under which builds of one kernel are paired)."""
+    return re.sub(r"<\d+", "<V", name, count=1)
+
+
+def load(run_dir, needle="gd::"):
+    """{kernel: {counter: mean over dispatches, 'dur_ns': mean, 'calls': n}} of one counter run."""
+    files = sorted(glob.glob(os.path.join(run_dir, "**", "*counter_collection.csv"), recursive=True))
+    if not files:
+        return {}
+    acc = collections.defaultdict(lambda: collections.defaultdict(list))
+    for path in files:
+        with open(path, newline="") as f:
+            for r in csv.DictReader(f):
+                if needle not in r["Kernel_Name"]:
+                    continue
+                k = short_name(r["Kernel_Name"])
+                acc[k][r["Counter_Name"]].append(float(r["Counter_Value"]))
+                acc[k]["dur_ns"].append(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
+    out = {}
+    for k, counters in acc.items():
+        out[k] = {c: sum(v) / len(v) for c, v in counters.items()}
+        out[k]["calls"] = max(len(v) for c, v in counters.items() if c != "dur_ns")
+    return out
+
+
+def instruction_table(ins):
+    lines = ["kernel | rule | waves | VALU | of which MFMA | SALU | VMEM | LDS | VALU per wave | SALU per wave",
+             "---|---|---|---|---|---|---|---|---|---"]
+    for k in sorted(ins):
+        v = ins[k]
+        w = v.get("SQ_WAVES") or 1.0
+        lines.append(f"{k} | {VARIANTS.get(variant_of(k), '')} | {v.get('SQ_WAVES', 0):.0f} | {v.get('SQ_INSTS_VALU', 0):.0f} | "
+                     f"{v.get('SQ_INSTS_VALU_MFMA_BF16', 0):.0f} | {v.get('SQ_INSTS_SALU', 0):.0f} | {v.get('SQ_INSTS_VMEM', 0):.0f} | "
+                     f"{v.get('SQ_INSTS_LDS', 0):.0f} | {v.get('SQ_INSTS_VALU', 0) / w:.1f} | {v.get('SQ_INSTS_SALU', 0) / w:.1f}")
+    return lines
+
+
+def fence_cost(ins):
+    """Per fenced kernel: vector and scalar instructions per wavefront minus those of the unfenced build."""
+    base = {generic(k): v for k, v in ins.items() if variant_of(k) == 0}
+    lines = ["kernel | rule | VALU per wave: fenced - unfenced | SALU per wave: fenced - unfenced | VALU overhead",
+             "---|---|---|---|---"]
+    rows = []
+    for k in sorted(ins):
+        b = base.get(generic(k))
+        if variant_of(k) in (None, 0) or not b:
+            continue
+        v = ins[k]
+        per = lambda d, c: d.get(c, 0) / (d.get("SQ_WAVES") or 1.0)
+        dv, ds = per(v, "SQ_INSTS_VALU") - per(b, "SQ_INSTS_VALU"), per(v, "SQ_INSTS_SALU") - per(b, "SQ_INSTS_SALU")
+        pct = 100.0 * dv / per(b, "SQ_INSTS_VALU") if per(b, "SQ_INSTS_VALU") else float("nan")
+        rows.append((k, dv, ds, pct))
+        lines.append(f"{k} | {VARIANTS.get(variant_of(k), '')} | {dv:+.1f} | {ds:+.1f} | {pct:+.1f} %")
+    return lines, rows
+
+
+def mfma_table(ins):
+    lines = []
+    for k in sorted(ins):
+        v = ins[k]
+        n = v.get("SQ_INSTS_VALU_MFMA_BF16", 0)
+        if not n or "GRBM_GUI_ACTIVE" not in v:
+            continue
+        cycles = v["GRBM_GUI_ACTIVE"] / XCDS
+        busy = v.get("SQ_VALU_MFMA_BUSY_CYCLES", 0)
+        lines.append(f"* {k}: {n:.0f} MFMA instructions, SQ_VALU_MFMA_BUSY_CYCLES {busy:.0f} ({busy / n:.1f} per instruction) over "
+                     f"{cycles:.0f} shader cycles x {SIMDS} SIMDs = {100.0 * busy / (cycles * SIMDS):.1f} % of the matrix-pipe cycles; "
+                     f"shader clock during the kernel {cycles / v['dur_ns']:.2f} GHz (GRBM_GUI_ACTIVE / {XCDS} XCDs / duration; "
+                     f"dispatches are serialised by the profiler, bench.py's timing is the reference for throughput)")
+    return lines
+
+
+def traffic_table(fetch, write, copy_elems):
+    copy = [k for k in fetch if generic(k).startswith("k_stream<V, 0") and variant_of(k) == 0 and k in write]
+    if not copy:
+        return ["(no unfenced copy kernel in the counter runs: FETCH_SIZE / WRITE_SIZE cannot be calibrated)"], None
+    ref = copy[0]
+    known_kib = 4.0 * copy_elems / 1024.0
+    cf, cw = known_kib / fetch[ref]["FETCH_SIZE"], known_kib / write[ref]["WRITE_SIZE"]
+    lines = [f"Calibration on `{ref}` (reads and writes {4 * copy_elems} bytes once): FETCH_SIZE reads "
+             f"{fetch[ref]['FETCH_SIZE']:.1f}, WRITE_SIZE reads {write[ref]['WRITE_SIZE']:.1f}; scale factors {cf:.5f} (fetch) and {cw:.5f} (write).",
+             "",
+             "kernel | rule | fetched bytes | written bytes | total | algorithmic | total / algorithmic",
+             "---|---|---|---|---|---|---"]
+    headline = None
+    for k in sorted(set(fetch) & set(write)):
+        fb = fetch[k]["FETCH_SIZE"] * cf * 1024.0
+        wb = write[k]["WRITE_SIZE"] * cw * 1024.0
+        alg = ALGORITHMIC.get(generic(k))
+        ratio = f"{(fb + wb) / alg:.3f}" if alg else ""
+        lines.append(f"{k} | {VARIANTS.get(variant_of(k), '')} | {fb:.4g} | {wb:.4g} | {fb + wb:.4g} | {alg or ''} | {ratio}")
+        if generic(k) == "k_stream<V, 1, true>" and variant_of(k) == 2:
+            headline = fb + wb
+    return lines, headline
+
+
+def summarise(root, copy_elems=1 << 28):
+    ins, fetch, write = (load(os.path.join(root, d)) for d in ("insts", "fetch", "write"))
+    out = ["## Instructions per dispatch", ""] + instruction_table(ins)
+    cost, _ = fence_cost(ins)
+    out += ["", "## Cost of the fence in instructions per wavefront", ""] + cost
+    mf = mfma_table(ins)
+    if mf:
+        out += ["", "## Matrix-pipe utilisation", ""] + mf
+    tr, headline = traffic_table(fetch, write, copy_elems)
+    out += ["", "## Bytes past the L2 per dispatch", ""] + tr
+    if headline is not None:
+        out += ["", "Fenced triad of the headline configuration (`roofline.traffic` of bench.py):", "",
+                f"traffic_bytes_per_launch: {headline:.0f}"]
+    return "\n".join(out) + "\n"
 
 
 if __name__ == "__main__":
-    main(sys.argv[1] if len(sys.argv) > 1 else '.')
+    ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
+    ap.add_argument("root")
+    ap.add_argument("--copy-elems", type=int, default=1 << 28)
+    a = ap.parse_args()
+    print(summarise(a.root, a.copy_elems), end="")
