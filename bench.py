@@ -38,8 +38,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--configs", default="c3,c4,power,c2,c1,c5,modes",
-                    help="comma list out of c1..c5 (c3 is the headline), power (GEMM against the chip's power limit) "
-                         "and modes (the paper's three rules side by side)")
+                    help="comma list out of c1..c5 (c3 is the headline), power (GEMM against the chip's power limit), "
+                         "modes (the paper's three rules side by side) and gatherpolicy (cache-policy bits on random loads; "
+                         "not in the default list)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--prewarm-ms", type=float, default=250.0,
                     help="untimed launches in front of every measurement until this much GPU time has passed "
@@ -617,6 +618,30 @@ def run_power(torch, gd, si, args):
 
 
 # ---------------------------------------------------------------------------------
+# random 4-byte loads under every cache-policy combination (not in the default list)
+# ---------------------------------------------------------------------------------
+
+def run_gatherpolicy(torch, gd, si, args):
+    """Configuration 2's gather (table 2^26 fp32, 2^26 int64 indices, in bounds) with the table load carrying each
+    combination of the sc0 / sc1 / nt bits.  Run under `rocprofv3 --pmc FETCH_SIZE` to read the bytes fetched past
+    the L2 per variant; the times here show whether any combination helps."""
+    n = tab_n = 1 << 26
+    log("[gatherpolicy] random 4-byte loads from a 256 MiB table, 8 cache-policy combinations")
+    tab = torch.empty(tab_n, dtype=torch.float32, device="cuda").normal_()
+    idx = torch.from_numpy(si.rng(2, 0).integers(0, tab_n, size=n, dtype=np.int64)).cuda()
+    out = torch.empty(n, dtype=torch.float32, device="cuda")
+    st = torch.cuda.Stream()
+    names = ("none", "sc0", "sc1", "sc0 sc1", "nt", "sc0 nt", "sc1 nt", "sc0 sc1 nt")
+    res = {"workload": "unfenced gather of 2^26 fp32 values through 2^26 uniform int64 indices over a 256 MiB table, per cache-policy bits on the table load"}
+    for p, name in enumerate(names):
+        sec = solo_avg_seconds(torch, st, lambda: gd.gd_probe_gather_policy(out.data_ptr(), tab.data_ptr(), idx.data_ptr(), n, p, stream=st.cuda_stream), max(3, args.steps // 2))
+        res[name] = {"ms": round(sec * 1e3, 4), "GBps_algorithmic": round(16 * n / sec / 1e9, 1)}
+        log(f"[gatherpolicy] {name:11s}: {sec * 1e3:.3f} ms, {16 * n / sec / 1e9:.1f} GB/s algorithmic")
+    assert torch.equal(out, tab[idx])
+    return res
+
+
+# ---------------------------------------------------------------------------------
 # the paper's three bounds-checking rules side by side; cache-resident regime; host path
 # ---------------------------------------------------------------------------------
 
@@ -812,7 +837,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
-    runners = {"c1": run_c1, "c2": run_c2, "c3": run_c3, "c4": run_c4, "c5": run_c5, "modes": run_modes, "power": run_power}
+    runners = {"c1": run_c1, "c2": run_c2, "c3": run_c3, "c4": run_c4, "c5": run_c5, "modes": run_modes, "power": run_power, "gatherpolicy": run_gatherpolicy}
     wanted = [c.strip() for c in args.configs.split(",") if c.strip()]
     per = {}
     for c in wanted:

@@ -230,6 +230,16 @@ uint64_t gd_fence_host(uint64_t base, uint64_t size, uint64_t addr, uint32_t wid
  * caller-owned plain device memory.  flop per launch = blocks * 4 * iters * 2^20. */
 int gd_probe_mfma(uint64_t operands, uint64_t out, uint32_t blocks, uint32_t iters, void *hip_stream);
 
+/* Measurement aid, not part of the fenced path (no pool, no tenant, no fence):
+ * out[i] = tab[idx[i]] for 4-byte values and 64-bit indices, the table load carrying
+ * the cache-policy bits `policy` (bit 0 = sc0, bit 1 = sc1, bit 2 = nt).  The caller
+ * owns all three arrays (plain device memory; out and idx 16-byte aligned, n a multiple
+ * of 4) and guarantees that every index addresses the table and that the table is
+ * smaller than 4 GiB.  bench.py times the eight combinations and, under rocprofv3,
+ * reads the bytes each fetches past the L2. */
+int gd_probe_gather_policy(uint64_t out, uint64_t tab, uint64_t idx, uint64_t n, uint32_t policy,
+                           void *hip_stream);
+
 const char *gd_strerror(int status);
 int gd_last_hip_error(void);   /* hipError_t of the last failed HIP call on this thread */
 

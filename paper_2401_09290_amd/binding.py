@@ -55,6 +55,7 @@ EXPORTS = {
                                    C.POINTER(_u32), C.POINTER(_u32), C.c_void_p, C.c_int]),
     "gd_sum_f32_noalloc": (C.c_int, [C.c_void_p, C.c_int, _u64, _u64, _u64, C.c_void_p, C.c_int]),
     "gd_probe_mfma": (C.c_int, [_u64, _u64, _u32, _u32, C.c_void_p]),
+    "gd_probe_gather_policy": (C.c_int, [_u64, _u64, _u64, _u64, _u32, C.c_void_p]),
     "gd_kernel_count": (C.c_int, []),
     "gd_kernel_name": (C.c_char_p, [C.c_int]),
     "gd_kernel_args_bytes": (C.c_size_t, [C.c_int]),
@@ -163,6 +164,10 @@ def gd_sum_f32_noalloc(pool, tenant, out, in_, n, stream=None, mode=GD_FENCE_BIT
 
 def gd_probe_mfma(operands, out, blocks, iters, stream=None):
     _ok(lib().gd_probe_mfma(operands, out, blocks, iters, C.c_void_p(stream or 0)), "gd_probe_mfma")
+
+
+def gd_probe_gather_policy(out, tab, idx, n, policy, stream=None):
+    _ok(lib().gd_probe_gather_policy(out, tab, idx, n, policy, C.c_void_p(stream or 0)), "gd_probe_gather_policy")
 
 
 def gd_fence_host(base, size, addr, width=1, mode=GD_FENCE_BITWISE):

@@ -214,6 +214,11 @@ int gd_probe_mfma(uint64_t operands, uint64_t out, uint32_t blocks, uint32_t ite
     GD_ABI_GUARD(gd::launch_mfma_probe(operands, out, blocks, iters, static_cast<hipStream_t>(hip_stream)))
 }
 
+int gd_probe_gather_policy(uint64_t out, uint64_t tab, uint64_t idx, uint64_t n, uint32_t policy, void *hip_stream)
+{
+    GD_ABI_GUARD(gd::launch_probe_gather_policy(out, tab, idx, n, policy, static_cast<hipStream_t>(hip_stream)))
+}
+
 const char *gd_strerror(int status)
 {
     switch (status) {

@@ -126,6 +126,67 @@ __global__ __launch_bounds__(1024) void k_scatter_f32_i64(gd_args_scatter p, Fen
     }
 }
 
+// ---- measurement aid: does a cache-policy bit change what a random 4-byte load costs? ----------
+// The gather of k_gather32 with 64-bit indices, unfenced, in bounds only, with the table
+// load written out so that it can carry any combination of the sc0 / sc1 / nt bits
+// (POLICY bit 0 = sc0, bit 1 = sc1, bit 2 = nt).  Index and output streams as in the
+// library kernel.  Used by bench.py to show that the memory system fills a whole
+// 128-byte line per random access whatever the bits say.
+template <int POLICY>
+__device__ __forceinline__ uint32_t ld_with_policy(const uint32_t *base, uint32_t off)
+{
+    uint32_t v;
+    if constexpr (POLICY == 0) asm volatile("global_load_dword %0, %1, %2" : "=v"(v) : "v"(off), "s"(base) : "memory");
+    if constexpr (POLICY == 1) asm volatile("global_load_dword %0, %1, %2 sc0" : "=v"(v) : "v"(off), "s"(base) : "memory");
+    if constexpr (POLICY == 2) asm volatile("global_load_dword %0, %1, %2 sc1" : "=v"(v) : "v"(off), "s"(base) : "memory");
+    if constexpr (POLICY == 3) asm volatile("global_load_dword %0, %1, %2 sc0 sc1" : "=v"(v) : "v"(off), "s"(base) : "memory");
+    if constexpr (POLICY == 4) asm volatile("global_load_dword %0, %1, %2 nt" : "=v"(v) : "v"(off), "s"(base) : "memory");
+    if constexpr (POLICY == 5) asm volatile("global_load_dword %0, %1, %2 sc0 nt" : "=v"(v) : "v"(off), "s"(base) : "memory");
+    if constexpr (POLICY == 6) asm volatile("global_load_dword %0, %1, %2 sc1 nt" : "=v"(v) : "v"(off), "s"(base) : "memory");
+    if constexpr (POLICY == 7) asm volatile("global_load_dword %0, %1, %2 sc0 sc1 nt" : "=v"(v) : "v"(off), "s"(base) : "memory");
+    return v;
+}
+
+template <int POLICY>
+__global__ __launch_bounds__(256) void k_probe_gather_policy(uint32_t *out, const uint32_t *tab, const uint64_t *idx, uint64_t n4)
+{
+    for (uint64_t q = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; q < n4; q += (uint64_t)gridDim.x * blockDim.x) {
+        const u64x2 k01 = __builtin_nontemporal_load((const u64x2 *)(idx + 4 * q));
+        const u64x2 k23 = __builtin_nontemporal_load((const u64x2 *)(idx + 4 * q + 2));
+        u32x4 v;
+        v[0] = ld_with_policy<POLICY>(tab, (uint32_t)(4 * k01[0]));
+        v[1] = ld_with_policy<POLICY>(tab, (uint32_t)(4 * k01[1]));
+        v[2] = ld_with_policy<POLICY>(tab, (uint32_t)(4 * k23[0]));
+        v[3] = ld_with_policy<POLICY>(tab, (uint32_t)(4 * k23[1]));
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(v) : : "memory");
+        __builtin_nontemporal_store(v, (u32x4 *)(out + 4 * q));
+    }
+}
+
+// The caller guarantees that every index is below table_elems and that table_elems * 4 fits 32 bits.
+int launch_probe_gather_policy(uint64_t out, uint64_t tab, uint64_t idx, uint64_t n, uint32_t policy, hipStream_t stream)
+{
+    if (!out || !tab || !idx || ((out | idx) & 15) || (tab & 3) || (n & 3) || policy > 7) return GD_EINVAL;
+    if (n == 0) return GD_OK;
+    const uint64_t n4 = n >> 2;
+    const dim3 grid((uint32_t)((n4 + 255) / 256 > 0x7fffffffull ? 0x7fffffffull : (n4 + 255) / 256)), block(256);
+    uint32_t *o = (uint32_t *)(uintptr_t)out;
+    const uint32_t *t = (const uint32_t *)(uintptr_t)tab;
+    const uint64_t *i = (const uint64_t *)(uintptr_t)idx;
+    switch (policy) {
+    case 0: hipLaunchKernelGGL((k_probe_gather_policy<0>), grid, block, 0, stream, o, t, i, n4); break;
+    case 1: hipLaunchKernelGGL((k_probe_gather_policy<1>), grid, block, 0, stream, o, t, i, n4); break;
+    case 2: hipLaunchKernelGGL((k_probe_gather_policy<2>), grid, block, 0, stream, o, t, i, n4); break;
+    case 3: hipLaunchKernelGGL((k_probe_gather_policy<3>), grid, block, 0, stream, o, t, i, n4); break;
+    case 4: hipLaunchKernelGGL((k_probe_gather_policy<4>), grid, block, 0, stream, o, t, i, n4); break;
+    case 5: hipLaunchKernelGGL((k_probe_gather_policy<5>), grid, block, 0, stream, o, t, i, n4); break;
+    case 6: hipLaunchKernelGGL((k_probe_gather_policy<6>), grid, block, 0, stream, o, t, i, n4); break;
+    default: hipLaunchKernelGGL((k_probe_gather_policy<7>), grid, block, 0, stream, o, t, i, n4); break;
+    }
+    GD_CHECK_LAUNCH();
+    return GD_OK;
+}
+
 // ---- launchers ---------------------------------------------------------------------
 
 static uint64_t blocks_for(uint64_t n, uint32_t block)

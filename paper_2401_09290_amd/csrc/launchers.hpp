@@ -39,6 +39,9 @@ int launch_sum_f32_noalloc(uint64_t out, uint64_t in, uint64_t n, const FenceArg
 // Matrix-pipe probe (gd_probe_mfma): no tenant, no fence.
 int launch_mfma_probe(uint64_t operands, uint64_t out, uint32_t blocks, uint32_t iters, hipStream_t);
 
+// Cache-policy probe of random 4-byte loads (gd_probe_gather_policy): no tenant, no fence.
+int launch_probe_gather_policy(uint64_t out, uint64_t tab, uint64_t idx, uint64_t n, uint32_t policy, hipStream_t);
+
 // 1-D launch shape of an element-wise kernel that loops over `tiles` tiles.
 // Returns false if the caller's shape is unusable.
 inline bool pick_1d(const Shape &s, uint64_t tiles, uint32_t default_block, uint32_t *grid,

@@ -272,7 +272,8 @@ def run(verbose=True):
             for n in names:
                 p = pretty[n].replace("void gd::", "").split("(")[0]
                 v = re.search(r"<(\d)", p)
-                variant = int(v.group(1)) if v else -1
+                # the measurement aids (k_*probe*) take no tenant and no fence: their template argument is not a rule
+                variant = int(v.group(1)) if v and "probe" not in p else -1
                 pr, ld, st, fc = lint_kernel(n, p, bodies[n], variant)
                 md = meta.get(n, {})
                 if md.get("scratch", 0) > 0:
