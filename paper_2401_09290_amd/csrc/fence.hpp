@@ -181,6 +181,25 @@ struct Fence {
         }
     }
 
+    // The same for a whole contiguous array of `bytes` bytes starting at `start` (both
+    // wave-uniform): if whole_run() holds, the fence maps the array to one contiguous
+    // range, so every tile of it is whole and scalar_fence(tile start) + lane offset is the
+    // fenced address of each access inside the array.  A kernel tests its streams once
+    // and then runs a loop that has no per-lane fence on them at all.
+    __device__ __forceinline__ bool whole_run(uint64_t start, uint64_t bytes) const
+    {
+        if constexpr (V == V_NONE || V == V_BUF) return true;       // V_BUF: offsets wrap at 2^32 by definition
+        else if constexpr (V == V_CHECK) return inside_run(start, bytes);
+        else if constexpr (V == V_MOD) return bytes <= mask && address<1>(start) - base <= mask - bytes;
+        else return bytes <= mask + 1 && (start & mask) <= mask + 1 - bytes;
+    }
+    __device__ __forceinline__ uint64_t scalar_fence(uint64_t start) const
+    {
+        uint64_t fenced;
+        (void)tile<16>(start, fenced);
+        return fenced;
+    }
+
     // The lane's byte offset inside a tile of TILE bytes, confined below TILE by an AND
     // with a constant (one instruction per kernel, not per access).
     template <int TILE>
@@ -197,14 +216,16 @@ struct Fence {
     // offset -- does not depend on what the optimiser makes of the address
     // arithmetic.  The compiler does not count these loads: tile_wait() must stand
     // between a ld_tile16 and the first use of its result.
-    template <typename T, bool STREAM = false>
+    // OFFS: a constant byte offset inside the tile, carried by the instruction (the tile
+    // test covers every byte of the tile, so fenced + lane_off + OFFS stays inside).
+    template <typename T, bool STREAM = false, int OFFS = 0>
     __device__ __forceinline__ T ld_tile16(uint64_t fenced, uint32_t lane_off) const
     {
-        static_assert(sizeof(T) == 16, "one 16-byte vector per lane");
-        if constexpr (V == V_BUF) return buf_load<T, STREAM>((uint32_t)fenced + lane_off);
+        static_assert(sizeof(T) == 16 && OFFS >= 0 && OFFS < 4096, "one 16-byte vector per lane");
+        if constexpr (V == V_BUF) return buf_load<T, STREAM>((uint32_t)fenced + lane_off + OFFS);
         T v;
-        if constexpr (STREAM) asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "=v"(v) : "v"(lane_off), "s"(fenced) : "memory");
-        else asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(v) : "v"(lane_off), "s"(fenced) : "memory");
+        if constexpr (STREAM) asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3 nt" : "=v"(v) : "v"(lane_off), "s"(fenced), "n"(OFFS) : "memory");
+        else asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3" : "=v"(v) : "v"(lane_off), "s"(fenced), "n"(OFFS) : "memory");
         return v;
     }
 

@@ -15,8 +15,23 @@ typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
 
 constexpr int EPT = 4;   // elements per thread on the vector path
 
+// A 64-bit value that is the same in every lane of the wavefront, moved to scalar registers.
+__device__ __forceinline__ uint64_t wave_uniform(uint64_t v)
+{
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return ((uint64_t)hi << 32) | lo;
+}
+
 // Under address checking (Section 4.4) the kernels take their per-element path,
 // where every access is tested on its own and an offending logical thread stops.
+//
+// The contiguous streams of the vector path (indices, offsets, the gather's output, the
+// scatter's source) are covered by each wavefront in tiles of 1 KiB (16 bytes per lane) or
+// 2 KiB (32 bytes per lane, as two 16-byte halves).  If the fence maps each of these arrays
+// to one contiguous range (Fence::whole_run: always, unless a pointer wraps at the partition
+// end) the kernel runs its tile loop, where the streams are fenced once per tile on the
+// scalar unit and only the data-dependent accesses are fenced per lane.
 
 // ---- y[o] = alpha*x[o] + y[o], o = off[i] ---------------------------------------
 template <int V>
@@ -28,8 +43,7 @@ __global__ __launch_bounds__(1024) void k_saxpy_idx(gd_args_saxpy_idx p, FenceAr
     uint64_t done = 0;
     if (!F.CHECKED && (p.off & 15) == 0) {
         const uint64_t n4 = p.n >> 2;
-        for (uint64_t q = tid; q < n4; q += stride) {
-            const i32x4 o = F.template ld<i32x4, true>(p.off + 16 * q);
+        auto four = [&](const i32x4 o) {
             float vx[EPT], vy[EPT];
 #pragma unroll
             for (int e = 0; e < EPT; ++e) {
@@ -40,6 +54,17 @@ __global__ __launch_bounds__(1024) void k_saxpy_idx(gd_args_saxpy_idx p, FenceAr
 #pragma unroll
             for (int e = 0; e < EPT; ++e)
                 F.template st<float>(p.y + (uint64_t)((int64_t)o[e] * 4), p.alpha * vx[e] + vy[e]);
+        };
+        if (F.whole_run(p.off, 16 * n4)) {
+            const uint32_t lane16 = Fence<V>::template tile_lane_offset<1024>(16 * (threadIdx.x & 63));
+            for (uint64_t q = tid; q < n4; q += stride) {
+                const uint64_t q0 = wave_uniform(q - (threadIdx.x & 63));      // the wavefront's first vector
+                i32x4 o = F.template ld_tile16<i32x4, true>(F.scalar_fence(p.off + 16 * q0), lane16);
+                F.tile_wait(o);
+                four(o);
+            }
+        } else {
+            for (uint64_t q = tid; q < n4; q += stride) four(F.template ld<i32x4, true>(p.off + 16 * q));
         }
         done = 4 * n4;
     }
@@ -66,21 +91,46 @@ __global__ __launch_bounds__(1024) void k_gather32(gd_args_gather p, FenceArgs f
     uint64_t done = 0;
     if (!F.CHECKED && ((p.idx | p.out) & 15) == 0) {
         const uint64_t n4 = p.n >> 2;
-        for (uint64_t q = tid; q < n4; q += stride) {
-            uint64_t k[EPT];
-            if (IDX64) {
-                const u64x2 k01 = F.template ld<u64x2, true>(p.idx + 32 * q);
-                const u64x2 k23 = F.template ld<u64x2, true>(p.idx + 32 * q + 16);
-                k[0] = k01[0]; k[1] = k01[1]; k[2] = k23[0]; k[3] = k23[1];
-            } else {
-                const i32x4 k4 = F.template ld<i32x4, true>(p.idx + 16 * q);
-#pragma unroll
-                for (int e = 0; e < EPT; ++e) k[e] = (uint64_t)(int64_t)k4[e];
-            }
+        auto four = [&](const uint64_t (&k)[EPT]) {
             u32x4 v;
 #pragma unroll
             for (int e = 0; e < EPT; ++e) v[e] = F.template ld<uint32_t>(p.tab + 4 * k[e]);
-            F.template st<u32x4, true>(p.out + 16 * q, v);
+            return v;
+        };
+        if (F.whole_run(p.idx, (IDX64 ? 32 : 16) * n4) && F.whole_run(p.out, 16 * n4)) {
+            const uint32_t lane16 = Fence<V>::template tile_lane_offset<1024>(16 * (threadIdx.x & 63));
+            const uint32_t lane32 = Fence<V>::template tile_lane_offset<2048>(32 * (threadIdx.x & 63));
+            for (uint64_t q = tid; q < n4; q += stride) {
+                const uint64_t q0 = wave_uniform(q - (threadIdx.x & 63));      // the wavefront's first vector
+                uint64_t k[EPT];
+                if (IDX64) {
+                    const uint64_t t_idx = F.scalar_fence(p.idx + 32 * q0);
+                    u64x2 k01 = F.template ld_tile16<u64x2, true>(t_idx, lane32);
+                    u64x2 k23 = F.template ld_tile16<u64x2, true, 16>(t_idx, lane32);
+                    F.tile_wait(k01, k23);
+                    k[0] = k01[0]; k[1] = k01[1]; k[2] = k23[0]; k[3] = k23[1];
+                } else {
+                    i32x4 k4 = F.template ld_tile16<i32x4, true>(F.scalar_fence(p.idx + 16 * q0), lane16);
+                    F.tile_wait(k4);
+#pragma unroll
+                    for (int e = 0; e < EPT; ++e) k[e] = (uint64_t)(int64_t)k4[e];
+                }
+                F.template st_tile16<u32x4, true>(F.scalar_fence(p.out + 16 * q0), lane16, four(k));
+            }
+        } else {
+            for (uint64_t q = tid; q < n4; q += stride) {
+                uint64_t k[EPT];
+                if (IDX64) {
+                    const u64x2 k01 = F.template ld<u64x2, true>(p.idx + 32 * q);
+                    const u64x2 k23 = F.template ld<u64x2, true>(p.idx + 32 * q + 16);
+                    k[0] = k01[0]; k[1] = k01[1]; k[2] = k23[0]; k[3] = k23[1];
+                } else {
+                    const i32x4 k4 = F.template ld<i32x4, true>(p.idx + 16 * q);
+#pragma unroll
+                    for (int e = 0; e < EPT; ++e) k[e] = (uint64_t)(int64_t)k4[e];
+                }
+                F.template st<u32x4, true>(p.out + 16 * q, four(k));
+            }
         }
         done = 4 * n4;
     }
@@ -105,14 +155,30 @@ __global__ __launch_bounds__(1024) void k_scatter_f32_i64(gd_args_scatter p, Fen
     uint64_t done = 0;
     if (!F.CHECKED && ((p.idx | p.src) & 15) == 0) {
         const uint64_t n4 = p.n >> 2;
-        for (uint64_t q = tid; q < n4; q += stride) {
-            const u64x2 k01 = F.template ld<u64x2, true>(p.idx + 32 * q);
-            const u64x2 k23 = F.template ld<u64x2, true>(p.idx + 32 * q + 16);
-            const f32x4 v = F.template ld<f32x4>(p.src + 16 * q);   // measured: the hint on this stream slows the scattered stores
+        auto four = [&](const u64x2 k01, const u64x2 k23, const f32x4 v) {
             F.template st<float>(p.dst + 4 * k01[0], p.scale * v[0]);
             F.template st<float>(p.dst + 4 * k01[1], p.scale * v[1]);
             F.template st<float>(p.dst + 4 * k23[0], p.scale * v[2]);
             F.template st<float>(p.dst + 4 * k23[1], p.scale * v[3]);
+        };
+        // measured: the nontemporal hint on the source stream slows the scattered stores
+        if (F.whole_run(p.idx, 32 * n4) && F.whole_run(p.src, 16 * n4)) {
+            const uint32_t lane16 = Fence<V>::template tile_lane_offset<1024>(16 * (threadIdx.x & 63));
+            const uint32_t lane32 = Fence<V>::template tile_lane_offset<2048>(32 * (threadIdx.x & 63));
+            for (uint64_t q = tid; q < n4; q += stride) {
+                const uint64_t q0 = wave_uniform(q - (threadIdx.x & 63));      // the wavefront's first vector
+                const uint64_t t_idx = F.scalar_fence(p.idx + 32 * q0);
+                u64x2 k01 = F.template ld_tile16<u64x2, true>(t_idx, lane32);
+                u64x2 k23 = F.template ld_tile16<u64x2, true, 16>(t_idx, lane32);
+                f32x4 v = F.template ld_tile16<f32x4>(F.scalar_fence(p.src + 16 * q0), lane16);
+                F.tile_wait(k01, k23);
+                F.tile_wait(v);
+                four(k01, k23, v);
+            }
+        } else {
+            for (uint64_t q = tid; q < n4; q += stride)
+                four(F.template ld<u64x2, true>(p.idx + 32 * q), F.template ld<u64x2, true>(p.idx + 32 * q + 16),
+                     F.template ld<f32x4>(p.src + 16 * q));
         }
         done = 4 * n4;
     }

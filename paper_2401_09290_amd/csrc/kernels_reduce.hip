@@ -199,7 +199,52 @@ __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, Fenc
 
     const bool vec = ((p.x | p.y | p.g) & 15) == 0 && (p.cols & 7) == 0 &&
                      p.cols <= (uint32_t)(RMS_WG * 8 * RMS_MAX_CHUNKS);
-    if (vec) {
+    const uint64_t row_bytes = 2 * (uint64_t)p.cols;
+    if (vec && F.whole_run(xrow, row_bytes) && F.whole_run(p.g, row_bytes) && F.whole_run(yrow, row_bytes)) {
+        // The row, the gains and the output row are each mapped to one contiguous range by the
+        // fence (always, unless a pointer wraps at the partition end inside them): every wavefront
+        // covers 1 KiB tiles of them and takes the fence once per tile, on the scalar unit.
+        const uint32_t chunks = p.cols >> 3;
+        const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        const uint32_t lane16 = Fence<V>::template tile_lane_offset<1024>(16 * (threadIdx.x & 63));
+        u32x4 xv[RMS_MAX_CHUNKS], gv[RMS_MAX_CHUNKS];
+#pragma unroll
+        for (int c = 0; c < RMS_MAX_CHUNKS; ++c) {
+            const uint32_t q0 = 64 * wave + c * RMS_WG;              // the wavefront's first chunk of this round
+            if (threadIdx.x + c * RMS_WG < chunks) {
+                xv[c] = F.template ld_tile16<u32x4>(F.scalar_fence(xrow + 16 * (uint64_t)q0), lane16);
+                gv[c] = F.template ld_tile16<u32x4>(F.scalar_fence(p.g + 16 * (uint64_t)q0), lane16);
+            }
+        }
+        F.tile_wait(xv[0], xv[1]);
+        F.tile_wait(gv[0], gv[1]);
+        static_assert(RMS_MAX_CHUNKS == 2, "the waits above name two chunks");
+        float ss = 0.0f;
+#pragma unroll
+        for (int c = 0; c < RMS_MAX_CHUNKS; ++c)
+            if (threadIdx.x + c * RMS_WG < chunks) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float a = bf16_lo(xv[c][e]), b = bf16_hi(xv[c][e]);
+                    ss += a * a;
+                    ss += b * b;
+                }
+            }
+        ss = block_sum<RMS_WG / 64>(ss, lds);
+        const float inv = 1.0f / sqrtf(ss * inv_cols + p.eps);
+#pragma unroll
+        for (int c = 0; c < RMS_MAX_CHUNKS; ++c) {
+            const uint32_t q0 = 64 * wave + c * RMS_WG;
+            if (threadIdx.x + c * RMS_WG < chunks) {
+                u32x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    o[e] = pack_bf16(bf16_lo(xv[c][e]) * inv * bf16_lo(gv[c][e]),
+                                     bf16_hi(xv[c][e]) * inv * bf16_hi(gv[c][e]));
+                F.template st_tile16<u32x4>(F.scalar_fence(yrow + 16 * (uint64_t)q0), lane16, o);
+            }
+        }
+    } else if (vec) {
         const uint32_t chunks = p.cols >> 3;
         u32x4 xv[RMS_MAX_CHUNKS];
         float ss = 0.0f;

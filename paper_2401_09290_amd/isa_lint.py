@@ -78,8 +78,7 @@ def kernels_of(asm_text):
             cur = m.group(1)
             bodies[cur] = []
             continue
-        if cur and re.match(r"^\s*s_endpgm", ln):
-            bodies[cur].append(ln)
+        if cur and re.match(r"^\.Lfunc_end\d+:", ln):        # a kernel may hold several s_endpgm: its text ends here
             cur = None
             continue
         if cur is not None:
