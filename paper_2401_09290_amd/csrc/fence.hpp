@@ -191,7 +191,7 @@ struct Fence {
         if constexpr (V == V_NONE || V == V_BUF) return true;       // V_BUF: offsets wrap at 2^32 by definition
         else if constexpr (V == V_CHECK) return inside_run(start, bytes);
         else if constexpr (V == V_MOD) return bytes <= mask && address<1>(start) - base <= mask - bytes;
-        else return bytes <= mask + 1 && (start & mask) <= mask + 1 - bytes;
+        else return (((start & mask) + (bytes ? bytes - 1 : 0)) & ~mask) == 0;    // last byte's offset <= mask, in a form the scalar unit has
     }
     __device__ __forceinline__ uint64_t scalar_fence(uint64_t start) const
     {
@@ -201,7 +201,8 @@ struct Fence {
     }
 
     // The lane's byte offset inside a tile of TILE bytes, confined below TILE by an AND
-    // with a constant (one instruction per kernel, not per access).
+    // with a constant (one instruction per kernel, not per access).  Callers may pass
+    // stride * threadIdx.x: the AND also reduces it to the lane's offset in its wavefront.
     template <int TILE>
     static __device__ __forceinline__ uint32_t tile_lane_offset(uint32_t off)
     {

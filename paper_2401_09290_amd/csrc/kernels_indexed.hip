@@ -15,14 +15,6 @@ typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
 
 constexpr int EPT = 4;   // elements per thread on the vector path
 
-// A 64-bit value that is the same in every lane of the wavefront, moved to scalar registers.
-__device__ __forceinline__ uint64_t wave_uniform(uint64_t v)
-{
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return ((uint64_t)hi << 32) | lo;
-}
-
 // Under address checking (Section 4.4) the kernels take their per-element path,
 // where every access is tested on its own and an offending logical thread stops.
 //
@@ -56,9 +48,11 @@ __global__ __launch_bounds__(1024) void k_saxpy_idx(gd_args_saxpy_idx p, FenceAr
                 F.template st<float>(p.y + (uint64_t)((int64_t)o[e] * 4), p.alpha * vx[e] + vy[e]);
         };
         if (F.whole_run(p.off, 16 * n4)) {
-            const uint32_t lane16 = Fence<V>::template tile_lane_offset<1024>(16 * (threadIdx.x & 63));
-            for (uint64_t q = tid; q < n4; q += stride) {
-                const uint64_t q0 = wave_uniform(q - (threadIdx.x & 63));      // the wavefront's first vector
+            const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+            const uint32_t lane16 = Fence<V>::template tile_lane_offset<1024>(16 * threadIdx.x);
+            // q0: the wavefront's first vector (scalar registers); q: this lane's
+            for (uint64_t q0 = (uint64_t)blockIdx.x * blockDim.x + 64 * wave; q0 < n4; q0 += stride) {
+                if (q0 + (threadIdx.x & 63) >= n4) continue;
                 i32x4 o = F.template ld_tile16<i32x4, true>(F.scalar_fence(p.off + 16 * q0), lane16);
                 F.tile_wait(o);
                 four(o);
@@ -98,10 +92,12 @@ __global__ __launch_bounds__(1024) void k_gather32(gd_args_gather p, FenceArgs f
             return v;
         };
         if (F.whole_run(p.idx, (IDX64 ? 32 : 16) * n4) && F.whole_run(p.out, 16 * n4)) {
-            const uint32_t lane16 = Fence<V>::template tile_lane_offset<1024>(16 * (threadIdx.x & 63));
-            const uint32_t lane32 = Fence<V>::template tile_lane_offset<2048>(32 * (threadIdx.x & 63));
-            for (uint64_t q = tid; q < n4; q += stride) {
-                const uint64_t q0 = wave_uniform(q - (threadIdx.x & 63));      // the wavefront's first vector
+            const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+            const uint32_t lane16 = Fence<V>::template tile_lane_offset<1024>(16 * threadIdx.x);
+            const uint32_t lane32 = Fence<V>::template tile_lane_offset<2048>(32 * threadIdx.x);
+            // q0: the wavefront's first vector (scalar registers); q: this lane's
+            for (uint64_t q0 = (uint64_t)blockIdx.x * blockDim.x + 64 * wave; q0 < n4; q0 += stride) {
+                if (q0 + (threadIdx.x & 63) >= n4) continue;
                 uint64_t k[EPT];
                 if (IDX64) {
                     const uint64_t t_idx = F.scalar_fence(p.idx + 32 * q0);
@@ -163,10 +159,12 @@ __global__ __launch_bounds__(1024) void k_scatter_f32_i64(gd_args_scatter p, Fen
         };
         // measured: the nontemporal hint on the source stream slows the scattered stores
         if (F.whole_run(p.idx, 32 * n4) && F.whole_run(p.src, 16 * n4)) {
-            const uint32_t lane16 = Fence<V>::template tile_lane_offset<1024>(16 * (threadIdx.x & 63));
-            const uint32_t lane32 = Fence<V>::template tile_lane_offset<2048>(32 * (threadIdx.x & 63));
-            for (uint64_t q = tid; q < n4; q += stride) {
-                const uint64_t q0 = wave_uniform(q - (threadIdx.x & 63));      // the wavefront's first vector
+            const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+            const uint32_t lane16 = Fence<V>::template tile_lane_offset<1024>(16 * threadIdx.x);
+            const uint32_t lane32 = Fence<V>::template tile_lane_offset<2048>(32 * threadIdx.x);
+            // q0: the wavefront's first vector (scalar registers); q: this lane's
+            for (uint64_t q0 = (uint64_t)blockIdx.x * blockDim.x + 64 * wave; q0 < n4; q0 += stride) {
+                if (q0 + (threadIdx.x & 63) >= n4) continue;
                 const uint64_t t_idx = F.scalar_fence(p.idx + 32 * q0);
                 u64x2 k01 = F.template ld_tile16<u64x2, true>(t_idx, lane32);
                 u64x2 k23 = F.template ld_tile16<u64x2, true, 16>(t_idx, lane32);

@@ -62,7 +62,7 @@ __global__ __launch_bounds__(WG) void k_sum_partial(gd_args_sum p, FenceArgs fa)
         const uint64_t tile = (uint64_t)WG * SUM_UNROLL;
         f32x4 a4 = {0.0f, 0.0f, 0.0f, 0.0f};
         const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        const uint32_t lane_off = Fence<V>::template tile_lane_offset<SUM_TILE>(16 * (threadIdx.x & 63));
+        const uint32_t lane_off = Fence<V>::template tile_lane_offset<SUM_TILE>(16 * threadIdx.x);
         for (uint64_t t0 = blockIdx.x * tile; t0 < n4; t0 += gridDim.x * tile) {
             const uint64_t i0 = t0 + threadIdx.x;
             // Full tiles: each of a wavefront's SUM_UNROLL accesses covers one contiguous 1 KiB,
@@ -206,7 +206,7 @@ __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, Fenc
         // covers 1 KiB tiles of them and takes the fence once per tile, on the scalar unit.
         const uint32_t chunks = p.cols >> 3;
         const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        const uint32_t lane16 = Fence<V>::template tile_lane_offset<1024>(16 * (threadIdx.x & 63));
+        const uint32_t lane16 = Fence<V>::template tile_lane_offset<1024>(16 * threadIdx.x);
         u32x4 xv[RMS_MAX_CHUNKS], gv[RMS_MAX_CHUNKS];
 #pragma unroll
         for (int c = 0; c < RMS_MAX_CHUNKS; ++c) {

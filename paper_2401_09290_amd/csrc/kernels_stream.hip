@@ -91,7 +91,7 @@ __global__ __launch_bounds__(1024) void k_stream(uint64_t pa, uint64_t pb, uint6
     if ((ptr_bits & 15) == 0) {
         const uint64_t n4 = n >> 2;
         const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        const uint32_t lane_off = Fence<V>::template tile_lane_offset<STREAM_TILE>(16 * (threadIdx.x & 63));
+        const uint32_t lane_off = Fence<V>::template tile_lane_offset<STREAM_TILE>(16 * threadIdx.x);
         for (uint64_t t0 = (uint64_t)blockIdx.x * blockDim.x; t0 < n4; t0 += (uint64_t)gridDim.x * blockDim.x) {
             const uint64_t w0 = t0 + 64 * wave;                  // first vector of this wavefront's tile
             const uint64_t i = w0 + (threadIdx.x & 63);
