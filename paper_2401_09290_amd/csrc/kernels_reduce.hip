@@ -63,21 +63,16 @@ __global__ __launch_bounds__(WG) void k_sum_partial(gd_args_sum p, FenceArgs fa)
         f32x4 a4 = {0.0f, 0.0f, 0.0f, 0.0f};
         const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         const uint32_t lane_off = Fence<V>::template tile_lane_offset<SUM_TILE>(16 * threadIdx.x);
+        const bool whole = F.whole_run(p.in, 16 * n4);     // the input is mapped to one contiguous range (wholly inside, if checked)
         for (uint64_t t0 = blockIdx.x * tile; t0 < n4; t0 += gridDim.x * tile) {
             const uint64_t i0 = t0 + threadIdx.x;
-            // Full tiles: each of a wavefront's SUM_UNROLL accesses covers one contiguous 1 KiB,
-            // fenced (or checked) once on the scalar unit.
-            uint64_t tf[SUM_UNROLL];
-            uint64_t split = t0 + tile <= n4 ? 0 : 1;
-            if (split == 0) {
-#pragma unroll
-                for (int u = 0; u < SUM_UNROLL; ++u)
-                    split |= F.template tile<SUM_TILE>(p.in + 16 * (t0 + (uint64_t)u * WG + 64 * wave), tf[u]);
-            }
-            if (split == 0) {
+            if (whole && t0 + tile <= n4) {
+                // Full tiles: each of a wavefront's SUM_UNROLL accesses covers one contiguous 1 KiB,
+                // fenced once on the scalar unit.
                 f32x4 v[SUM_UNROLL];
 #pragma unroll
-                for (int u = 0; u < SUM_UNROLL; ++u) v[u] = F.template ld_tile16<f32x4, true>(tf[u], lane_off);
+                for (int u = 0; u < SUM_UNROLL; ++u)
+                    v[u] = F.template ld_tile16<f32x4, true>(F.scalar_fence(p.in + 16 * (t0 + (uint64_t)u * WG + 64 * wave)), lane_off);
                 static_assert(SUM_UNROLL == 4, "the wait below names four vectors");
                 F.tile_wait(v[0], v[1]);
                 F.tile_wait(v[2], v[3]);

@@ -59,10 +59,11 @@ __global__ __launch_bounds__(1024) void k_fence_addrs(gd_args_fence_addrs p, Fen
 // OP 0: a = b.  OP 1: a = b + s*c (one fused multiply-add per element).
 // Vector path when all pointers are 16-byte aligned (then a 16-byte access equals
 // four fenced 4-byte accesses); otherwise every element is accessed on its own.
-// On the vector path a wavefront covers one contiguous 1 KiB tile of each array, so
-// the fence is taken once per tile and array on the scalar unit (Fence::tile) and
-// costs no vector instruction; a tile that the fence would split (a pointer that
-// wraps at the partition end inside it) is fenced per lane instead.
+// On the vector path a wavefront covers one contiguous 1 KiB tile of each array.  If the
+// fence maps each array to one contiguous range (Fence::whole_run, tested once per launch:
+// always, unless a pointer wraps at the partition end inside its array) the fence is
+// taken once per tile and array on the scalar unit and costs no vector instruction;
+// otherwise every vector is fenced per lane.
 // Under address checking a vector whose three 16-byte accesses are not all inside
 // the partition is redone element by element, so that exactly the offending
 // logical threads stop.
@@ -91,29 +92,26 @@ __global__ __launch_bounds__(1024) void k_stream(uint64_t pa, uint64_t pb, uint6
     if ((ptr_bits & 15) == 0) {
         const uint64_t n4 = n >> 2;
         const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        const uint32_t lane_off = Fence<V>::template tile_lane_offset<STREAM_TILE>(16 * threadIdx.x);
-        for (uint64_t t0 = (uint64_t)blockIdx.x * blockDim.x; t0 < n4; t0 += (uint64_t)gridDim.x * blockDim.x) {
-            const uint64_t w0 = t0 + 64 * wave;                  // first vector of this wavefront's tile
-            const uint64_t i = w0 + (threadIdx.x & 63);
-            uint64_t ta, tb, tc = 0;
-            uint64_t split = F.template tile<STREAM_TILE>(pb + 16 * w0, tb);
-            if (OP) split |= F.template tile<STREAM_TILE>(pc + 16 * w0, tc);
-            split |= F.template tile<STREAM_TILE>(pa + 16 * w0, ta);
-            if (split == 0) {
-                if (i < n4) {
-                    f32x4 vb = F.template ld_tile16<f32x4, NT>(tb, lane_off);
-                    if (OP) {
-                        f32x4 vc = F.template ld_tile16<f32x4, NT>(tc, lane_off);
-                        F.tile_wait(vb, vc);
-                        vb = vb + s * vc;
-                    } else {
-                        F.tile_wait(vb);
-                    }
-                    F.template st_tile16<f32x4, NT>(ta, lane_off, vb);
+        const uint64_t step = (uint64_t)gridDim.x * blockDim.x;
+        if (F.whole_run(pb, 16 * n4) && (!OP || F.whole_run(pc, 16 * n4)) && F.whole_run(pa, 16 * n4)) {
+            // every array is mapped to one contiguous range: scalar fence per wavefront tile, no per-lane fence
+            const uint32_t lane_off = Fence<V>::template tile_lane_offset<STREAM_TILE>(16 * threadIdx.x);
+            for (uint64_t w0 = (uint64_t)blockIdx.x * blockDim.x + 64 * wave; w0 < n4; w0 += step) {   // w0: the tile's first vector
+                if (w0 + (threadIdx.x & 63) >= n4) continue;
+                f32x4 vb = F.template ld_tile16<f32x4, NT>(F.scalar_fence(pb + 16 * w0), lane_off);
+                if (OP) {
+                    f32x4 vc = F.template ld_tile16<f32x4, NT>(F.scalar_fence(pc + 16 * w0), lane_off);
+                    F.tile_wait(vb, vc);
+                    vb = vb + s * vc;
+                } else {
+                    F.tile_wait(vb);
                 }
-            } else if (i < n4) {
-                uint64_t i = w0 + (threadIdx.x & 63);
-                asm volatile("" : "+v"(i));          // keeps this path's address arithmetic inside the branch
+                F.template st_tile16<f32x4, NT>(F.scalar_fence(pa + 16 * w0), lane_off, vb);
+            }
+        } else {
+            // a pointer wraps at the partition end inside its array (or, under address checking, an array is
+            // not wholly inside): every vector is fenced (checked) per lane
+            for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += step) {
                 if (F.CHECKED &&
                     !(F.template inside<16>(pb + 16 * i) && (!OP || F.template inside<16>(pc + 16 * i)) &&
                       F.template inside<16>(pa + 16 * i))) {
