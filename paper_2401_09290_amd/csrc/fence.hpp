@@ -182,10 +182,12 @@ struct Fence {
     }
 
     // The same for a whole contiguous array of `bytes` bytes starting at `start` (both
-    // wave-uniform): if whole_run() holds, the fence maps the array to one contiguous
-    // range, so every tile of it is whole and scalar_fence(tile start) + lane offset is the
-    // fenced address of each access inside the array.  A kernel tests its streams once
-    // and then runs a loop that has no per-lane fence on them at all.
+    // wave-uniform): if whole_run() holds, the fence maps the array to ONE contiguous
+    // range, i.e. fence(start + d) == fence(start) + d for every d < bytes, exactly.  A
+    // kernel tests its streams once, fences each array's first byte once
+    // (scalar_fence(start), on the scalar unit), and then addresses the array as
+    // "fenced start + offset" like a native kernel: no fence instruction is left in
+    // its loop, for any rule.
     __device__ __forceinline__ bool whole_run(uint64_t start, uint64_t bytes) const
     {
         if constexpr (V == V_NONE || V == V_BUF) return true;       // V_BUF: offsets wrap at 2^32 by definition

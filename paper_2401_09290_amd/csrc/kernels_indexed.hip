@@ -22,8 +22,9 @@ constexpr int EPT = 4;   // elements per thread on the vector path
 // scatter's source) are covered by each wavefront in tiles of 1 KiB (16 bytes per lane) or
 // 2 KiB (32 bytes per lane, as two 16-byte halves).  If the fence maps each of these arrays
 // to one contiguous range (Fence::whole_run: always, unless a pointer wraps at the partition
-// end) the kernel runs its tile loop, where the streams are fenced once per tile on the
-// scalar unit and only the data-dependent accesses are fenced per lane.
+// end) the kernel fences each stream's first byte once, on the scalar unit, and runs its
+// tile loop, which addresses the streams as "fenced start + offset" like a native kernel;
+// only the data-dependent accesses are fenced per lane.
 
 // ---- y[o] = alpha*x[o] + y[o], o = off[i] ---------------------------------------
 template <int V>
@@ -50,10 +51,11 @@ __global__ __launch_bounds__(1024) void k_saxpy_idx(gd_args_saxpy_idx p, FenceAr
         if (F.whole_run(p.off, 16 * n4)) {
             const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
             const uint32_t lane16 = Fence<V>::template tile_lane_offset<1024>(16 * threadIdx.x);
+            const uint64_t f_off = F.scalar_fence(p.off);                      // fenced first byte of the offsets
             // q0: the wavefront's first vector (scalar registers); q: this lane's
             for (uint64_t q0 = (uint64_t)blockIdx.x * blockDim.x + 64 * wave; q0 < n4; q0 += stride) {
                 if (q0 + (threadIdx.x & 63) >= n4) continue;
-                i32x4 o = F.template ld_tile16<i32x4, true>(F.scalar_fence(p.off + 16 * q0), lane16);
+                i32x4 o = F.template ld_tile16<i32x4, true>(f_off + 16 * q0, lane16);
                 F.tile_wait(o);
                 four(o);
             }
@@ -95,23 +97,24 @@ __global__ __launch_bounds__(1024) void k_gather32(gd_args_gather p, FenceArgs f
             const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
             const uint32_t lane16 = Fence<V>::template tile_lane_offset<1024>(16 * threadIdx.x);
             const uint32_t lane32 = Fence<V>::template tile_lane_offset<2048>(32 * threadIdx.x);
+            const uint64_t f_idx = F.scalar_fence(p.idx), f_out = F.scalar_fence(p.out);   // fenced first bytes of the streams
             // q0: the wavefront's first vector (scalar registers); q: this lane's
             for (uint64_t q0 = (uint64_t)blockIdx.x * blockDim.x + 64 * wave; q0 < n4; q0 += stride) {
                 if (q0 + (threadIdx.x & 63) >= n4) continue;
                 uint64_t k[EPT];
                 if (IDX64) {
-                    const uint64_t t_idx = F.scalar_fence(p.idx + 32 * q0);
+                    const uint64_t t_idx = f_idx + 32 * q0;
                     u64x2 k01 = F.template ld_tile16<u64x2, true>(t_idx, lane32);
                     u64x2 k23 = F.template ld_tile16<u64x2, true, 16>(t_idx, lane32);
                     F.tile_wait(k01, k23);
                     k[0] = k01[0]; k[1] = k01[1]; k[2] = k23[0]; k[3] = k23[1];
                 } else {
-                    i32x4 k4 = F.template ld_tile16<i32x4, true>(F.scalar_fence(p.idx + 16 * q0), lane16);
+                    i32x4 k4 = F.template ld_tile16<i32x4, true>(f_idx + 16 * q0, lane16);
                     F.tile_wait(k4);
 #pragma unroll
                     for (int e = 0; e < EPT; ++e) k[e] = (uint64_t)(int64_t)k4[e];
                 }
-                F.template st_tile16<u32x4, true>(F.scalar_fence(p.out + 16 * q0), lane16, four(k));
+                F.template st_tile16<u32x4, true>(f_out + 16 * q0, lane16, four(k));
             }
         } else {
             for (uint64_t q = tid; q < n4; q += stride) {
@@ -162,13 +165,14 @@ __global__ __launch_bounds__(1024) void k_scatter_f32_i64(gd_args_scatter p, Fen
             const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
             const uint32_t lane16 = Fence<V>::template tile_lane_offset<1024>(16 * threadIdx.x);
             const uint32_t lane32 = Fence<V>::template tile_lane_offset<2048>(32 * threadIdx.x);
+            const uint64_t f_idx = F.scalar_fence(p.idx), f_src = F.scalar_fence(p.src);   // fenced first bytes of the streams
             // q0: the wavefront's first vector (scalar registers); q: this lane's
             for (uint64_t q0 = (uint64_t)blockIdx.x * blockDim.x + 64 * wave; q0 < n4; q0 += stride) {
                 if (q0 + (threadIdx.x & 63) >= n4) continue;
-                const uint64_t t_idx = F.scalar_fence(p.idx + 32 * q0);
+                const uint64_t t_idx = f_idx + 32 * q0;
                 u64x2 k01 = F.template ld_tile16<u64x2, true>(t_idx, lane32);
                 u64x2 k23 = F.template ld_tile16<u64x2, true, 16>(t_idx, lane32);
-                f32x4 v = F.template ld_tile16<f32x4>(F.scalar_fence(p.src + 16 * q0), lane16);
+                f32x4 v = F.template ld_tile16<f32x4>(f_src + 16 * q0, lane16);
                 F.tile_wait(k01, k23);
                 F.tile_wait(v);
                 four(k01, k23, v);

@@ -64,15 +64,16 @@ __global__ __launch_bounds__(WG) void k_sum_partial(gd_args_sum p, FenceArgs fa)
         const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         const uint32_t lane_off = Fence<V>::template tile_lane_offset<SUM_TILE>(16 * threadIdx.x);
         const bool whole = F.whole_run(p.in, 16 * n4);     // the input is mapped to one contiguous range (wholly inside, if checked)
+        const uint64_t f_in = F.scalar_fence(p.in);        // fenced first byte; used only if `whole`
         for (uint64_t t0 = blockIdx.x * tile; t0 < n4; t0 += gridDim.x * tile) {
             const uint64_t i0 = t0 + threadIdx.x;
             if (whole && t0 + tile <= n4) {
-                // Full tiles: each of a wavefront's SUM_UNROLL accesses covers one contiguous 1 KiB,
-                // fenced once on the scalar unit.
+                // Full tiles: each of a wavefront's SUM_UNROLL accesses covers one contiguous 1 KiB at
+                // "fenced start + offset".
                 f32x4 v[SUM_UNROLL];
 #pragma unroll
                 for (int u = 0; u < SUM_UNROLL; ++u)
-                    v[u] = F.template ld_tile16<f32x4, true>(F.scalar_fence(p.in + 16 * (t0 + (uint64_t)u * WG + 64 * wave)), lane_off);
+                    v[u] = F.template ld_tile16<f32x4, true>(f_in + 16 * (t0 + (uint64_t)u * WG + 64 * wave), lane_off);
                 static_assert(SUM_UNROLL == 4, "the wait below names four vectors");
                 F.tile_wait(v[0], v[1]);
                 F.tile_wait(v[2], v[3]);
@@ -197,18 +198,20 @@ __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, Fenc
     const uint64_t row_bytes = 2 * (uint64_t)p.cols;
     if (vec && F.whole_run(xrow, row_bytes) && F.whole_run(p.g, row_bytes) && F.whole_run(yrow, row_bytes)) {
         // The row, the gains and the output row are each mapped to one contiguous range by the
-        // fence (always, unless a pointer wraps at the partition end inside them): every wavefront
-        // covers 1 KiB tiles of them and takes the fence once per tile, on the scalar unit.
+        // fence (always, unless a pointer wraps at the partition end inside them): their first
+        // bytes are fenced once, on the scalar unit, and every wavefront covers 1 KiB tiles at
+        // "fenced start + offset".
         const uint32_t chunks = p.cols >> 3;
         const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         const uint32_t lane16 = Fence<V>::template tile_lane_offset<1024>(16 * threadIdx.x);
+        const uint64_t fx = F.scalar_fence(xrow), fg = F.scalar_fence(p.g), fy = F.scalar_fence(yrow);
         u32x4 xv[RMS_MAX_CHUNKS], gv[RMS_MAX_CHUNKS];
 #pragma unroll
         for (int c = 0; c < RMS_MAX_CHUNKS; ++c) {
             const uint32_t q0 = 64 * wave + c * RMS_WG;              // the wavefront's first chunk of this round
             if (threadIdx.x + c * RMS_WG < chunks) {
-                xv[c] = F.template ld_tile16<u32x4>(F.scalar_fence(xrow + 16 * (uint64_t)q0), lane16);
-                gv[c] = F.template ld_tile16<u32x4>(F.scalar_fence(p.g + 16 * (uint64_t)q0), lane16);
+                xv[c] = F.template ld_tile16<u32x4>(fx + 16 * (uint64_t)q0, lane16);
+                gv[c] = F.template ld_tile16<u32x4>(fg + 16 * (uint64_t)q0, lane16);
             }
         }
         F.tile_wait(xv[0], xv[1]);
@@ -236,7 +239,7 @@ __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, Fenc
                 for (int e = 0; e < 4; ++e)
                     o[e] = pack_bf16(bf16_lo(xv[c][e]) * inv * bf16_lo(gv[c][e]),
                                      bf16_hi(xv[c][e]) * inv * bf16_hi(gv[c][e]));
-                F.template st_tile16<u32x4>(F.scalar_fence(yrow + 16 * (uint64_t)q0), lane16, o);
+                F.template st_tile16<u32x4>(fy + 16 * (uint64_t)q0, lane16, o);
             }
         }
     } else if (vec) {

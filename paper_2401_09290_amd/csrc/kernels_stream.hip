@@ -61,9 +61,9 @@ __global__ __launch_bounds__(1024) void k_fence_addrs(gd_args_fence_addrs p, Fen
 // four fenced 4-byte accesses); otherwise every element is accessed on its own.
 // On the vector path a wavefront covers one contiguous 1 KiB tile of each array.  If the
 // fence maps each array to one contiguous range (Fence::whole_run, tested once per launch:
-// always, unless a pointer wraps at the partition end inside its array) the fence is
-// taken once per tile and array on the scalar unit and costs no vector instruction;
-// otherwise every vector is fenced per lane.
+// always, unless a pointer wraps at the partition end inside its array) each array's first
+// byte is fenced once, on the scalar unit, and the loop addresses "fenced start + offset"
+// with the instructions of the native kernel; otherwise every vector is fenced per lane.
 // Under address checking a vector whose three 16-byte accesses are not all inside
 // the partition is redone element by element, so that exactly the offending
 // logical threads stop.
@@ -76,6 +76,12 @@ __global__ __launch_bounds__(1024) void k_stream(uint64_t pa, uint64_t pb, uint6
                                                  float s, uint32_t repeat, FenceArgs fa)
 {
     const Fence<V> F(fa);
+    // Launch-invariant: are all pointers 16-byte aligned, does the fence map each array to one
+    // contiguous range, and where does each array's first byte go.
+    const uint64_t ptr_bits = OP ? (pa | pb | pc) : (pa | pb);
+    const uint64_t n4 = n >> 2;
+    const bool whole = F.whole_run(pb, 16 * n4) && (!OP || F.whole_run(pc, 16 * n4)) && F.whole_run(pa, 16 * n4);
+    const uint64_t fb = F.scalar_fence(pb), fc = OP ? F.scalar_fence(pc) : 0, fa_ = F.scalar_fence(pa);   // used only if `whole`
   for (uint32_t rep = 0; rep < repeat; ++rep) {      // repeat > 1: the cache-resident regime in one launch
     // one logical thread: accesses in the order load b, load c, store a
     auto element = [&](uint64_t i) {
@@ -88,25 +94,23 @@ __global__ __launch_bounds__(1024) void k_stream(uint64_t pa, uint64_t pb, uint6
         if (!F.template inside<4>(pa + 4 * i)) { F.fault(); return; }
         F.template st<float>(pa + 4 * i, r);
     };
-    const uint64_t ptr_bits = OP ? (pa | pb | pc) : (pa | pb);
     if ((ptr_bits & 15) == 0) {
-        const uint64_t n4 = n >> 2;
         const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         const uint64_t step = (uint64_t)gridDim.x * blockDim.x;
-        if (F.whole_run(pb, 16 * n4) && (!OP || F.whole_run(pc, 16 * n4)) && F.whole_run(pa, 16 * n4)) {
-            // every array is mapped to one contiguous range: scalar fence per wavefront tile, no per-lane fence
+        if (whole) {
+            // every array is mapped to one contiguous range and its first byte is fenced: address it like a native kernel
             const uint32_t lane_off = Fence<V>::template tile_lane_offset<STREAM_TILE>(16 * threadIdx.x);
             for (uint64_t w0 = (uint64_t)blockIdx.x * blockDim.x + 64 * wave; w0 < n4; w0 += step) {   // w0: the tile's first vector
                 if (w0 + (threadIdx.x & 63) >= n4) continue;
-                f32x4 vb = F.template ld_tile16<f32x4, NT>(F.scalar_fence(pb + 16 * w0), lane_off);
+                f32x4 vb = F.template ld_tile16<f32x4, NT>(fb + 16 * w0, lane_off);
                 if (OP) {
-                    f32x4 vc = F.template ld_tile16<f32x4, NT>(F.scalar_fence(pc + 16 * w0), lane_off);
+                    f32x4 vc = F.template ld_tile16<f32x4, NT>(fc + 16 * w0, lane_off);
                     F.tile_wait(vb, vc);
                     vb = vb + s * vc;
                 } else {
                     F.tile_wait(vb);
                 }
-                F.template st_tile16<f32x4, NT>(F.scalar_fence(pa + 16 * w0), lane_off, vb);
+                F.template st_tile16<f32x4, NT>(fa_ + 16 * w0, lane_off, vb);
             }
         } else {
             // a pointer wraps at the partition end inside its array (or, under address checking, an array is

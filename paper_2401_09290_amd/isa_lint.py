@@ -16,9 +16,10 @@ the same guarantee is checked after the fact, on the assembly text produced by
 * in every kernel built with the 64-bit fence (variant 2) each global access
   uses a 64-bit VGPR address whose high word was last written by ``v_or_b32``
   with an SGPR operand (the OR with the partition base, after the AND);
-* in both, an access through the scalar tile fence uses an SGPR pair last written
-  by the fence's ``s_or_b64`` as its base and a lane offset confined by an AND with a
-  constant below 4096 (or zero) as its offset;
+* in both, an access through the scalar fence of a contiguous array uses as its base an
+  SGPR pair that is the fence's ``s_or_b64`` result, or that result plus an offset
+  (scalar add with carry), and as its offset a lane offset confined by an AND with a
+  constant below 4096 (or zero);
 * in every kernel built for the hardware-checked rule (variant 5) all accesses to tenant
   memory are buffer instructions with a VGPR offset and a zero SGPR offset (the range
   check covers exactly that offset), and there is no global_* access;
@@ -150,25 +151,29 @@ class Flow:
             if not op.startswith(("s_branch", "s_endpgm")) and i + 1 < n:
                 self.preds[i + 1].append(i)
 
-    def reaching(self, idx, kind, reg):
-        """The instructions (stripped text) whose write of `reg` can reach instruction idx;
-        'ENTRY' stands for the value the register holds when the kernel starts."""
+    def reaching_at(self, idx, kind, reg):
+        """Indices of the instructions whose write of `reg` can reach instruction idx; -1 stands for
+        the value the register holds when the kernel starts."""
         found, seen, stack = set(), set(), list(self.preds[idx])
         if not stack:
-            found.add("ENTRY")
+            found.add(-1)
         while stack:
             j = stack.pop()
             if j in seen:
                 continue
             seen.add(j)
             if any(k == kind and lo <= reg <= hi for (k, lo, hi) in dests(self.body[j])):
-                found.add(self.body[j].strip())
+                found.add(j)
                 continue
             if self.preds[j]:
                 stack.extend(self.preds[j])
             else:
-                found.add("ENTRY")
+                found.add(-1)
         return found
+
+    def reaching(self, idx, kind, reg):
+        """The same as instruction texts ('ENTRY' for the kernel's start)."""
+        return {"ENTRY" if j < 0 else self.body[j].strip() for j in self.reaching_at(idx, kind, reg)}
 
 
 FENCE_AND32 = re.compile(r"^v_and_b32\w*\s+v\d+,\s*(s\d+,\s*v\d+|v\d+,\s*s\d+)$")
@@ -177,6 +182,39 @@ TILE_OR64 = re.compile(r"^s_or_b64\s+s\[\d+:\d+\],\s*s\[\d+:\d+\],\s*s\[\d+:\d+\
 LANE_CONFINED = re.compile(r"^v_and_b32\w*\s+v\d+,\s*(0x[0-9a-f]+|\d+),\s*v\d+$")
 ZERO_V = re.compile(r"^v_mov_b32\w*\s+v\d+,\s*0$")
 ZERO_S = re.compile(r"^s_mov_b(32|64)\s+s(\d+|\[\d+:\d+\]),\s*0$")
+
+
+SCALAR_ADD = re.compile(r"^s_addc?_u32\s+s(\d+),\s*(s\d+|\S+),\s*(s\d+|\S+)$")
+
+
+def fenced_scalar(flow, idx, sreg, depth=0, seen=None):
+    """Is the SGPR `sreg`, as read by instruction idx, a fenced address word?  Every definition that
+    reaches the read must be the fence's s_or_b64, the zero a never-taken path initialises it with, or a
+    scalar add one of whose operands is such a word (fenced start + offset: the carry chain of a 64-bit
+    add).  Returns (ok, saw_fence)."""
+    seen = set() if seen is None else seen
+    ok, saw = True, False
+    for j in flow.reaching_at(idx, "s", sreg):
+        if j < 0:
+            return False, saw
+        text = flow.body[j].strip()
+        if TILE_OR64.match(text):
+            saw = True
+        elif ZERO_S.match(text):
+            pass
+        elif SCALAR_ADD.match(text) and depth < 6:
+            if (j, sreg) in seen:
+                saw = True                                # a loop-carried add: judged where the chain was entered
+                continue
+            seen.add((j, sreg))
+            srcs = [o for o in SCALAR_ADD.match(text).groups()[1:] if re.match(r"^s\d+$", o)]
+            sub = [fenced_scalar(flow, j, int(o[1:]), depth + 1, seen) for o in srcs]
+            if not any(k and f for k, f in sub):
+                return False, saw
+            saw = True
+        else:
+            return False, saw
+    return ok, saw
 
 
 def lint_kernel(name, pretty, body, variant):
@@ -229,8 +267,9 @@ def lint_kernel(name, pretty, body, variant):
         # below the tile size by an AND with a constant, or zero.
         if sb and sb[0] == "s" and va and va[0] == "v" and va[1] == va[2]:
             bdefs = flow.reaching(i, "s", sb[2])
-            if any(TILE_OR64.match(d) for d in bdefs):
-                if not all(TILE_OR64.match(d) or ZERO_S.match(d) for d in bdefs):
+            ok_hi, saw_fence = fenced_scalar(flow, i, sb[2])
+            if saw_fence or any(TILE_OR64.match(d) for d in bdefs):
+                if not (ok_hi and fenced_scalar(flow, i, sb[1])[0]):
                     problems.append(f"{pretty}: tile access `{what}`: base also defined by {sorted(bdefs)}")
                 for d in flow.reaching(i, "v", va[1]):
                     lit = LANE_CONFINED.match(d)
