@@ -305,3 +305,19 @@ def test_launch_argument_errors_need_no_gpu():
         gd.gd_launch_fenced(pool, 0, gd.GD_K_COPY, gd.gd_args_copy(1 << 40, (1 << 40) + 4096, 16), mode=gd.GD_FENCE_HWCHECK)
     assert e.value.status == gd.GD_ESHAPE
     gd.gd_pool_destroy(pool)
+
+
+def test_measurement_aids_refuse_bad_arguments_without_a_gpu():
+    """gd_probe_mfma and gd_probe_gather_policy validate their arguments before any launch."""
+    for args in ((0, 4096, 1, 1), (4096, 0, 1, 1), (4096 + 8, 8192, 1, 1), (4096, 8192 + 2, 1, 1), (4096, 8192, 0, 1),
+                 (4096, 8192, 1 << 20, 1)):
+        with pytest.raises(gd.GuardianError) as e:
+            gd.gd_probe_mfma(*args)
+        assert e.value.status == gd.GD_EINVAL
+    for args in ((0, 4096, 8192, 16, 0), (4096, 0, 8192, 16, 0), (4096, 8192, 0, 16, 0), (4096 + 4, 8192, 16384, 16, 0),
+                 (4096, 8192 + 2, 16384, 16, 0), (4096, 8192, 16384 + 8, 16, 0), (4096, 8192, 16384, 18, 0),
+                 (4096, 8192, 16384, 16, 8)):
+        with pytest.raises(gd.GuardianError) as e:
+            gd.gd_probe_gather_policy(*args)
+        assert e.value.status == gd.GD_EINVAL
+    gd.gd_probe_gather_policy(4096, 8192, 16384, 0, 3)          # nothing to do: no launch, no GPU needed

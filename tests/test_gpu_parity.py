@@ -206,16 +206,17 @@ def test_triad_repeat_field_gives_the_single_pass_image(mode, repeat):
 
 
 @pytest.mark.parametrize("mode", [gd.GD_FENCE_BITWISE, gd.GD_FENCE_MODULO])
-def test_copy_triad_with_a_wavefront_tile_split_by_the_partition_end(rig2, mode):
-    """16-byte aligned arrays that run over the end of the partition in the middle of a wavefront's
-    1 KiB tile: the scalar fence of that tile does not apply, its lanes are fenced one by one, and
-    the whole image still equals the oracle's (tiles before and after take the scalar path)."""
+def test_copy_triad_with_arrays_split_by_the_partition_end(rig2, mode):
+    """16-byte aligned arrays that run over the end of the partition (at a tile boundary, inside a tile,
+    inside a vector's neighbourhood) or end exactly there: the fence maps a wrapping array to two ranges,
+    so the kernel's test of the whole array fails and every vector is fenced per lane; an array that ends
+    at the partition's last byte still takes the per-array fence.  The image equals the oracle's either way."""
     r = rig2
     omode = ok.MODE_BITWISE if mode == gd.GD_FENCE_BITWISE else ok.MODE_MODULO
     base, size = r.row(1)
     g = si.rng(0, 44)
     n = 6000
-    for cut in (16, 1024 - 16, 400 * 4, 1024 * 3 + 528):          # bytes of the array in front of the partition end
+    for cut in (16, 1024 - 16, 400 * 4, 1024 * 3 + 528, 4 * n):   # bytes of the array in front of the partition end (4n: it ends exactly there)
         lo = r.alloc(1, 64 * KiB)                                  # keeps the partition's first bytes free of inputs
         b, c = r.alloc(1, 4 * n), r.alloc(1, 4 * n)
         r.upload(1, b, si.uniform_f32(g, n))
@@ -239,7 +240,7 @@ def test_copy_triad_with_a_wavefront_tile_split_by_the_partition_end(rig2, mode)
             r.free(1, p)
 
 
-def test_triad_tile_split_on_a_partition_larger_than_4gib():
+def test_triad_array_split_on_a_partition_larger_than_4gib():
     """The same on the 64-bit rule (8 GiB partition): values from the oracle on the in-bounds twin of the
     launch, locations from the oracle's fence."""
     r = Rig([8 * GiB], fill=None, simulate=False)
@@ -705,3 +706,36 @@ def test_recarve_mid_run_leaves_other_tenants_untouched():
             assert np.array_equal(r.download(dst, np.float32, n), r.sim.view(src, np.float32, n))
     finally:
         r.close()
+
+
+# ---------------------------------------------------------------------------
+# the two measurement aids (no tenant, no fence): they compute what they say
+# ---------------------------------------------------------------------------
+
+def test_gather_policy_probe_is_a_gather_for_every_policy():
+    g = si.rng(0, 60)
+    tab_n, n = 1 << 20, (1 << 18) + 4
+    tab = torch.from_numpy(g.integers(0, 1 << 32, size=tab_n, dtype=np.uint64).astype(np.uint32).view(np.int32)).cuda()
+    idx_h = g.integers(0, tab_n, size=n, dtype=np.int64)
+    idx = torch.from_numpy(idx_h).cuda()
+    want = tab.cpu().numpy()[idx_h]
+    for policy in range(8):
+        out = torch.zeros(n, dtype=torch.int32, device="cuda")
+        gd.gd_probe_gather_policy(out.data_ptr(), tab.data_ptr(), idx.data_ptr(), n, policy)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), want), policy
+
+
+def test_mfma_probe_multiplies_what_it_is_given():
+    """All operands 1.0 (bf16 0x3F80): every accumulator of the 16x16x32 tiles grows by 32 per instruction and
+    the kernel reports acc[0][0][0] + acc[7][7][3]: 2 * 32 * iterations (exact in fp32)."""
+    ops = torch.full((16 * 256 * 8,), 0x3F80, dtype=torch.int16, device="cuda")
+    blocks, iters = 8, 5
+    out = torch.zeros(blocks * 256, dtype=torch.float32, device="cuda")
+    gd.gd_probe_mfma(ops.data_ptr(), out.data_ptr(), blocks, iters)
+    torch.cuda.synchronize()
+    assert torch.all(out == 2.0 * 32.0 * iters).item()
+    ops.zero_()
+    gd.gd_probe_mfma(ops.data_ptr(), out.data_ptr(), blocks, iters)
+    torch.cuda.synchronize()
+    assert torch.all(out == 0).item()
