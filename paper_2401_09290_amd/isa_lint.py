@@ -25,6 +25,15 @@ the same guarantee is checked after the fact, on the assembly text produced by
   check covers exactly that offset), and there is no global_* access;
 * the sum kernels that keep their partial sums in the library's own device array
   access that array unfenced (manager memory), and nothing else;
+* for all five rules, on the backward slice of each access's address registers (through
+  registers, condition codes and earlier loads, down to the scalar loads of the kernel
+  arguments, whose layout the code object's metadata gives): scalar loads read the kernel
+  arguments only; under the bitwise and hardware-checked rules every address depends on the
+  partition's base and size, under the modulo rule also on the reciprocal; under address
+  checking every access runs under a scalar branch or an exec-mask selection that depends on
+  base, size and on every kernel argument its own address depends on.  This shows that no
+  access bypasses its rule; that the rule's arithmetic and the comparison's sense are right
+  is what the parity tests show (images, neighbours' bytes, exact fault counts);
 * per kernel: loads, stores, fence instructions, VGPR/SGPR counts and the
   register delta against the unfenced build of the same kernel.
 
@@ -69,6 +78,44 @@ def demangle(names):
     return pretty
 
 
+def fence_param_index(mangled):
+    """Position of the gd::FenceArgs parameter in a kernel's parameter list, read off the Itanium name
+    (parameters here are structs passed by value, pointers and builtin integers), or None."""
+    m = re.match(r"^_ZN2gd\d+[a-z_0-9]+?(?:I.*?E)?Ev(.*)$", mangled)
+    if not m:
+        return None
+    rest, k = m.group(1), 0
+    while rest:
+        rest = rest.lstrip("PK")
+        if rest.startswith("NS_9FenceArgsE"):
+            return k
+        nested = rest.startswith("N")
+        rest = rest[1:] if nested else rest
+        parts = 0
+        while True:
+            d = re.match(r"^(\d+)", rest)
+            sub = re.match(r"^S[0-9A-Z]*_", rest)
+            if d:
+                rest = rest[len(d.group(1)) + int(d.group(1)):]
+            elif sub:
+                rest = rest[sub.end():]
+            else:
+                break
+            parts += 1
+            if not nested:
+                break
+        if nested:
+            if not rest.startswith("E"):
+                return None
+            rest = rest[1:]
+        elif parts == 0:
+            if not rest or not rest[0].isalpha():
+                return None
+            rest = rest[1:]                              # a builtin type
+        k += 1
+    return None
+
+
 def kernels_of(asm_text):
     """name -> list of instruction lines, plus metadata dicts, from one .s file."""
     bodies, meta = {}, {}
@@ -94,6 +141,15 @@ def kernels_of(asm_text):
             return int(g.group(1)) if g else -1
         meta[name] = {"vgpr": grab("amdhsa_next_free_vgpr"), "sgpr": grab("amdhsa_next_free_sgpr"),
                       "scratch": grab("amdhsa_private_segment_fixed_size"), "accum": grab("amdhsa_accum_offset")}
+    # kernel arguments from the code object's metadata; which of them is the fence's 40-byte parameter block
+    # follows from the position of gd::FenceArgs in the kernel's (mangled) parameter list
+    for m in re.finditer(r"\.args:\n(.*?)\n    \.group_segment_fixed_size.*?\.name:\s+(\S+)", asm_text, re.S):
+        args = re.findall(r"\.offset:\s+(\d+)\n\s+\.size:\s+(\d+)\n\s+\.value_kind:\s+(\w+)", m.group(1))
+        explicit = [(int(o), int(z)) for o, z, kind in args if not kind.startswith("hidden")]
+        if m.group(2) in meta and explicit:
+            meta[m.group(2)]["explicit_end"] = explicit[-1][0] + explicit[-1][1]
+            k = fence_param_index(m.group(2))
+            meta[m.group(2)]["fence_offset"] = explicit[k][0] if k is not None and k < len(explicit) and explicit[k][1] == 40 else None
     return bodies, meta
 
 
@@ -103,35 +159,85 @@ NO_DEST = ("s_cmp", "s_cbranch", "s_branch", "s_waitcnt", "s_barrier", "s_nop", 
 # instructions whose second operand is written as well (carry / scale outputs)
 TWO_DEST = ("v_mad_u64_u32", "v_mad_i64_i32", "v_add_co_u32", "v_sub_co_u32", "v_subrev_co_u32", "v_addc_co_u32",
             "v_subb_co_u32", "v_subbrev_co_u32", "v_div_scale_f32", "v_div_scale_f64")
+# condition registers, tracked as kind 'x': vcc, scc, exec (halves count as the whole)
+SPECIAL = {"vcc": 0, "vcc_lo": 0, "vcc_hi": 0, "scc": 1, "exec": 2, "exec_lo": 2, "exec_hi": 2}
+VCC, SCC, EXEC = ("x", 0, 0), ("x", 1, 1), ("x", 2, 2)
+# scalar instructions that leave their outcome in scc
+SCC_WRITERS = ("s_add_", "s_addc_", "s_sub_", "s_subb_", "s_and_", "s_andn2_", "s_or_", "s_orn2_", "s_xor_", "s_nand_",
+               "s_nor_", "s_xnor_", "s_lshl_", "s_lshr_", "s_ashr_", "s_bfe_", "s_cmp_", "s_bitcmp", "s_min_", "s_max_",
+               "s_abs_", "s_not_", "s_bcnt", "s_absdiff", "s_lshl1_add", "s_lshl2_add", "s_lshl3_add", "s_lshl4_add",
+               "s_wqm", "s_quadmask")
+SCC_READERS = ("s_addc_", "s_subb_", "s_cselect", "s_cmov", "s_cbranch_scc")
 
 
 def _regs(operand):
-    """('v'|'s', lo, hi) of a register operand, or None."""
+    """('v'|'s'|'x', lo, hi) of a register operand, or None."""
+    operand = operand.lstrip("-|").rstrip("|")
     m = re.match(r"^([vs])(\d+)$", operand)
     if m:
         return m.group(1), int(m.group(2)), int(m.group(2))
     m = re.match(r"^([vs])\[(\d+):(\d+)\]$", operand)
     if m:
         return m.group(1), int(m.group(2)), int(m.group(3))
+    if operand in SPECIAL:
+        return "x", SPECIAL[operand], SPECIAL[operand]
     return None
 
 
-def dests(line):
-    """Registers an instruction writes (explicit operands only; vcc, scc, exec and m0 are not tracked)."""
+def _split(line):
     code = line.strip()
-    m = re.match(r"^(\w+)\s+(.*)$", code)
-    if not m or LABEL_RE.match(code) or code.startswith(NO_DEST):
+    m = re.match(r"^(\w+)\s*(.*)$", code)
+    if not m or LABEL_RE.match(code):
+        return None, []
+    return m.group(1), [o.strip().split()[0] for o in m.group(2).split(",") if o.strip()]
+
+
+def _no_return_atomic(op, ops):
+    """global_atomic_* vaddr, vdata, saddr (three operands): nothing comes back, nothing is written."""
+    return op.startswith("global_atomic") and len(ops) == 3
+
+
+def dests(line):
+    """Registers an instruction writes: its explicit results, and scc / exec where the
+    instruction leaves its outcome there (m0 is not tracked)."""
+    op, ops = _split(line)
+    if op is None:
         return []
-    op, ops = m.group(1), [o.strip().split()[0] for o in m.group(2).split(",") if o.strip()]
     out = []
-    for k in range(2 if op.startswith(TWO_DEST) else 1):
-        if k < len(ops) and _regs(ops[k]):
-            out.append(_regs(ops[k]))
+    if not line.strip().startswith(NO_DEST) and not _no_return_atomic(op, ops):
+        for k in range(2 if op.startswith(TWO_DEST) else 1):
+            if k < len(ops) and _regs(ops[k]):
+                out.append(_regs(ops[k]))
+    if op.startswith(SCC_WRITERS):
+        out.append(SCC)
+    if "saveexec" in op or op.startswith("v_cmpx"):
+        out.append(EXEC)
+    return out
+
+
+def srcs(line):
+    """Registers an instruction reads (explicit operands, and scc / vcc / exec where a
+    branch, a carry or an exec-mask update takes them implicitly)."""
+    op, ops = _split(line)
+    if op is None:
+        return []
+    if (line.strip().startswith(NO_DEST) and not line.strip().startswith("s_mov_b32 m0")) or _no_return_atomic(op, ops):
+        first = 0
+    else:
+        first = 2 if op.startswith(TWO_DEST) else 1
+    out = [r for r in (_regs(o) for o in ops[first:]) if r]
+    if op.startswith(SCC_READERS):
+        out.append(SCC)
+    if op.startswith("s_cbranch_vcc"):
+        out.append(VCC)
+    if op.startswith("s_cbranch_exec") or "saveexec" in op:
+        out.append(EXEC)
     return out
 
 
 class Flow:
-    """Control-flow graph of one kernel body and reaching definitions on it."""
+    """Control-flow graph of one kernel body; reaching definitions, dominators and
+    backward slices on it."""
 
     def __init__(self, body):
         self.body = body
@@ -142,14 +248,21 @@ class Flow:
             if m:
                 label_at[m.group(1)] = i
         self.preds = [[] for _ in range(n + 1)]            # instruction index -> indices it can be reached from
+        self.succs = [[] for _ in range(n + 1)]
+        self.ops = []
         for i, ln in enumerate(body):
             code = ln.strip()
             op = code.split()[0] if code else ""
+            self.ops.append(op)
             target = code.split()[-1] if op.startswith(("s_branch", "s_cbranch")) else None
             if target is not None and target in label_at:
                 self.preds[label_at[target]].append(i)
+                self.succs[i].append(label_at[target])
             if not op.startswith(("s_branch", "s_endpgm")) and i + 1 < n:
                 self.preds[i + 1].append(i)
+                self.succs[i].append(i + 1)
+        self.dst = [dests(ln) for ln in body]
+        self._dom = None
 
     def reaching_at(self, idx, kind, reg):
         """Indices of the instructions whose write of `reg` can reach instruction idx; -1 stands for
@@ -162,7 +275,7 @@ class Flow:
             if j in seen:
                 continue
             seen.add(j)
-            if any(k == kind and lo <= reg <= hi for (k, lo, hi) in dests(self.body[j])):
+            if any(k == kind and lo <= reg <= hi for (k, lo, hi) in self.dst[j]):
                 found.add(j)
                 continue
             if self.preds[j]:
@@ -174,6 +287,66 @@ class Flow:
     def reaching(self, idx, kind, reg):
         """The same as instruction texts ('ENTRY' for the kernel's start)."""
         return {"ENTRY" if j < 0 else self.body[j].strip() for j in self.reaching_at(idx, kind, reg)}
+
+    def dominators(self, idx):
+        """Indices of the instructions every path from the kernel's start to idx passes (idx included),
+        as a bit set in a Python integer."""
+        if self._dom is None:
+            n = len(self.body)
+            full = (1 << n) - 1
+            dom = [full] * n
+            if n:
+                dom[0] = 1
+            changed = True
+            while changed:
+                changed = False
+                for i in range(1, n):
+                    acc = full
+                    for p in self.preds[i]:
+                        acc &= dom[p]
+                    if not self.preds[i]:
+                        acc = 0                            # unreachable text
+                    acc |= 1 << i
+                    if acc != dom[i]:
+                        dom[i], changed = acc, True
+            self._dom = dom
+        return self._dom[idx]
+
+    def slice_of(self, idx, regs, through_exec=True):
+        """Backward slice: every instruction whose result can flow into one of `regs`
+        (a list of (kind, number)) as read by instruction idx.  Returns {(j, kind, number)}: definition j
+        (-1 = kernel start) was reached for that register.  through_exec=False does not follow the exec
+        mask an exec-mask update read (the conditions that were already in force), only what it combined
+        it with."""
+        out, seen = set(), set()
+        work = [(idx, k, r) for (k, r) in regs]
+        while work:
+            i, k, r = work.pop()
+            if (i, k, r) in seen:
+                continue
+            seen.add((i, k, r))
+            for j in self.reaching_at(i, k, r):
+                out.add((j, k, r))
+                if j >= 0:
+                    for (sk, lo, hi) in srcs(self.body[j]):
+                        if (sk, lo, hi) == EXEC and not through_exec:
+                            continue
+                        for q in range(lo, hi + 1):
+                            work.append((j, sk, q))
+        return out
+
+    def reaches_end_avoiding(self, start, avoid):
+        """Can the kernel end, starting at instruction `start`, without executing instruction `avoid`?"""
+        seen, stack = set(), [start]
+        while stack:
+            j = stack.pop()
+            if j in seen or j == avoid:
+                continue
+            seen.add(j)
+            if self.ops[j].startswith("s_endpgm") or not self.succs[j]:
+                return True
+            stack.extend(self.succs[j])
+        return False
 
 
 FENCE_AND32 = re.compile(r"^v_and_b32\w*\s+v\d+,\s*(s\d+,\s*v\d+|v\d+,\s*s\d+)$")
@@ -217,7 +390,196 @@ def fenced_scalar(flow, idx, sreg, depth=0, seen=None):
     return ok, saw
 
 
-def lint_kernel(name, pretty, body, variant):
+LOAD_BYTES = {"s_load_dword": 4, "s_load_dwordx2": 8, "s_load_dwordx4": 16, "s_load_dwordx8": 32, "s_load_dwordx16": 64}
+FENCE_FIELDS = {"base": (0, 8), "size": (8, 16), "magic": (16, 24)}      # byte ranges inside the fence's kernel parameter
+NEEDS = {1: ("base", "size"), 2: ("base", "size"), 3: ("base", "size", "magic"), 5: ("base", "size")}
+# exec-mask updates that select lanes by a condition: "then" (AND with the condition), loop exits, and the "else"
+# half of a two-way split (saved mask AND NOT the lanes that ran the first half)
+EXEC_NARROW = re.compile(r"^(s_and_saveexec_b64\s|s_and_b64\s+exec,|s_andn2_b64\s+exec,\s*exec,|s_andn2_saveexec_b64\s)")
+EXEC_WIDEN = re.compile(r"^(s_or_b64\s+exec,|s_mov_b64\s+exec,|s_xor_b64\s+exec,|s_andn2_saveexec_b64\s|s_or_saveexec_b64\s|"
+                        r"s_xor_saveexec_b64\s|s_orn2_saveexec_b64\s|s_andn2_wrexec)")
+MASK_ALGEBRA = ("s_and_b64", "s_or_b64", "s_xor_b64", "s_andn2_b64", "s_mov_b64")
+
+
+def mask_within(flow, idx, pair, guard, depth=0, seen=None):
+    """Is the lane mask in the SGPR pair `pair` = (lo, hi), as read by instruction idx, a subset of the
+    exec mask that the narrowing instruction `guard` left?  True for masks saved from exec inside the
+    guard's region and for combinations of such masks with exec; false for the mask the guard itself
+    saved (the lanes in force before it) and for anything else."""
+    seen = set() if seen is None else seen
+    if depth > 8:
+        return False
+    for d in flow.reaching_at(idx, "s", pair[0]) | flow.reaching_at(idx, "s", pair[1]):
+        if d < 0 or d == guard or not (flow.dominators(d) >> guard) & 1:
+            return False
+        if (d, pair) in seen:
+            continue
+        seen.add((d, pair))
+        op, ops = _split(flow.body[d])
+        if "saveexec" in op:
+            continue                                       # exec as it stood at d, inside the region
+        if not op.startswith(MASK_ALGEBRA):
+            return False
+        for o in ops[1:]:
+            r = _regs(o)
+            if r == EXEC:
+                continue
+            if not (r and r[0] == "s" and r[2] == r[1] + 1 and mask_within(flow, d, (r[1], r[2]), guard, depth + 1, seen)):
+                return False
+    return True
+
+
+def widens(flow, k, guard):
+    """Does instruction k (an exec-mask update) let lanes run that the narrowing `guard` switched off?"""
+    text = flow.body[k].strip()
+    if not EXEC_WIDEN.match(text):
+        return False
+    op, ops = _split(text)
+    for o in ops[1:]:
+        r = _regs(o)
+        if r == EXEC:
+            continue
+        if not (r and r[0] == "s" and r[2] == r[1] + 1 and mask_within(flow, k, (r[1], r[2]), guard)):
+            return True
+    return False
+
+
+def kernarg_offset(flow, idx, lo, hi):
+    """If the SGPR pair s[lo:hi], as read by instruction idx, is the kernel-argument pointer the kernel
+    starts with in s[0:1], or that pointer plus a constant, return the constant; otherwise None."""
+    dl, dh = flow.reaching_at(idx, "s", lo), flow.reaching_at(idx, "s", hi)
+    if dl == {-1} and dh == {-1}:
+        return 0 if (lo, hi) == (0, 1) else None
+    if len(dl) == 1 and len(dh) == 1:
+        jl, jh = next(iter(dl)), next(iter(dh))
+        if jl >= 0 and jh >= 0:
+            ml = re.match(r"^s_add_u32\s+s\d+,\s*s0,\s*(0x[0-9a-f]+|\d+)$", flow.body[jl].strip())
+            mh = re.match(r"^s_addc_u32\s+s\d+,\s*s1,\s*0$", flow.body[jh].strip())
+            if ml and mh and flow.reaching_at(jl, "s", 0) == {-1} and flow.reaching_at(jh, "s", 1) == {-1}:
+                return int(ml.group(1), 0)
+    return None
+
+
+def scalar_load(flow, j):
+    """(first result SGPR, kernel-argument byte offset or None) of the scalar load at instruction j."""
+    op, ops = _split(flow.body[j])
+    dst, base = _regs(ops[0]), _regs(ops[1])
+    imm = int(ops[2], 0) if len(ops) > 2 and re.match(r"^(0x[0-9a-f]+|\d+)$", ops[2]) else None
+    ko = kernarg_offset(flow, j, base[1], base[2]) if base and base[0] == "s" and base[2] == base[1] + 1 else None
+    return dst[1], (ko + imm if ko is not None and imm is not None else None)
+
+
+def kernarg_bytes(flow, sl):
+    """Kernel-argument byte offsets (one per 4-byte word) that a backward slice depends on; None stands
+    for a scalar load from anywhere else."""
+    out = set()
+    for (j, kind, reg) in sl:
+        if j >= 0 and kind == "s" and flow.ops[j] in LOAD_BYTES:
+            first, off = scalar_load(flow, j)
+            out.add(None if off is None else off + 4 * (reg - first))
+    return out
+
+
+def fence_fields(words, fence_offset):
+    return {name for name, (lo, hi) in FENCE_FIELDS.items() if any(w is not None and fence_offset + lo <= w < fence_offset + hi for w in words)}
+
+
+def guarded_by_bounds(flow, i, addr_words, fence_offset):
+    """Address checking: is the access at instruction i executed only under a condition that depends on the
+    partition's base and size and on everything its own address depends on?  The condition is a scalar
+    branch that decides whether i runs, or an exec-mask narrowing that still holds at i."""
+    dom = flow.dominators(i)
+    for j in range(i - 1, -1, -1):
+        if not (dom >> j) & 1:
+            continue
+        op, text = flow.ops[j], flow.body[j].strip()
+        if op.startswith(("s_cbranch_scc", "s_cbranch_vcc")):
+            if not flow.reaches_end_avoiding(j, i):
+                continue                                  # both outcomes run the access: it does not depend on this branch
+            cond = [("x", SCC[1] if "scc" in op else VCC[1])]
+        elif EXEC_NARROW.match(text):
+            seen, stack, widened = set(), list(flow.preds[i]), False
+            while stack and not widened:                  # every path from the narrowing to the access: no widening on it
+                k = stack.pop()
+                if k in seen or k == j:
+                    continue
+                seen.add(k)
+                widened = widens(flow, k, j)
+                stack.extend(flow.preds[k])
+            if widened:
+                continue
+            cond = [(k, q) for (k, lo, hi) in srcs(text) for q in range(lo, hi + 1) if (k, lo, hi) != EXEC]
+        else:
+            continue
+        words = kernarg_bytes(flow, flow.slice_of(j, cond, through_exec=False))
+        if {"base", "size"} <= fence_fields(words, fence_offset) and addr_words <= words:
+            return True
+    return False
+
+
+def access_address(line):
+    """The registers that address a global or buffer access, as [(kind, number)], or None for other lines."""
+    m = MEM_RE.match(line)
+    if m:
+        inst, ops = m.group(1), [o.strip().split()[0] for o in m.group(2).split(",")]
+        if inst.startswith("global_load_lds"):
+            parts = ops[0:2]
+        elif inst.startswith("global_store"):
+            parts = [ops[0]] + ops[2:3]
+        elif inst.startswith("global_atomic") and len(ops) == 3:     # no returned value: address, data, base
+            parts = [ops[0], ops[2]]
+        else:
+            parts = ops[1:3]
+    else:
+        m = BUF_RE.match(line)
+        if not m:
+            return None
+        inst, ops = m.group(1), [o.strip().split()[0] for o in m.group(2).split(",")]
+        parts = ops[1:4]                                           # offset VGPR, descriptor, scalar offset
+    return inst, [(r[0], q) for r in (_regs(o) for o in parts) if r for q in range(r[1], r[2] + 1)]
+
+
+def dependency_problems(flow, pretty, variant, fence_offset, explicit_end, own_ws=False):
+    """What each access's address is computed from, on the backward slice of its address registers.
+
+    * No scalar load reads anything but the kernel arguments (tenant memory is never read through the
+      scalar cache, where no rule applies).
+    * Bitwise, modulo and hardware-checked rules: the address of every access to tenant memory depends on
+      the partition's base and size (and, modulo rule, on the reciprocal): an address that never met the
+      fence cannot.
+    * Address checking: every access runs under a condition (guarded_by_bounds) that depends on base, size
+      and on every kernel argument the address itself depends on.
+    This shows that no access bypasses the rule; that the rule's arithmetic and the comparison's sense are
+    right is what the parity tests show (images, neighbours' bytes, exact fault counts)."""
+    problems = []
+    for i, ln in enumerate(flow.body):
+        if flow.ops[i].startswith(("s_load_", "s_buffer_load")):
+            if flow.ops[i] not in LOAD_BYTES or scalar_load(flow, i)[1] is None:
+                problems.append(f"{pretty}: scalar load from memory other than the kernel arguments: {ln.strip()}")
+            continue
+        if fence_offset is None or variant not in (1, 2, 3, 4, 5):
+            continue
+        acc = access_address(ln)
+        if acc is None or acc[0] in UNFENCED_OK:
+            continue
+        inst, regs = acc
+        if own_ws and (("store" in inst and "k_sum_partial" in pretty) or ("load" in inst and "k_sum_final" in pretty)):
+            continue                                      # the library's own partial-sum array
+        words = kernarg_bytes(flow, flow.slice_of(i, regs))
+        if variant == 4:
+            mine = {w for w in words if w is not None and w < explicit_end and not fence_offset <= w < fence_offset + 40}
+            if not guarded_by_bounds(flow, i, mine, fence_offset):
+                problems.append(f"{pretty}: `{ln.strip()}` does not run under a comparison of its address with the partition's bounds")
+        else:
+            missing = set(NEEDS[variant]) - fence_fields(words, fence_offset)
+            if missing:
+                problems.append(f"{pretty}: address of `{ln.strip()}` does not depend on the fence's {', '.join(sorted(missing))}")
+    return problems
+
+
+def lint_kernel(name, pretty, body, variant, fence_offset=None, explicit_end=None):
+    """fence_offset / explicit_end: byte offset of the fence's parameter block among the kernel arguments and
+    the end of the explicit arguments (from the code object's metadata); the dependency rules need them."""
     problems, loads, stores, fences = [], 0, 0, 0
     tiles = own_ws_seen = 0
     own_ws = bool(re.search(r"k_sum_\w+<\d, (true|1)>", pretty))
@@ -293,31 +655,45 @@ def lint_kernel(name, pretty, body, variant):
                     problems.append(f"{pretty}: high word v{va[2]} of `{what}` defined by `{d}`")
     if own_ws and variant in (1, 2) and own_ws_seen == 0:
         problems.append(f"{pretty}: expected an access to the library's own partial-sum array")
+    if variant >= 0:
+        problems += dependency_problems(flow, pretty, variant, fence_offset, explicit_end, own_ws)
     return problems, loads, stores, fences
+
+
+def lint_file(source, tmp):
+    """Compile one HIP source to gfx950 assembly and audit every gd:: kernel in it.
+    Returns (rows, problems); a row is (kernel, variant, loads, stores, fences, VGPRs, SGPRs, scratch)."""
+    rows, problems = [], []
+    out = os.path.join(tmp, os.path.basename(source) + ".s")
+    res = subprocess.run(["hipcc", *FLAGS, "-o", out, source], capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(res.stderr)
+    bodies, meta = kernels_of(open(out).read())
+    names = [n for n in bodies if "gd" in n]
+    pretty = dict(zip(names, demangle(names)))
+    for n in names:
+        p = pretty[n].replace("void gd::", "").split("(")[0]
+        v = re.search(r"<(\d)", p)
+        # the measurement aids (k_*probe*) take no tenant and no fence: their template argument is not a rule
+        variant = int(v.group(1)) if v and "probe" not in p else -1
+        md = meta.get(n, {})
+        pr, ld, st, fc = lint_kernel(n, p, bodies[n], variant, md.get("fence_offset"), md.get("explicit_end"))
+        if variant > 0 and md.get("fence_offset") is None:
+            pr.append(f"{p}: the fence's parameter block was not found among the kernel arguments")
+        if md.get("scratch", 0) > 0:
+            pr.append(f"{p}: uses {md['scratch']} bytes of scratch")
+        problems += pr
+        rows.append((p, variant, ld, st, fc, md.get("vgpr", -1), md.get("sgpr", -1), md.get("scratch", -1)))
+    return rows, problems
 
 
 def run(verbose=True):
     rows, problems = [], []
     with tempfile.TemporaryDirectory() as tmp:
         for src in HIP_SOURCES:
-            out = os.path.join(tmp, src + ".s")
-            res = subprocess.run(["hipcc", *FLAGS, "-o", out, os.path.join(CSRC, src)], capture_output=True, text=True)
-            if res.returncode != 0:
-                raise RuntimeError(res.stderr)
-            bodies, meta = kernels_of(open(out).read())
-            names = [n for n in bodies if "gd" in n]
-            pretty = dict(zip(names, demangle(names)))
-            for n in names:
-                p = pretty[n].replace("void gd::", "").split("(")[0]
-                v = re.search(r"<(\d)", p)
-                # the measurement aids (k_*probe*) take no tenant and no fence: their template argument is not a rule
-                variant = int(v.group(1)) if v and "probe" not in p else -1
-                pr, ld, st, fc = lint_kernel(n, p, bodies[n], variant)
-                md = meta.get(n, {})
-                if md.get("scratch", 0) > 0:
-                    pr.append(f"{p}: uses {md['scratch']} bytes of scratch")
-                problems += pr
-                rows.append((p, variant, ld, st, fc, md.get("vgpr", -1), md.get("sgpr", -1), md.get("scratch", -1)))
+            r, pr = lint_file(os.path.join(CSRC, src), tmp)
+            rows += r
+            problems += pr
     base = {re.sub(r"<\d", "<0", r[0]): r for r in rows if r[1] == 0}
     lines = ["kernel | variant | loads | stores | fence v_and_b32 | VGPRs | SGPRs | scratch | VGPR delta vs unfenced | SGPR delta",
              "---|---|---|---|---|---|---|---|---|---"]
