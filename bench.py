@@ -717,6 +717,17 @@ def run_modes(torch, gd, si, args):
     torch.cuda.synchronize()
     res["host_ns_per_call"] = {k: round(v, 1) for k, v in host_ns.items()}
     log("[modes] host ns per call: " + ", ".join(f"{k} {v:.0f}" for k, v in host_ns.items()))
+    # The same path timed inside the library (no binding in the figures), against the bare HIP launch call of the
+    # same kernel: Section 7.6's Table 5 (lookup and augmentation against the launch itself).
+    native = {}
+    for label, mode in (("bitwise", gd.GD_FENCE_BITWISE), ("modulo", gd.GD_FENCE_MODULO), ("unfenced", gd.GD_FENCE_NONE)):
+        gd.gd_probe_host_path(dp.pool, 0, a, 2000, stream=st.cuda_stream, mode=mode)             # warm
+        up_to, with_launch, bare = gd.gd_probe_host_path(dp.pool, 0, a, 20000, stream=st.cuda_stream, mode=mode)
+        native[label] = {"lookup_and_augmentation_ns": round(up_to, 1), "gd_launch_fenced_ns": round(with_launch, 1),
+                         "bare_hip_launch_ns": round(bare, 1), "library_share_of_launch_pct": round(100.0 * (with_launch - bare) / bare, 1)}
+        log(f"[modes] host path inside the library, {label}: up to the launch {up_to:.0f} ns, with the launch {with_launch:.0f} ns, "
+            f"bare HIP launch {bare:.0f} ns")
+    res["host_ns_per_call_native"] = native
     dp.close()
     return res
 

@@ -240,6 +240,21 @@ int gd_probe_mfma(uint64_t operands, uint64_t out, uint32_t blocks, uint32_t ite
 int gd_probe_gather_policy(uint64_t out, uint64_t tab, uint64_t idx, uint64_t n, uint32_t policy,
                            void *hip_stream);
 
+/* Measurement aid: what the fenced launch path costs on the host, per call, timed
+ * inside the library (no language binding in the figures) -- the analogue of the
+ * paper's Table 5 (Section 7.6: kernel lookup and parameter augmentation against the
+ * launch call itself).  Uses GD_K_STORE_TID on 64 elements at `dptr`, a device
+ * address the caller has allocated in `tenant`'s partition (256 bytes are written,
+ * fenced under `mode`).  ns[0]: gd_launch_fenced up to the launch (lookup, bounds-table
+ * row, parameter augmentation; an n = 0 launch returns there); ns[1]: gd_launch_fenced
+ * including the launch; ns[2]: the bare HIP launch call of the same kernel with
+ * arguments prepared once.  Each is the mean over `iters` calls (1 .. 2^20) on
+ * `hip_stream`, which is synchronised before and after each of the three loops: this
+ * call blocks, unlike every other entry point.  ns is host memory, 3 doubles,
+ * untouched on error. */
+int gd_probe_host_path(gd_pool *pool, int tenant, uint64_t dptr, uint32_t iters, void *hip_stream, int mode,
+                       double *ns);
+
 const char *gd_strerror(int status);
 int gd_last_hip_error(void);   /* hipError_t of the last failed HIP call on this thread */
 

@@ -56,6 +56,7 @@ EXPORTS = {
     "gd_sum_f32_noalloc": (C.c_int, [C.c_void_p, C.c_int, _u64, _u64, _u64, C.c_void_p, C.c_int]),
     "gd_probe_mfma": (C.c_int, [_u64, _u64, _u32, _u32, C.c_void_p]),
     "gd_probe_gather_policy": (C.c_int, [_u64, _u64, _u64, _u64, _u32, C.c_void_p]),
+    "gd_probe_host_path": (C.c_int, [C.c_void_p, C.c_int, _u64, _u32, C.c_void_p, C.c_int, C.POINTER(C.c_double)]),
     "gd_kernel_count": (C.c_int, []),
     "gd_kernel_name": (C.c_char_p, [C.c_int]),
     "gd_kernel_args_bytes": (C.c_size_t, [C.c_int]),
@@ -168,6 +169,13 @@ def gd_probe_mfma(operands, out, blocks, iters, stream=None):
 
 def gd_probe_gather_policy(out, tab, idx, n, policy, stream=None):
     _ok(lib().gd_probe_gather_policy(out, tab, idx, n, policy, C.c_void_p(stream or 0)), "gd_probe_gather_policy")
+
+
+def gd_probe_host_path(pool, tenant, dptr, iters, stream=None, mode=GD_FENCE_BITWISE):
+    """(ns up to the launch, ns with the launch, ns of the bare HIP launch call), each per call."""
+    ns = (C.c_double * 3)()
+    _ok(lib().gd_probe_host_path(pool, tenant, dptr, iters, C.c_void_p(stream or 0), mode, ns), "gd_probe_host_path")
+    return tuple(ns)
 
 
 def gd_fence_host(base, size, addr, width=1, mode=GD_FENCE_BITWISE):

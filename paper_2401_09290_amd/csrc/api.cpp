@@ -7,6 +7,7 @@
 // gets the native (unfenced) build of the same kernel.
 #include <hip/hip_runtime.h>
 
+#include <chrono>
 #include <cstring>
 #include <new>
 
@@ -198,6 +199,39 @@ static int sum_noalloc(gd_pool *pool, int tenant, uint64_t out, uint64_t in, uin
     return gd::launch_sum_f32_noalloc(out, in, n, extra, variant, static_cast<hipStream_t>(hip_stream));
 }
 
+static int probe_host_path(gd_pool *pool, int tenant, uint64_t dptr, uint32_t iters, void *hip_stream, int mode, double *ns)
+{
+    if (!pool || !ns || !dptr || iters == 0 || iters > (1u << 20)) return GD_EINVAL;
+    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    int variant;
+    gd::FenceArgs extra;
+    int rc = fence_args_for(pool, tenant, mode, &variant, &extra);
+    if (rc != GD_OK) return rc;
+    double out[3];
+    const gd_args_store_tid none = {dptr, 0, 1, 0}, some = {dptr, 64, 1, 0};
+    auto sync = [&]() {
+        const hipError_t e = hipStreamSynchronize(stream);
+        if (e != hipSuccess) gd::note_hip_error(e);
+        return e == hipSuccess ? GD_OK : GD_EHIP;
+    };
+    auto timed = [&](const gd_args_store_tid &a, double *per_call) {
+        if ((rc = sync()) != GD_OK) return rc;
+        const auto t0 = std::chrono::steady_clock::now();
+        for (uint32_t i = 0; i < iters && rc == GD_OK; ++i)
+            rc = launch_fenced(pool, tenant, GD_K_STORE_TID, &a, sizeof a, nullptr, nullptr, hip_stream, mode);
+        const auto t1 = std::chrono::steady_clock::now();
+        *per_call = std::chrono::duration<double, std::nano>(t1 - t0).count() / iters;
+        return rc;
+    };
+    if ((rc = timed(none, &out[0])) != GD_OK) return rc;
+    if ((rc = timed(some, &out[1])) != GD_OK) return rc;
+    if ((rc = sync()) != GD_OK) return rc;
+    if ((rc = gd::probe_raw_launches(some, extra, variant, iters, stream, &out[2])) != GD_OK) return rc;
+    if ((rc = sync()) != GD_OK) return rc;
+    std::memcpy(ns, out, sizeof out);
+    return GD_OK;
+}
+
 int gd_launch_fenced(gd_pool *pool, int tenant, int kernel_id, const void *args, size_t args_bytes,
                      const uint32_t grid[3], const uint32_t block[3], void *hip_stream, int mode)
 {
@@ -212,6 +246,11 @@ int gd_sum_f32_noalloc(gd_pool *pool, int tenant, uint64_t out, uint64_t in, uin
 int gd_probe_mfma(uint64_t operands, uint64_t out, uint32_t blocks, uint32_t iters, void *hip_stream)
 {
     GD_ABI_GUARD(gd::launch_mfma_probe(operands, out, blocks, iters, static_cast<hipStream_t>(hip_stream)))
+}
+
+int gd_probe_host_path(gd_pool *pool, int tenant, uint64_t dptr, uint32_t iters, void *hip_stream, int mode, double *ns)
+{
+    GD_ABI_GUARD(probe_host_path(pool, tenant, dptr, iters, hip_stream, mode, ns))
 }
 
 int gd_probe_gather_policy(uint64_t out, uint64_t tab, uint64_t idx, uint64_t n, uint32_t policy, void *hip_stream)

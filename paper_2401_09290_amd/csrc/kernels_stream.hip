@@ -4,6 +4,8 @@
 // single-wavefront workgroup per 1 KiB tile).  The fence (fence.hpp) is applied to
 // the final address of every access; kernels are identical for every variant apart
 // from it.
+#include <chrono>
+
 #include "launchers.hpp"
 
 namespace gd {
@@ -153,6 +155,20 @@ int launch_store_tid(const void *args, const FenceArgs &f, int variant, const Sh
     });
     if (rc != GD_OK) return rc;
     GD_CHECK_LAUNCH();
+    return GD_OK;
+}
+
+int probe_raw_launches(const gd_args_store_tid &p, const FenceArgs &f, int variant, uint32_t iters, hipStream_t stream,
+                       double *ns_per_call)
+{
+    void (*kernel)(gd_args_store_tid, FenceArgs) = nullptr;
+    const int rc = with_variant(variant, [&](auto v) { kernel = k_store_tid<decltype(v)::value>; });
+    if (rc != GD_OK) return rc;
+    const auto t0 = std::chrono::steady_clock::now();
+    for (uint32_t i = 0; i < iters; ++i) hipLaunchKernelGGL(kernel, dim3(1), dim3(256), 0, stream, p, f);   // the shape launch_store_tid picks for 64 elements
+    const auto t1 = std::chrono::steady_clock::now();
+    GD_CHECK_LAUNCH();
+    *ns_per_call = std::chrono::duration<double, std::nano>(t1 - t0).count() / iters;
     return GD_OK;
 }
 

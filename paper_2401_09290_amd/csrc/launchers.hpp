@@ -39,6 +39,11 @@ int launch_sum_f32_noalloc(uint64_t out, uint64_t in, uint64_t n, const FenceArg
 // Matrix-pipe probe (gd_probe_mfma): no tenant, no fence.
 int launch_mfma_probe(uint64_t operands, uint64_t out, uint32_t blocks, uint32_t iters, hipStream_t);
 
+// Host-path probe (gd_probe_host_path): `iters` bare HIP launches of the store_tid kernel built for
+// `variant`, arguments prepared once; *ns_per_call = mean host time of the launch call.
+int probe_raw_launches(const gd_args_store_tid &p, const FenceArgs &f, int variant, uint32_t iters, hipStream_t,
+                       double *ns_per_call);
+
 // Cache-policy probe of random 4-byte loads (gd_probe_gather_policy): no tenant, no fence.
 int launch_probe_gather_policy(uint64_t out, uint64_t tab, uint64_t idx, uint64_t n, uint32_t policy, hipStream_t);
 

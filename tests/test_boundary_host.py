@@ -308,7 +308,7 @@ def test_launch_argument_errors_need_no_gpu():
 
 
 def test_measurement_aids_refuse_bad_arguments_without_a_gpu():
-    """gd_probe_mfma and gd_probe_gather_policy validate their arguments before any launch."""
+    """The measurement aids validate their arguments before any launch."""
     for args in ((0, 4096, 1, 1), (4096, 0, 1, 1), (4096 + 8, 8192, 1, 1), (4096, 8192 + 2, 1, 1), (4096, 8192, 0, 1),
                  (4096, 8192, 1 << 20, 1)):
         with pytest.raises(gd.GuardianError) as e:
@@ -321,3 +321,14 @@ def test_measurement_aids_refuse_bad_arguments_without_a_gpu():
             gd.gd_probe_gather_policy(*args)
         assert e.value.status == gd.GD_EINVAL
     gd.gd_probe_gather_policy(4096, 8192, 16384, 0, 3)          # nothing to do: no launch, no GPU needed
+    # gd_probe_host_path: arguments and the tenant's row are checked before the first HIP call
+    pool = gd.gd_pool_create(1 << 40, 1 << 24, [1 << 22, 1 << 22])
+    for args, status in (((0, 0, 1 << 40, 10), gd.GD_EINVAL), ((pool, 0, 0, 10), gd.GD_EINVAL), ((pool, 0, 1 << 40, 0), gd.GD_EINVAL),
+                         ((pool, 0, 1 << 40, (1 << 20) + 1), gd.GD_EINVAL), ((pool, 7, 1 << 40, 10), gd.GD_ENOTENANT)):
+        with pytest.raises(gd.GuardianError) as e:
+            gd.gd_probe_host_path(*args)
+        assert e.value.status == status, args
+    with pytest.raises(gd.GuardianError) as e:
+        gd.gd_probe_host_path(pool, 0, 1 << 40, 10, mode=gd.GD_FENCE_CHECK)      # no fault counters registered
+    assert e.value.status == gd.GD_EINVAL
+    gd.gd_pool_destroy(pool)

@@ -739,3 +739,18 @@ def test_mfma_probe_multiplies_what_it_is_given():
     gd.gd_probe_mfma(ops.data_ptr(), out.data_ptr(), blocks, iters)
     torch.cuda.synchronize()
     assert torch.all(out == 0).item()
+
+
+def test_host_path_probe_times_three_loops_and_leaves_the_kernels_result(rig2):
+    """gd_probe_host_path runs Listing 1's kernel on 64 elements (value 1) through the fenced path and through the
+    bare launch call: the image must be what the oracle's single launch leaves, the three per-call times positive,
+    and the path that stops before the launch cheaper than the one that launches."""
+    r = rig2
+    dst = r.alloc(1, 4096)
+    for mode, omode in ((gd.GD_FENCE_BITWISE, ok.MODE_BITWISE), (gd.GD_FENCE_NONE, ok.MODE_NONE)):
+        up_to, with_launch, bare = gd.gd_probe_host_path(r.pool, 1, dst, 200, mode=mode)
+        torch.cuda.synchronize()
+        r.oracle("store_tid", 1, dst, 1, 64, mode=omode)
+        r.assert_images_equal(what="host path probe")
+        assert 0 < up_to < with_launch and 0 < bare, (up_to, with_launch, bare)
+        assert up_to < 1e5 and with_launch < 1e6 and bare < 1e6        # nanoseconds per call: sanity only
