@@ -332,3 +332,26 @@ def test_measurement_aids_refuse_bad_arguments_without_a_gpu():
         gd.gd_probe_host_path(pool, 0, 1 << 40, 10, mode=gd.GD_FENCE_CHECK)      # no fault counters registered
     assert e.value.status == gd.GD_EINVAL
     gd.gd_pool_destroy(pool)
+
+
+def test_pool_is_safe_to_use_from_several_threads(tmp_path):
+    """The header promises one lock per pool: tests/native/pool_threads.cpp drives alloc / free / range checks /
+    bounds-table reads / attach / detach from eight threads, built together with csrc/pool.cpp under the thread
+    sanitizer (host code only); it checks disjointness, confinement and full coalescing itself."""
+    import shutil
+    import subprocess
+    if shutil.which("g++") is None:
+        pytest.skip("needs g++")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = str(tmp_path / "pool_threads")
+    build = subprocess.run(["g++", "-O1", "-g", "-fsanitize=thread", "-std=c++17", "-o", exe,
+                            os.path.join(root, "tests", "native", "pool_threads.cpp"),
+                            os.path.join(root, "paper_2401_09290_amd", "csrc", "pool.cpp"), "-lpthread"],
+                           capture_output=True, text=True)
+    if build.returncode != 0 and "tsan" in build.stderr:
+        pytest.skip("thread sanitizer runtime not installed")
+    assert build.returncode == 0, build.stderr
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=300,
+                         env=dict(os.environ, TSAN_OPTIONS="halt_on_error=1 exitcode=66"))
+    assert run.returncode == 0, (run.returncode, run.stdout[-2000:], run.stderr[-4000:])
+    assert "failures 0" in run.stdout
