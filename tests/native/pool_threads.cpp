@@ -1,7 +1,7 @@
 // Concurrency check of the pool's host side: the header promises that a pool may be used from
 // several threads at once (one lock per pool).  Eight threads allocate, free, range-check, read
 // the bounds table and attach / detach tenants on one pool; the program is built with the
-// thread sanitizer by tests/test_boundary_host.py, and it checks on its own that allocations
+// thread sanitizer, and again with the address and undefined-behaviour sanitizers, by tests/test_boundary_host.py, and it checks on its own that allocations
 // of one tenant never overlap, stay inside the partition, and coalesce back into one block.
 // Exit status 0 = all invariants held (a sanitizer report ends the run with its own status).
 #include <atomic>
@@ -93,6 +93,7 @@ int main()
         uint64_t whole = 0;                                   // everything coalesced: the whole partition is one block again
         EXPECT(gd::alloc(pool, tenant, 16 * MiB, 256, &whole) == GD_OK && whole == pb);
     }
+    delete pool;                                              // what gd_pool_destroy does
     std::printf("threads %d rounds %d failures %d\n", THREADS, ROUNDS, failures.load());
     return failures.load() ? 1 : 0;
 }

@@ -337,21 +337,22 @@ def test_measurement_aids_refuse_bad_arguments_without_a_gpu():
 def test_pool_is_safe_to_use_from_several_threads(tmp_path):
     """The header promises one lock per pool: tests/native/pool_threads.cpp drives alloc / free / range checks /
     bounds-table reads / attach / detach from eight threads, built together with csrc/pool.cpp under the thread
-    sanitizer (host code only); it checks disjointness, confinement and full coalescing itself."""
+    sanitizer and under the address + undefined-behaviour sanitizers (host code only); it checks disjointness, confinement and full coalescing itself."""
     import shutil
     import subprocess
     if shutil.which("g++") is None:
         pytest.skip("needs g++")
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    exe = str(tmp_path / "pool_threads")
-    build = subprocess.run(["g++", "-O1", "-g", "-fsanitize=thread", "-std=c++17", "-o", exe,
-                            os.path.join(root, "tests", "native", "pool_threads.cpp"),
-                            os.path.join(root, "paper_2401_09290_amd", "csrc", "pool.cpp"), "-lpthread"],
-                           capture_output=True, text=True)
-    if build.returncode != 0 and "tsan" in build.stderr:
-        pytest.skip("thread sanitizer runtime not installed")
-    assert build.returncode == 0, build.stderr
-    run = subprocess.run([exe], capture_output=True, text=True, timeout=300,
-                         env=dict(os.environ, TSAN_OPTIONS="halt_on_error=1 exitcode=66"))
-    assert run.returncode == 0, (run.returncode, run.stdout[-2000:], run.stderr[-4000:])
-    assert "failures 0" in run.stdout
+    for flags, options in ((["-fsanitize=thread"], {"TSAN_OPTIONS": "halt_on_error=1 exitcode=66"}),
+                           (["-fsanitize=address,undefined", "-fno-sanitize-recover=undefined"], {"ASAN_OPTIONS": "exitcode=67"})):
+        exe = str(tmp_path / ("pool_threads" + flags[0].split("=")[1].split(",")[0]))
+        build = subprocess.run(["g++", "-O1", "-g", *flags, "-std=c++17", "-o", exe,
+                                os.path.join(root, "tests", "native", "pool_threads.cpp"),
+                                os.path.join(root, "paper_2401_09290_amd", "csrc", "pool.cpp"), "-lpthread"],
+                               capture_output=True, text=True)
+        if build.returncode != 0 and re.search(r"cannot find -l(tsan|asan|ubsan)", build.stderr):
+            pytest.skip("sanitizer runtime not installed")
+        assert build.returncode == 0, build.stderr
+        run = subprocess.run([exe], capture_output=True, text=True, timeout=300, env=dict(os.environ, **options))
+        assert run.returncode == 0, (flags, run.returncode, run.stdout[-2000:], run.stderr[-4000:])
+        assert "failures 0" in run.stdout
