@@ -18,14 +18,22 @@ _LIB_OMP = os.path.join(_HERE, "libgd_oracle_omp.so")     # the same file with -
 MODE_NONE, MODE_BITWISE, MODE_MODULO, MODE_CHECK, MODE_HWCHECK = 0, 1, 2, 3, 4
 
 
+# GDO_UBSAN=1 in the environment: every check runs on a build of the same file with gcc's
+# undefined-behaviour sanitizer, which aborts the process on the first finding (shifts, signed
+# overflow, misaligned or out-of-bounds accesses of the checker itself).
+_UBSAN = os.environ.get("GDO_UBSAN") == "1"
+_LIB_UBSAN = os.path.join(_HERE, "libgd_oracle_ubsan.so")
+
+
 def build(force=False, openmp=False):
     """Compile the oracle (plain gcc, -O2, no fast-math).  openmp=False: the sequential
     build every check uses.  openmp=True: its timing twin (see the header of the C file)."""
-    out = _LIB_OMP if openmp else _LIB
+    out = _LIB_OMP if openmp else (_LIB_UBSAN if _UBSAN else _LIB)
+    extra = ["-fopenmp"] if openmp else (
+        ["-g", "-fsanitize=undefined", "-fno-sanitize-recover=undefined", "-static-libubsan"] if _UBSAN else [])
     if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(_SRC):
         subprocess.check_call(
-            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fno-fast-math", "-ffp-contract=off"]
-            + (["-fopenmp"] if openmp else []) + ["-o", out, _SRC, "-lm"])
+            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fno-fast-math", "-ffp-contract=off"] + extra + ["-o", out, _SRC, "-lm"])
     return out
 
 

@@ -640,3 +640,23 @@ def test_hwcheck_kernels_read_zero_and_drop_stores_outside():
     pool.run("gather32_i64", table[0], ok.MODE_HWCHECK, out, tab, idxp, idx.size)
     t = pool.view(tab, np.uint32, 16).copy()
     assert pool.view(out, np.uint32, idx.size).tolist() == [t[0], t[5], 0, 0, t[7], t[9]]
+
+
+def test_the_oracle_itself_is_free_of_undefined_behaviour():
+    """The checker is C with wrap-around address arithmetic, shifts and type-punned pool bytes: rerun this file's
+    pins on a build of oracle/gd_oracle.c under gcc's undefined-behaviour sanitizer (GDO_UBSAN=1 makes
+    oracle/kernels.py load that build; the first finding aborts the run)."""
+    import os
+    import subprocess
+    import sys
+    if os.environ.get("GDO_UBSAN") == "1":
+        pytest.skip("already running on the sanitizer build")
+    probe = subprocess.run(["gcc", "-fsanitize=undefined", "-static-libubsan", "-x", "c", "-", "-o", os.devnull],
+                           input="int main(void){return 0;}", capture_output=True, text=True)
+    if probe.returncode != 0:
+        pytest.skip("gcc's undefined-behaviour sanitizer runtime is not installed")
+    run = subprocess.run([sys.executable, "-m", "pytest", os.path.abspath(__file__), "-q", "-x", "-p", "no:cacheprovider"],
+                         env=dict(os.environ, GDO_UBSAN="1"), capture_output=True, text=True, timeout=900,
+                         cwd=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    assert run.returncode == 0, run.stdout[-3000:] + run.stderr[-3000:]
+    assert "runtime error" not in run.stderr and " passed" in run.stdout
