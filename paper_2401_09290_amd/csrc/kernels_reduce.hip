@@ -208,7 +208,7 @@ __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, Fenc
         u32x4 xv[RMS_MAX_CHUNKS], gv[RMS_MAX_CHUNKS];
 #pragma unroll
         for (int c = 0; c < RMS_MAX_CHUNKS; ++c) {
-            const uint32_t q0 = 64 * wave + c * RMS_WG;              // the wavefront's first chunk of this round
+            const uint32_t q0 = 64 * wave + c * RMS_WG;              // the wavefront's first chunk of this pass over the row
             if (threadIdx.x + c * RMS_WG < chunks) {
                 xv[c] = F.template ld_tile16<u32x4>(fx + 16 * (uint64_t)q0, lane16);
                 gv[c] = F.template ld_tile16<u32x4>(fg + 16 * (uint64_t)q0, lane16);

@@ -112,7 +112,7 @@ __global__ __launch_bounds__(1024) void k_stream(uint64_t pa, uint64_t pb, uint6
                 } else {
                     F.tile_wait(vb);
                 }
-                F.template st_tile16<f32x4, NT>(fa_ + 16 * w0, lane_off, vb);
+                F.template st_tile16<f32x4, NT, true>(fa_ + 16 * w0, lane_off, vb);
             }
         } else {
             // a pointer wraps at the partition end inside its array (or, under address checking, an array is
