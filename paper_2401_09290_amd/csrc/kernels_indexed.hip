@@ -36,17 +36,25 @@ __global__ __launch_bounds__(1024) void k_saxpy_idx(gd_args_saxpy_idx p, FenceAr
     uint64_t done = 0;
     if (!F.CHECKED && (p.off & 15) == 0) {
         const uint64_t n4 = p.n >> 2;
+        // all eight fenced addresses first, in registers of their own (Fence::keep_apart), then the loads, then the stores
         auto four = [&](const i32x4 o) {
-            float vx[EPT], vy[EPT];
+            typename Fence<V>::Handle hx[EPT], hy[EPT];
 #pragma unroll
             for (int e = 0; e < EPT; ++e) {
                 const uint64_t byte_off = (uint64_t)((int64_t)o[e] * 4);
-                vx[e] = F.template ld<float>(p.x + byte_off);
-                vy[e] = F.template ld<float>(p.y + byte_off);
+                hx[e] = F.template fenced<4>(p.x + byte_off);
+                hy[e] = F.template fenced<4>(p.y + byte_off);
+            }
+            Fence<V>::keep_apart(hx[0], hx[1], hx[2], hx[3]);
+            Fence<V>::keep_apart(hy[0], hy[1], hy[2], hy[3]);
+            float vx[EPT], vy[EPT];
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) {
+                vx[e] = F.template ld_fenced<float>(hx[e]);
+                vy[e] = F.template ld_fenced<float>(hy[e]);
             }
 #pragma unroll
-            for (int e = 0; e < EPT; ++e)
-                F.template st<float>(p.y + (uint64_t)((int64_t)o[e] * 4), p.alpha * vx[e] + vy[e]);
+            for (int e = 0; e < EPT; ++e) F.template st_fenced<float>(hy[e], p.alpha * vx[e] + vy[e]);
         };
         if (F.whole_run(p.off, 16 * n4)) {
             const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -154,11 +162,16 @@ __global__ __launch_bounds__(1024) void k_scatter_f32_i64(gd_args_scatter p, Fen
     uint64_t done = 0;
     if (!F.CHECKED && ((p.idx | p.src) & 15) == 0) {
         const uint64_t n4 = p.n >> 2;
+        // all four fenced addresses and values first, in registers of their own, then the four stores back to back
         auto four = [&](const u64x2 k01, const u64x2 k23, const f32x4 v) {
-            F.template st<float>(p.dst + 4 * k01[0], p.scale * v[0]);
-            F.template st<float>(p.dst + 4 * k01[1], p.scale * v[1]);
-            F.template st<float>(p.dst + 4 * k23[0], p.scale * v[2]);
-            F.template st<float>(p.dst + 4 * k23[1], p.scale * v[3]);
+            typename Fence<V>::Handle h0 = F.template fenced<4>(p.dst + 4 * k01[0]), h1 = F.template fenced<4>(p.dst + 4 * k01[1]),
+                                      h2 = F.template fenced<4>(p.dst + 4 * k23[0]), h3 = F.template fenced<4>(p.dst + 4 * k23[1]);
+            float d0 = p.scale * v[0], d1 = p.scale * v[1], d2 = p.scale * v[2], d3 = p.scale * v[3];
+            Fence<V>::keep_apart(h0, h1, h2, h3, d0, d1, d2, d3);
+            F.template st_fenced<float>(h0, d0);
+            F.template st_fenced<float>(h1, d1);
+            F.template st_fenced<float>(h2, d2);
+            F.template st_fenced<float>(h3, d3);
         };
         // measured: the nontemporal hint on the source stream slows the scattered stores
         if (F.whole_run(p.idx, 32 * n4) && F.whole_run(p.src, 16 * n4)) {
