@@ -18,6 +18,7 @@ Parity status: every function is pinned by the CPU tests (printed example of
 Section 4.3, brute force on tiny pools, equality with the modulo definition,
 textbook NumPy routines on in-bounds inputs) EXCEPT the values left at
 locations that a kernel's own wrapped stores alias with its own live data:
-the paper leaves them unspecified ("potentially corrupt their data",
-Section 4.3), so they are "parity unpinned" and the tests exclude them.
+the paper leaves them unspecified (Section 4.3 only says that an offending
+kernel may damage its own data), so they are "parity unpinned" and the tests
+exclude them.
 """
