@@ -137,6 +137,49 @@ def test_modulo_fence_on_partitions_of_odd_size_and_alignment():
         r.close()
 
 
+def test_modulo_scatter_and_indexed_saxpy_through_indices_that_wrap_whole_partitions():
+    """Indices and offsets that are too large by whole multiples of the (odd) partition size: the modulo rule brings
+    every such access back to the element an in-range index would have named (not so for negative ones: the rule
+    works on the wrap-around difference, and 2^64 is no multiple of an odd size), so the launch is free of aliasing by
+    construction, every wrapped access is counted by the oracle, and the whole image must match bit for bit
+    (vector path and, through a misaligned index array, the per-element path)."""
+    sizes = [3 * MiB + 256, 5 * MiB + 768]
+    r = FlexRig(sizes)
+    try:
+        g = si.rng(6, 51)
+        t = 1
+        base, size = r.table[t]
+        per = size // 4                                   # the partition in 4-byte elements (size is a multiple of 256)
+        n = 50003
+        for shift in (0, 8):                              # shift 8: the 64-bit index array is not 16-byte aligned
+            src, dst, idx, x, y, off = (r.alloc(t, 4 * n), r.alloc(t, 4 * n), r.alloc(t, 8 * n + 16), r.alloc(t, 4 * n),
+                                        r.alloc(t, 4 * n), r.alloc(t, 4 * n + 16))
+            r.upload(t, src, si.uniform_f32(g, n))
+            r.upload(t, dst, np.zeros(n, np.float32))
+            k = g.permutation(n).astype(np.int64)
+            far = g.choice(n, size=n // 20, replace=False)
+            k[far] += g.integers(1, 1000, size=far.size) * per
+            r.upload(t, idx + shift, k)
+            gd.gd_launch_fenced(r.pool, t, gd.GD_K_SCATTER_F32_I64, gd.gd_args_scatter(dst, src, idx + shift, n, -2.0, 0), mode=gd.GD_FENCE_MODULO)
+            r.sim.run("scatter_f32_i64", (base, size), ok.MODE_MODULO, dst, src, idx + shift, -2.0, n)
+            assert r.sim.last[2] >= far.size and r.sim.last[0] == 0
+            assert r.images_equal(), f"scatter, shift {shift}"
+            o = np.arange(n, dtype=np.int64)
+            o[far] += g.integers(1, 300, size=far.size) * per
+            assert np.abs(o).max() < 1 << 31
+            r.upload(t, x, si.uniform_f32(g, n))
+            r.upload(t, y, si.uniform_f32(g, n))
+            r.upload(t, off + shift // 2, o.astype(np.int32))
+            gd.gd_launch_fenced(r.pool, t, gd.GD_K_SAXPY_IDX, gd.gd_args_saxpy_idx(x, y, off + shift // 2, n, 0.625, 0), mode=gd.GD_FENCE_MODULO)
+            r.sim.run("saxpy_idx", (base, size), ok.MODE_MODULO, x, y, off + shift // 2, 0.625, n)
+            assert r.sim.last[2] >= far.size and r.sim.last[0] == 0
+            assert rel_frobenius(r.download(y, np.float32, n), r.sim.view(y, np.float32, n)) <= 1e-5
+            assert r.images_equal(skip=[(y, 4 * n)]), f"saxpy, shift {shift}"
+            r.upload(t, y, r.sim.view(y, np.float32, n).copy())
+    finally:
+        r.close()
+
+
 def test_modulo_mode_rmsnorm_and_gemm_match_the_oracle():
     r = FlexRig([6 * MiB + 512, 2 * MiB + 256])
     try:

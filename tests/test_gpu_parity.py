@@ -275,6 +275,60 @@ def test_triad_array_split_on_a_partition_larger_than_4gib():
         r.close()
 
 
+def test_indexed_kernels_on_a_partition_larger_than_4gib():
+    """Scatter, gather and indexed saxpy on the 64-bit rule (8 GiB partition, arrays above its 4 GiB line), with a
+    twentieth of the indices off by whole multiples of the partition size, up and down: the bitwise rule brings each
+    of them back to the element the in-range index names, so the result must equal the oracle's on the in-bounds twin
+    of the launch (plain addresses, in-range indices, same values), bit for bit for the moved data."""
+    r = Rig([8 * GiB], fill=None, simulate=False)
+    try:
+        base, size = r.row(0)
+        g = si.rng(0, 46)
+        n = 40003
+        per = size // 4
+        r.alloc(0, 5 * GiB)
+        src, dst, idx, out, x, y, off = (r.alloc(0, 4 * n), r.alloc(0, 4 * n), r.alloc(0, 8 * n), r.alloc(0, 4 * n),
+                                         r.alloc(0, 4 * n), r.alloc(0, 4 * n), r.alloc(0, 4 * n))
+        assert src - base > 4 * GiB
+        vs, vx, vy = si.uniform_f32(g, n), si.uniform_f32(g, n), si.uniform_f32(g, n)
+        k0 = g.permutation(n).astype(np.int64)
+        far = g.choice(n, size=n // 20, replace=False)
+        k = k0.copy()
+        k[far] += g.integers(1, 1 << 20, size=far.size) * per * g.choice([-1, 1], size=far.size)
+        r.upload(0, src, vs)
+        r.upload(0, idx, k)
+        r.dview(dst, np.float32, n).zero_()
+        # the in-bounds twin
+        sim = ok.SimPool(1 << 30, 32 * n, 0)
+        t_src, t_dst, t_idx, t_out = (sim.pool_base + 4 * n * j for j in (0, 1, 2, 4))
+        sim.view(t_src, np.float32, n)[:] = vs
+        sim.view(t_idx, np.int64, n)[:] = k0
+        twin = (sim.pool_base, 1 << 30)
+        r.launch(0, gd.GD_K_SCATTER_F32_I64, gd.gd_args_scatter(dst, src, idx, n, -1.5, 0))
+        sim.run("scatter_f32_i64", twin, ok.MODE_BITWISE, t_dst, t_src, t_idx, -1.5, n)
+        assert np.array_equal(r.download(dst, np.float32, n).view(np.uint32), sim.view(t_dst, np.uint32, n))
+        r.launch(0, gd.GD_K_GATHER32_I64, gd.gd_args_gather(out, dst, idx, n))
+        sim.run("gather32_i64", twin, ok.MODE_BITWISE, t_out, t_dst, t_idx, n)
+        assert np.array_equal(r.download(out, np.float32, n).view(np.uint32), sim.view(t_out, np.uint32, n))
+        # saxpy: int32 offsets reach +-2^31 elements = 8 GiB = exactly one partition size either way
+        o = np.arange(n, dtype=np.int64)
+        o[far] += per * g.choice([-1, 1], size=far.size)
+        o[o >= 1 << 31] -= 2 * per
+        r.upload(0, x, vx)
+        r.upload(0, y, vy)
+        r.upload(0, off, o.astype(np.int32))
+        t_x, t_y, t_off = t_src, t_dst, t_out
+        sim.view(t_x, np.float32, n)[:] = vx
+        sim.view(t_y, np.float32, n)[:] = vy
+        sim.view(t_off, np.int32, n)[:] = np.arange(n, dtype=np.int32)
+        r.launch(0, gd.GD_K_SAXPY_IDX, gd.gd_args_saxpy_idx(x, y, off, n, 0.375, 0))
+        sim.run("saxpy_idx", twin, ok.MODE_BITWISE, t_x, t_y, t_off, 0.375, n)
+        assert rel_frobenius(r.download(y, np.float32, n), sim.view(t_y, np.float32, n)) <= FP32_TOL
+        assert np.array_equal(r.download(x, np.float32, n), vx) and np.array_equal(r.download(src, np.float32, n), vs)
+    finally:
+        r.close()
+
+
 # ---------------------------------------------------------------------------
 # indexed saxpy (configuration 1 shape) with out-of-range offsets
 # ---------------------------------------------------------------------------
