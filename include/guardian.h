@@ -12,8 +12,9 @@
  * partition and an in-partition access is unchanged.
  *
  * Conventions.  Device addresses cross this ABI as uint64_t.  The library
- * never dereferences pool memory on the host, so every call except
- * gd_launch_fenced also works with made-up addresses and without a GPU.  All
+ * never dereferences pool memory on the host, so every call that launches no
+ * kernel (all but gd_launch_fenced, gd_sum_f32_noalloc and the gd_probe_*
+ * measurement aids) also works with made-up addresses and without a GPU.  All
  * functions return a gd_status; on error, out-parameters are left untouched.
  * Nothing aborts, nothing throws across the ABI (host allocation failure is
  * reported as GD_ENOMEM).  A pool is protected by one mutex: calls on the same
@@ -82,7 +83,8 @@ int gd_pool_create(uint64_t dev_base, uint64_t dev_bytes, const uint64_t *part_b
  * multiples of GD_GRANULE and at least GD_MIN_PARTITION (else GD_ENOTPOW2);
  * partitions are placed in tenant order, each at the lowest GD_GRANULE-aligned
  * free address.  Kernels on such a pool can only be launched with
- * GD_FENCE_MODULO, GD_FENCE_CHECK or GD_FENCE_NONE (GD_FENCE_BITWISE: GD_EINVAL);
+ * GD_FENCE_MODULO, GD_FENCE_CHECK, GD_FENCE_HWCHECK or GD_FENCE_NONE
+ * (GD_FENCE_BITWISE: GD_EINVAL);
  * gd_tenant_attach on it follows the same placement rule. */
 int gd_pool_create_flex(uint64_t dev_base, uint64_t dev_bytes, const uint64_t *part_bytes,
                         int n_tenants, gd_pool **out);
