@@ -45,11 +45,11 @@ __global__ __launch_bounds__(1024) void k_fence_addrs(gd_args_fence_addrs p, Fen
         uint64_t f;
         bool ok;
         switch (p.width) {
-        case 1: f = F.template address<1>(a); ok = F.template inside<1>(a); break;
-        case 2: f = F.template address<2>(a); ok = F.template inside<2>(a); break;
-        case 4: f = F.template address<4>(a); ok = F.template inside<4>(a); break;
-        case 8: f = F.template address<8>(a); ok = F.template inside<8>(a); break;
-        default: f = F.template address<16>(a); ok = F.template inside<16>(a); break;
+        case 1: f = F.template lane_address<1>(a); ok = F.template inside<1>(a); break;
+        case 2: f = F.template lane_address<2>(a); ok = F.template inside<2>(a); break;
+        case 4: f = F.template lane_address<4>(a); ok = F.template inside<4>(a); break;
+        case 8: f = F.template lane_address<8>(a); ok = F.template inside<8>(a); break;
+        default: f = F.template lane_address<16>(a); ok = F.template inside<16>(a); break;
         }
         if (!ok) { F.fault(); f = ~(uint64_t)0; }
         if (!F.template inside<8>(p.out + 8 * i)) { F.fault(); continue; }

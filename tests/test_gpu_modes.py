@@ -108,6 +108,16 @@ def test_modulo_fence_on_partitions_of_odd_size_and_alignment():
                 got = r.download(dst, np.uint64, n)
                 assert np.array_equal(got, ok.fence_array(base, size, raw, width, ok.MODE_MODULO))
                 assert got.min() >= base and got.max() + width <= base + size
+            # whole wavefronts of addresses inside the partition (the per-lane rule's wave-uniform shortcut), the last
+            # 64 bytes of the partition among them (inside or not, depending on the width), then mixed wavefronts
+            inb = np.uint64(base) + g.integers(0, size - 16, size=n, dtype=np.uint64)
+            inb[:64] = np.uint64(base + size) - np.arange(1, 65, dtype=np.uint64)
+            inb[n // 2:] = raw[n // 2:]
+            r.upload(t, src, inb)
+            for width in (1, 2, 4, 8, 16):
+                gd.gd_launch_fenced(r.pool, t, gd.GD_K_FENCE_ADDRS, gd.gd_args_fence_addrs(dst, src, n, width, 0), mode=gd.GD_FENCE_MODULO)
+                r.sim.run("fence_addrs", (base, size), ok.MODE_MODULO, dst, src, width, n)
+                assert np.array_equal(r.download(dst, np.uint64, n), ok.fence_array(base, size, inb, width, ok.MODE_MODULO)), width
             # a store loop twice as long as the partition, from a pointer in front of it: wraps, stays inside
             gd.gd_launch_fenced(r.pool, t, gd.GD_K_STORE_TID, gd.gd_args_store_tid(base - 1000 * 4, 2 * size // 4, 40 + t, 0), mode=gd.GD_FENCE_MODULO)
             r.sim.run("store_tid", (base, size), ok.MODE_MODULO, base - 1000 * 4, 40 + t, 2 * size // 4)
