@@ -4,6 +4,7 @@
 #include "pool.hpp"
 
 #include <algorithm>
+#include <memory>
 #include <new>
 
 namespace gd {
@@ -57,16 +58,13 @@ int pool_create(uint64_t dev_base, uint64_t dev_bytes, const uint64_t *part_byte
     if (!out || n < 0 || (n > 0 && !part_bytes)) return GD_EINVAL;
     if (dev_base + dev_bytes < dev_base) return GD_EINVAL;           // range wraps 2^64
 
-    Pool *p = new (std::nothrow) Pool;
+    std::unique_ptr<Pool> p(new (std::nothrow) Pool);      // freed on every early return and if anything below throws
     if (!p) return GD_ENOMEM;
     p->dev_base = dev_base;
     p->dev_bytes = dev_bytes;
     p->flex = flex;
     for (int i = 0; i < n; ++i)
-        if (!size_ok(*p, part_bytes[i])) {
-            delete p;
-            return GD_ENOTPOW2;
-        }
+        if (!size_ok(*p, part_bytes[i])) return GD_ENOTPOW2;
     p->rows.resize(n);
 
     // power-of-two pools: by decreasing size (packs without gaps); flex pools: tenant order
@@ -77,10 +75,7 @@ int pool_create(uint64_t dev_base, uint64_t dev_bytes, const uint64_t *part_byte
                          [&](int x, int y) { return part_bytes[x] > part_bytes[y]; });
     for (int t : order) {
         uint64_t where;
-        if (!place(*p, part_bytes[t], &where)) {
-            delete p;
-            return GD_ENOMEM;
-        }
+        if (!place(*p, part_bytes[t], &where)) return GD_ENOMEM;
         Partition &r = p->rows[t];
         r.attached = true;
         r.base = where;
@@ -89,7 +84,7 @@ int pool_create(uint64_t dev_base, uint64_t dev_bytes, const uint64_t *part_byte
         r.free_blocks[where] = part_bytes[t];
         r.live.clear();
     }
-    *out = p;
+    *out = p.release();
     return GD_OK;
 }
 
@@ -102,13 +97,15 @@ int tenant_attach(Pool *p, uint64_t bytes, int *tenant_out)
     if (!place(*p, bytes, &where)) return GD_ENOMEM;
     size_t slot = 0;
     while (slot < p->rows.size() && p->rows[slot].attached) ++slot;
+    // what can fail (host allocations) comes first and changes nothing; the row is then filled in without allocating
+    std::map<uint64_t, uint64_t> whole;
+    whole.emplace(where, bytes);
     if (slot == p->rows.size()) p->rows.emplace_back();
     Partition &r = p->rows[slot];
     r.attached = true;
     r.base = where;
     r.size = bytes;
-    r.free_blocks.clear();
-    r.free_blocks[where] = bytes;
+    r.free_blocks.swap(whole);
     r.live.clear();
     *tenant_out = (int)slot;
     return GD_OK;
@@ -180,11 +177,27 @@ int alloc(Pool *p, int tenant, uint64_t bytes, uint64_t align, uint64_t *dptr_ou
         const uint64_t start = it->first, len = it->second, stop = start + len;
         uint64_t at;
         if (!align_up(start, align, &at) || at >= stop || stop - at < need) continue;
-        // split: [start, at) stays free, [at, at+need) is taken, [at+need, stop) stays free
-        r->free_blocks.erase(it);
-        if (at > start) r->free_blocks[start] = at - start;
-        if (at + need < stop) r->free_blocks[at + need] = stop - (at + need);
-        r->live[at] = need;
+        // split: [start, at) stays free, [at, at+need) is taken, [at+need, stop) stays free.  The steps that
+        // allocate a node come first and are undone if a later one fails; the rest cannot fail.
+        auto taken = r->live.emplace(at, need).first;
+        if (at > start && at + need < stop) {              // two remainders: one new node
+            try {
+                r->free_blocks.emplace(at + need, stop - (at + need));
+            } catch (...) {
+                r->live.erase(taken);
+                throw;
+            }
+            it->second = at - start;
+        } else if (at > start) {                           // front remainder only: the node shrinks
+            it->second = at - start;
+        } else if (at + need < stop) {                     // back remainder only: the node moves
+            auto node = r->free_blocks.extract(it);
+            node.key() = at + need;
+            node.mapped() = stop - (at + need);
+            r->free_blocks.insert(std::move(node));
+        } else {
+            r->free_blocks.erase(it);
+        }
         *dptr_out = at;
         return GD_OK;
     }
@@ -200,7 +213,7 @@ int free_(Pool *p, int tenant, uint64_t dptr)
     auto it = r->live.find(dptr);
     if (it == r->live.end()) return GD_EINVAL;
     uint64_t start = it->first, len = it->second;
-    r->live.erase(it);
+    auto node = r->live.extract(it);          // kept: it becomes the free list's node if no neighbour absorbs the block (no allocation, cannot fail)
     // merge with the free block behind and the one in front
     auto next = r->free_blocks.lower_bound(start);
     if (next != r->free_blocks.end() && next->first == start + len) {
@@ -214,7 +227,8 @@ int free_(Pool *p, int tenant, uint64_t dptr)
             return GD_OK;
         }
     }
-    r->free_blocks[start] = len;
+    node.mapped() = len;
+    r->free_blocks.insert(std::move(node));
     return GD_OK;
 }
 

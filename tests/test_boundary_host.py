@@ -356,3 +356,26 @@ def test_pool_is_safe_to_use_from_several_threads(tmp_path):
         run = subprocess.run([exe], capture_output=True, text=True, timeout=300, env=dict(os.environ, **options))
         assert run.returncode == 0, (flags, run.returncode, run.stdout[-2000:], run.stderr[-4000:])
         assert "failures 0" in run.stdout
+
+
+def test_host_allocation_failures_come_back_as_status_codes_and_lose_nothing(tmp_path):
+    """tests/native/abi_nothrow.cpp replaces operator new with one that fails on the k-th allocation and calls the
+    entry points that allocate (gd_pool_create, gd_alloc, gd_free, gd_tenant_attach) through the built library with
+    k = 0, 1, 2, ...: every failing call must return GD_ENOMEM with its out-parameter untouched, nothing may abort,
+    and afterwards the whole partition must still be allocatable as one block."""
+    import shutil
+    import subprocess
+    if shutil.which("g++") is None:
+        pytest.skip("needs g++")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    libdir = os.path.join(root, "paper_2401_09290_amd")
+    gd.lib()                                                   # fails loudly if the library is not built
+    exe = str(tmp_path / "abi_nothrow")
+    build = subprocess.run(["g++", "-O1", "-g", "-std=c++17", "-o", exe, os.path.join(root, "tests", "native", "abi_nothrow.cpp"),
+                            "-L" + libdir, "-lguardian", "-Wl,-rpath," + libdir], capture_output=True, text=True)
+    assert build.returncode == 0, build.stderr
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert run.returncode == 0, (run.returncode, run.stdout[-2000:], run.stderr[-4000:])
+    assert "problems 0" in run.stdout and "injected" in run.stdout
+    injected = int(run.stdout.split("injected")[1].split()[0])
+    assert injected >= 8                                       # failures really were injected at several points
