@@ -763,7 +763,7 @@ def test_recarve_mid_run_leaves_other_tenants_untouched():
 
 
 # ---------------------------------------------------------------------------
-# the two measurement aids (no tenant, no fence): they compute what they say
+# the measurement aids: they compute what they say
 # ---------------------------------------------------------------------------
 
 def test_gather_policy_probe_is_a_gather_for_every_policy():
