@@ -65,3 +65,71 @@ def test_fenced_launches_recorded_in_a_graph_replay_to_the_oracle_image():
             assert np.array_equal(g2, w2), f"replay {replay}: bytes outside the triad results differ"
     finally:
         r.close()
+
+
+def test_every_kind_of_kernel_and_the_allocation_free_sum_replay_from_a_graph():
+    """One graph holding a gather, a scatter, the two-pass sum, the allocation-free sum (the entry point meant for
+    callers under capture), an RMSNorm and an MFMA GEMM: every replay, with eager wipes of all outputs in between,
+    must reproduce what the oracle computes for the same launches."""
+    from harness import assert_bf16_close
+    r = Rig([32 * MiB, 4 * MiB])
+    try:
+        g = si.rng(3, 60)
+        n = 100003
+        tab, idx, out, src, dst = r.alloc(0, 4 * n), r.alloc(0, 8 * n), r.alloc(0, 4 * n), r.alloc(0, 4 * n), r.alloc(0, 4 * n)
+        ws, s_ref, s_out = r.alloc(0, gd.GD_SUM_WORKSPACE), r.alloc(0, 256), r.alloc(0, 256)
+        rows, cols = 64, 1024
+        x, y, gain = r.alloc(0, 2 * rows * cols), r.alloc(0, 2 * rows * cols), r.alloc(0, 2 * cols)
+        M, N, K = 256, 512, 256
+        A, B, Cc = r.alloc(0, 2 * M * K), r.alloc(0, 2 * N * K), r.alloc(0, 2 * M * N)
+        r.upload(0, tab, si.uniform_f32(g, n))
+        r.upload(0, idx, g.integers(0, n, size=n, dtype=np.int64))
+        r.upload(0, src, si.uniform_f32(g, n, 0.0, 1.0))
+        perm = r.alloc(0, 8 * n)
+        r.upload(0, perm, g.permutation(n).astype(np.int64))
+        r.upload(0, x, si.f32_to_bf16_bits(si.normal_f32(g, rows * cols)))
+        r.upload(0, gain, si.f32_to_bf16_bits(si.uniform_f32(g, cols, 0.5, 1.5)))
+        r.upload(0, A, si.f32_to_bf16_bits(si.normal_f32(g, M * K) * np.float32(K ** -0.5)))
+        r.upload(0, B, si.f32_to_bf16_bits(si.normal_f32(g, N * K)))
+        outputs = [(out, 4 * n), (dst, 4 * n), (s_ref, 4), (s_out, 4), (y, 2 * rows * cols), (Cc, 2 * M * N)]
+
+        def launches(stream):
+            r.launch(0, gd.GD_K_GATHER32_I64, gd.gd_args_gather(out, tab, idx, n), stream=stream)
+            r.launch(0, gd.GD_K_SCATTER_F32_I64, gd.gd_args_scatter(dst, src, perm, n, 2.0, 0), stream=stream)
+            r.launch(0, gd.GD_K_SUM_F32, gd.gd_args_sum(s_ref, src, ws, n), stream=stream)
+            gd.gd_sum_f32_noalloc(r.pool, 0, s_out, src, n, stream=stream)
+            r.launch(0, gd.GD_K_RMSNORM_BF16, gd.gd_args_rmsnorm(y, x, gain, rows, cols, 1e-6, 0), stream=stream)
+            r.launch(0, gd.GD_K_GEMM_BF16, gd.gd_args_gemm(Cc, A, B, M, N, K, 1), stream=stream)
+
+        r.oracle("gather32_i64", 0, out, tab, idx, n)
+        r.oracle("scatter_f32_i64", 0, dst, src, perm, 2.0, n)
+        r.oracle("sum_f32", 0, s_ref, src, n)
+        r.oracle("rmsnorm_bf16", 0, y, x, gain, rows, cols, 1e-6)
+        r.oracle("gemm_bf16", 0, Cc, A, B, M, N, K, 1, 0, M, 0, N)
+        want_sum = float(r.sim.view(s_ref, np.float32, 1)[0])
+
+        side = torch.cuda.Stream()
+        # the allocation-free sum looks its array up on its first call on a device: that call stays outside the capture
+        gd.gd_sum_f32_noalloc(r.pool, 0, s_out, src, 16, stream=side.cuda_stream)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            launches(torch.cuda.current_stream().cuda_stream)
+        for replay in range(3):
+            for (p, nb) in outputs:
+                r.dview(p, np.uint8, nb).fill_(0xCD)
+            r.dview(ws, np.uint8, gd.GD_SUM_WORKSPACE).fill_(0xCD)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(r.download(out, np.uint32, n), r.sim.view(out, np.uint32, n)), replay
+            assert np.array_equal(r.download(dst, np.uint32, n), r.sim.view(dst, np.uint32, n)), replay
+            a, b = r.download(s_ref, np.uint32, 1)[0], r.download(s_out, np.uint32, 1)[0]
+            assert a == b, (replay, hex(int(a)), hex(int(b)))
+            assert abs(float(np.uint32(a).view(np.float32)) - want_sum) <= FP32_TOL * want_sum
+            got_y, want_y = r.download(y, np.uint16, rows * cols), r.sim.view(y, np.uint16, rows * cols)
+            assert rel_frobenius(si.bf16_bits_to_f32(got_y), si.bf16_bits_to_f32(want_y)) <= 1e-3 and np.mean(got_y != want_y) < 0.02
+            assert_bf16_close(r.download(Cc, np.uint16, M * N), r.sim.view(Cc, np.uint16, M * N), abs_tol=3e-5, what=f"gemm, replay {replay}")
+            r.assert_images_equal(skip=outputs + [(ws, gd.GD_SUM_WORKSPACE)], what=f"replay {replay}")
+    finally:
+        r.close()
