@@ -336,3 +336,53 @@ def test_config5_mixed_tenants_full_size_kernels_and_recarve():
         assert float(r.download(out, np.float32, 1)[0]) == got
     finally:
         r.close()
+
+
+def test_copy_and_triad_of_more_than_2_pow_32_elements():
+    """Maximum sizes: arrays of 2^32 + 1027 fp32 elements (16 GiB each) in a 64 GiB partition, so that element
+    indices, byte offsets and tile counts all pass 2^32.  The values are an address-dependent pattern made on the
+    device; the whole result is compared on the device with what the definition gives (copy: the same bits; triad:
+    one fused multiply-add per element, the kernel's own precision), and the oracle recomputes sampled windows --
+    the first MiB, and the MiB in front of element 2^32 together with everything behind it -- from the bytes the kernel read."""
+    n = (1 << 32) + 1027
+    r = Rig([64 * GiB], fill=None, simulate=False)
+    try:
+        base, size = r.row(0)
+        a, b, c = (r.alloc(0, 4 * n) for _ in range(3))
+        chunk = 1 << 28
+        for p, salt in ((b, 0x9E3779B1), (c, 0x85EBCA77)):
+            view = r.dview(p, np.float32, n)
+            for lo in range(0, n, chunk):
+                hi = min(n, lo + chunk)
+                i = torch.arange(lo, hi, dtype=torch.int64, device="cuda")
+                view[lo:hi] = (((i * salt) >> 7) & 0xFFFFF).to(torch.float32) * (1.0 / (1 << 19)) - 1.0     # exact in fp32, in [-1, 1)
+                del i
+        r.dview(a, np.uint8, 4 * n).fill_(0x5A)
+        s = 0.6180339887
+        windows = [(0, 1 << 18), ((1 << 32) - (1 << 18), (1 << 18) + 1027)]      # the second one crosses element 2^32 and ends with the arrays
+        for kid, args, oname in ((gd.GD_K_COPY, gd.gd_args_copy(a, b, n), "copy"), (gd.GD_K_TRIAD, gd.gd_args_triad(a, b, c, n, s, 0), "triad")):
+            r.launch(0, kid, args)
+            torch.cuda.synchronize()
+            va, vb, vc = (r.dview(p, np.float32, n) for p in (a, b, c))
+            for lo in range(0, n, chunk):
+                hi = min(n, lo + chunk)
+                if oname == "copy":
+                    assert torch.equal(va[lo:hi].view(torch.int32), vb[lo:hi].view(torch.int32)), (oname, lo)
+                else:
+                    want = torch.addcmul(vb[lo:hi].double(), vc[lo:hi].double(), torch.tensor(s, dtype=torch.float32, device="cuda").double()).float()
+                    assert torch.equal(va[lo:hi], want), (oname, lo)        # fp64 product and sum rounded once = the fused multiply-add
+                    del want
+            for (lo, cnt) in windows:
+                sim = ok.SimPool(1 << 30, 3 * 4 * cnt, 0)
+                sa, sb, sc = sim.pool_base, sim.pool_base + 4 * cnt, sim.pool_base + 8 * cnt
+                sim.view(sb, np.float32, cnt)[:] = r.download(b + 4 * lo, np.float32, cnt)
+                sim.view(sc, np.float32, cnt)[:] = r.download(c + 4 * lo, np.float32, cnt)
+                if oname == "copy":
+                    sim.run("copy", (sim.pool_base, 1 << 30), ok.MODE_BITWISE, sa, sb, cnt)
+                    assert np.array_equal(r.download(a + 4 * lo, np.uint32, cnt), sim.view(sa, np.uint32, cnt)), (oname, lo)
+                else:
+                    sim.run("triad", (sim.pool_base, 1 << 30), ok.MODE_BITWISE, sa, sb, sc, float(np.float32(s)), cnt)
+                    assert rel_frobenius(r.download(a + 4 * lo, np.float32, cnt), sim.view(sa, np.float32, cnt)) <= FP32_TOL, (oname, lo)
+            r.dview(a, np.uint8, 4 * n).fill_(0x5A)
+    finally:
+        r.close()

@@ -44,6 +44,8 @@ def test_store_tid_in_bounds_overrun_and_foreign_pointer(rig2):
              (1, b0 + 64, 9, 777),                    # tenant 1 passes a pointer into partition 0
              (1, b1 - 4 * 100, 10, 300),              # starts in front of its partition
              (0, b0 + 2, 11, 5),                      # misaligned pointer: low bits dropped
+             (1, (1 << 64) - 8192 + 4, 13, 5000),     # a pointer just below 2^64: the element addresses wrap through zero
+             (0, 0, 14, 3000),                        # the null pointer
              (0, b0, 12, 0)]                          # empty launch
     for tenant, A, j, n in cases:
         r.launch(tenant, gd.GD_K_STORE_TID, gd.gd_args_store_tid(A, n, j, 0))
