@@ -338,7 +338,7 @@ def test_config5_mixed_tenants_full_size_kernels_and_recarve():
         r.close()
 
 
-def test_copy_and_triad_of_more_than_2_pow_32_elements():
+def test_copy_triad_and_sum_of_more_than_2_pow_32_elements():
     """Maximum sizes: arrays of 2^32 + 1027 fp32 elements (16 GiB each) in a 64 GiB partition, so that element
     indices, byte offsets and tile counts all pass 2^32.  The values are an address-dependent pattern made on the
     device; the whole result is compared on the device with what the definition gives (copy: the same bits; triad:
@@ -384,5 +384,16 @@ def test_copy_and_triad_of_more_than_2_pow_32_elements():
                     sim.run("triad", (sim.pool_base, 1 << 30), ok.MODE_BITWISE, sa, sb, sc, float(np.float32(s)), cnt)
                     assert rel_frobenius(r.download(a + 4 * lo, np.float32, cnt), sim.view(sa, np.float32, cnt)) <= FP32_TOL, (oname, lo)
             r.dview(a, np.uint8, 4 * n).fill_(0x5A)
+        # the sum over the same 2^32 + 1027 values (grid-stride loop past 2^32): against the fp64 sum taken chunk by chunk
+        # on the device; the values are centred on zero, so the bound is relative to the sum of magnitudes
+        ws, out = r.alloc(0, gd.GD_SUM_WORKSPACE), r.alloc(0, 256)
+        r.launch(0, gd.GD_K_SUM_F32, gd.gd_args_sum(out, b, ws, n))
+        torch.cuda.synchronize()
+        vb = r.dview(b, np.float32, n)
+        exact = sum(float(vb[lo:min(n, lo + chunk)].double().sum().item()) for lo in range(0, n, chunk))
+        magnitude = sum(float(vb[lo:min(n, lo + chunk)].double().abs().sum().item()) for lo in range(0, n, chunk))
+        got = float(r.download(out, np.float32, 1)[0])
+        assert abs(got - exact) <= FP32_TOL * magnitude, (got, exact, magnitude)
+        assert abs(exact) > 1.0                                  # a zero result would pass the bound for the wrong reason
     finally:
         r.close()
