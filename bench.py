@@ -164,9 +164,9 @@ def run_c3(torch, gd, si, args):
     torch.cuda.synchronize()
     del host
 
-    def round_of(mode):
+    def round_of(mode, active=tenants):
         def go():
-            for (t, a, b, c, s), st in zip(plan, streams):
+            for (t, a, b, c, s), st in zip(plan[:active], streams):
                 gd.gd_launch_fenced(dp.pool, t, gd.GD_K_COPY, gd.gd_args_copy(a, b, n), stream=st.cuda_stream, mode=mode)
                 gd.gd_launch_fenced(dp.pool, t, gd.GD_K_TRIAD, gd.gd_args_triad(a, b, c, n, s, 0), stream=st.cuda_stream, mode=mode)
         return go
@@ -177,6 +177,19 @@ def run_c3(torch, gd, si, args):
         dev, wall = timed_rounds(torch, streams, round_of(mode), args.steps, args.warmup)
         res[name] = {"seconds": dev, "wall_seconds": wall, "GBps": bytes_round * args.steps / dev / 1e9}
         log(f"[c3] {name}: {res[name]['GBps']:.1f} GB/s aggregate over {tenants} streams ({dev / args.steps * 1e3:.3f} ms/round)")
+
+    # the same round with 1, 2 and 4 of the tenants active (co-location, the paper's Section 7.1 setting): aggregate rate
+    by_tenants = {}
+    for active in (1, 2, 4):
+        row = {}
+        for name, mode in (("fenced", gd.GD_FENCE_BITWISE), ("unfenced", gd.GD_FENCE_NONE)):
+            dev, _ = timed_rounds(torch, streams[:active], round_of(mode, active), max(3, args.steps // 2), 1)
+            row[name + "_GBps"] = active * (8 + 12) * n * max(3, args.steps // 2) / dev / 1e9
+        row["overhead_pct"] = pct_overhead(row["fenced_GBps"], row["unfenced_GBps"])
+        by_tenants[str(active)] = row
+        log(f"[c3] {active} tenant(s) active: fenced {row['fenced_GBps']:.1f} / unfenced {row['unfenced_GBps']:.1f} GB/s aggregate")
+    by_tenants[str(tenants)] = {"fenced_GBps": res["fenced"]["GBps"], "unfenced_GBps": res["unfenced"]["GBps"],
+                                "overhead_pct": pct_overhead(res["fenced"]["GBps"], res["unfenced"]["GBps"])}
 
     # each kernel alone on tenant 0's stream: the per-launch figures of the roofline
     t, a, b, c, s = plan[0]
@@ -198,6 +211,7 @@ def run_c3(torch, gd, si, args):
         "ms_per_round_fenced": res["fenced"]["seconds"] / args.steps * 1e3,
         "wall_seconds_fenced": res["fenced"]["wall_seconds"],
         "solo": solo,
+        "aggregate_by_active_tenants": by_tenants,
         "triad_bytes_per_launch": 12 * n,
     }
 
