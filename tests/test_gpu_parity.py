@@ -810,3 +810,45 @@ def test_host_path_probe_times_three_loops_and_leaves_the_kernels_result(rig2):
         r.assert_images_equal(what="host path probe")
         assert 0 < up_to < with_launch and 0 < bare, (up_to, with_launch, bare)
         assert up_to < 1e5 and with_launch < 1e6 and bare < 1e6        # nanoseconds per call: sanity only
+
+
+def test_a_tenant_aiming_every_access_at_its_neighbour_changes_nothing_there(rig2):
+    """The threat the paper is about (Sections 1 and 3): tenant 0 passes pointers and indices that all name tenant 1's
+    memory -- a store loop over the neighbour's whole partition, a scatter whose every index points into the
+    neighbour's live arrays, a gather that tries to read them -- while tenant 1 computes on another stream.  Tenant 1's
+    partition must end up exactly as the oracle computes it from tenant 1's own launches; tenant 0 finds its accesses
+    redirected into its own partition (and reads back only its own bytes)."""
+    r = rig2
+    (b0, s0), (b1, s1) = r.row(0), r.row(1)
+    g = si.rng(0, 70)
+    n = 200000
+    va, vb, vc = (r.alloc(1, 4 * n) for _ in range(3))                  # the victim's arrays
+    r.upload(1, vb, si.uniform_f32(g, n))
+    r.upload(1, vc, si.uniform_f32(g, n))
+    src, idx, out = r.alloc(0, 4 * n), r.alloc(0, 8 * n), r.alloc(0, 4 * n)
+    secret = r.sim.view(vb, np.float32, n).copy()
+    r.upload(0, src, np.full(n, 1234.5, np.float32))
+    # indices that, added to tenant 0's own table pointer, name the victim's arrays element by element
+    aim = ((vb - src) // 4 + np.arange(n, dtype=np.int64))
+    r.upload(0, idx, aim)
+    s_att, s_vic = torch.cuda.Stream(), torch.cuda.Stream()
+    for rep in range(3):
+        r.launch(1, gd.GD_K_TRIAD, gd.gd_args_triad(va, vb, vc, n, 0.5, 0), stream=s_vic.cuda_stream)
+        r.launch(0, gd.GD_K_SCATTER_F32_I64, gd.gd_args_scatter(src, src, idx, n, 1.0, 0), stream=s_att.cuda_stream)
+        r.launch(0, gd.GD_K_GATHER32_I64, gd.gd_args_gather(out, src, idx, n), stream=s_att.cuda_stream)
+        if rep == 0:
+            torch.cuda.synchronize()
+            stolen = r.download(out, np.float32, n).copy()       # what the aimed gather brought back
+        # last, a store loop over the neighbour's whole partition (it wipes the attacker's own arrays instead:
+        # the later repetitions attack with whatever indices that leaves)
+        r.launch(0, gd.GD_K_STORE_TID, gd.gd_args_store_tid(b1, s1 // 4, 0xDEAD, 0), stream=s_att.cuda_stream)
+    torch.cuda.synchronize()
+    r.oracle("triad", 1, va, vb, vc, 0.5, n)
+    got, want = r.image(), r.sim.mem
+    lo, hi, a_lo = b1 - r.base, b1 - r.base + s1, va - r.base
+    assert np.array_equal(got[lo:a_lo], want[lo:a_lo]) and np.array_equal(got[a_lo + 4 * n:hi], want[a_lo + 4 * n:hi])
+    assert rel_frobenius(r.download(va, np.float32, n), r.sim.view(va, np.float32, n)) <= FP32_TOL
+    # the aimed gather read the attacker's own partition: none of the victim's values came back
+    assert not np.isin(stolen, secret).any()
+    # and the store loop, as long as a partition, ended up covering the attacker's own partition, word for word
+    assert (r.download(b0, np.uint32, s0 // 4) == 0xDEAD).all()
