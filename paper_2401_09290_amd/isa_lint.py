@@ -263,13 +263,18 @@ class Flow:
                 self.succs[i].append(i + 1)
         self.dst = [dests(ln) for ln in body]
         self._dom = None
+        self._reach = {}                                   # memo of reaching_at
 
     def reaching_at(self, idx, kind, reg):
         """Indices of the instructions whose write of `reg` can reach instruction idx; -1 stands for
         the value the register holds when the kernel starts."""
+        key = (idx, kind, reg)
+        if key in self._reach:
+            return self._reach[key]
         found, seen, stack = set(), set(), list(self.preds[idx])
         if not stack:
             found.add(-1)
+        self._reach[key] = found
         while stack:
             j = stack.pop()
             if j in seen:
