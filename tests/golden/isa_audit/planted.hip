@@ -67,11 +67,29 @@ __global__ void k_planted_uniform_read(planted_args p, FenceArgs fa)
     F.template st<float>(b, s);
 }
 
+// a contiguous array read 16 bytes per lane through the per-array form, but from the raw pointer: the first byte was
+// never fenced and the array never tested (under the hardware-checked rule the descriptor still bounds the access)
+template <int V>
+__global__ void k_planted_raw_tile(planted_args p, FenceArgs fa)
+{
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const Fence<V> F(fa);
+    const uint64_t q0 = (uint64_t)blockIdx.x * blockDim.x;
+    if (q0 + threadIdx.x >= p.n) return;
+    const uint32_t lane_off = Fence<V>::template tile_lane_offset<1024>(16 * threadIdx.x);
+    u32x4 v = F.template ld_tile16<u32x4>(p.x + 16 * q0, lane_off);
+    F.tile_wait(v);
+    const uint64_t b = p.y + 16 * (q0 + threadIdx.x);
+    if (!F.template inside<16>(b)) { F.fault(); return; }
+    F.template st<u32x4>(b, v);
+}
+
 #define GD_PLANT(V)                                                        \
     template __global__ void k_planted_ok<V>(planted_args, FenceArgs);        \
     template __global__ void k_planted_raw_store<V>(planted_args, FenceArgs); \
     template __global__ void k_planted_wrong_test<V>(planted_args, FenceArgs); \
-    template __global__ void k_planted_uniform_read<V>(planted_args, FenceArgs);
+    template __global__ void k_planted_uniform_read<V>(planted_args, FenceArgs); \
+    template __global__ void k_planted_raw_tile<V>(planted_args, FenceArgs);
 GD_PLANT(1)
 GD_PLANT(2)
 GD_PLANT(3)

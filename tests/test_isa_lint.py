@@ -116,13 +116,13 @@ def test_audit_follows_fenced_start_plus_offset_chains():
 
 @pytest.mark.skipif(shutil.which("hipcc") is None, reason="needs hipcc")
 def test_planted_omissions_are_reported_in_every_rule(tmp_path):
-    """tests/golden/isa_audit/planted.hip: one kernel that fences everything and three that forget the
+    """tests/golden/isa_audit/planted.hip: one kernel that fences everything and four that forget the
     fence once each, built for the five rules.  The audit must report the forgetful ones, the access they
     forgot, and nothing else."""
     import os
     src = os.path.join(os.path.dirname(__file__), "golden", "isa_audit", "planted.hip")
     rows, problems = isa_lint.lint_file(src, str(tmp_path))
-    assert len(rows) == 20
+    assert len(rows) == 25
     by = {}
     for p in problems:
         by.setdefault(p.split(":")[0], []).append(p)
@@ -132,6 +132,11 @@ def test_planted_omissions_are_reported_in_every_rule(tmp_path):
         assert raw and all("global_store_dword" in p for p in raw), (v, raw)
         uni = by.get(f"k_planted_uniform_read<{v}>", [])
         assert len(uni) == 1 and "scalar load from memory other than the kernel arguments" in uni[0], (v, uni)
+        tile = by.get(f"k_planted_raw_tile<{v}>", [])
+        if v == 5:      # any offset is bounded by the descriptor: nothing unsafe to report
+            assert not tile, tile
+        else:
+            assert tile and all("global_load_dwordx4" in p for p in tile), (v, tile)
         wrong = by.get(f"k_planted_wrong_test<{v}>", [])
         if v == 4:      # tested against the other array's address: the store's own address met no comparison
             assert len(wrong) == 1 and "does not run under a comparison of its address" in wrong[0], wrong
