@@ -673,14 +673,14 @@ def run_modes(torch, gd, si, args):
              ("hwcheck", gd.GD_FENCE_HWCHECK))
     res = {"workload": "1 tenant, 2 GiB partition, all accesses in bounds: fp32 triad 2^26 (HBM resident); triad repeated inside one launch over working sets resident in L1, L2 and the Infinity Cache (each workgroup re-reads its own 3 KiB); gather 2^24 with int64 indices"}
 
-    def sweep(label, kid, kargs, nbytes, reps):
+    def sweep(label, kid, kargs, work, reps, unit="GBps", scale=1e9):
         out = {}
         for name, mode in modes:
             sec = solo_avg_seconds(torch, st, lambda: gd.gd_launch_fenced(dp.pool, 0, kid, kargs, stream=st.cuda_stream, mode=mode), reps)
-            out[name + "_GBps"] = nbytes / sec / 1e9
+            out[name + "_" + unit] = work / sec / scale
             out[name + "_us"] = sec * 1e6
         for name, _ in modes[1:]:
-            out[name + "_overhead_pct"] = pct_overhead(out[name + "_GBps"], out["none_GBps"])
+            out[name + "_overhead_pct"] = pct_overhead(out[name + "_" + unit], out["none_" + unit])
         log(f"[modes] {label}: " + ", ".join(f"{n} {out[n + '_us']:.2f} us" for n, _ in modes)
             + " | overhead " + ", ".join(f"{n} {out[n + '_overhead_pct']:+.1f} %" for n, _ in modes[1:]))
         res[label] = out
@@ -710,6 +710,22 @@ def run_modes(torch, gd, si, args):
     idx = dp.alloc(0, 8 * ng)
     dp.upload(0, idx, g.integers(0, n, size=ng, dtype=np.int64))
     sweep("gather_i64_2^24", gd.GD_K_GATHER32_I64, gd.gd_args_gather(a, b, idx, ng), 16 * ng, args.steps)
+    # the reduction, the normalisation and the GEMM under the five rules (configuration 5 / 4 shapes)
+    ns = 1 << 27
+    ws, sout = dp.alloc(0, gd.GD_SUM_WORKSPACE), dp.alloc(0, 256)
+    sweep("sum_2^27", gd.GD_K_SUM_F32, gd.gd_args_sum(sout, b, ws, ns), 4 * ns, args.steps)        # b and c are adjacent: 2^27 values from b on
+    rows, cols = 4096, 8192
+    x, y, gain = dp.alloc(0, 2 * rows * cols), dp.alloc(0, 2 * rows * cols), dp.alloc(0, 2 * cols)
+    dp.view(x, 2 * rows * cols).view(torch.bfloat16).normal_()
+    dp.view(gain, 2 * cols).view(torch.bfloat16).uniform_(0.5, 1.5)
+    sweep("rmsnorm_4096x8192", gd.GD_K_RMSNORM_BF16, gd.gd_args_rmsnorm(y, x, gain, rows, cols, 1e-6, 0), 4 * rows * cols, args.steps)
+    M = 8192
+    A, B, Cc = (dp.alloc(0, 2 * M * M) for _ in range(3))
+    dp.view(A, 2 * M * M).view(torch.bfloat16).normal_(0.0, M ** -0.5)
+    dp.view(B, 2 * M * M).view(torch.bfloat16).normal_()
+    # bitwise and modulo run the DMA-ring kernel; checking and hardware checking need predicated resp. buffer loads
+    # and run the register-staged kernel
+    sweep("gemm_8192^3_bf16", gd.GD_K_GEMM_BF16, gd.gd_args_gemm(Cc, A, B, M, M, M, 1), 2.0 * M ** 3, max(3, args.steps // 2), unit="TFLOPs", scale=1e12)
     res["check_faults_counted"] = int(counters.sum().item())       # all accesses were in bounds: must be 0
 
     # host path, per call, Python binding included (the trivial call shows the binding's own share)

@@ -390,6 +390,9 @@ struct Fence {
         } else if constexpr (V == V_BIT32) {
             const uint32_t m = (uint32_t)mask & ~(uint32_t)(W - 1);
             return fence_and32((uint32_t)uniform_part + lane_off, m);
+        } else if constexpr (V == V_BUF) {
+            // the buffer offset of the sum: the uniform part's offset (scalar unit) plus the lane's
+            return (uint64_t)((((uint32_t)uniform_part - (uint32_t)base) + lane_off) & ~(uint32_t)(W - 1));
         } else {
             return address<W>(uniform_part + lane_off);
         }
@@ -433,6 +436,18 @@ struct Fence {
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                          :
                          : "s"(lds_addr), "v"(h), "s"(b)
+                         : "memory");
+        } else if constexpr (V == V_BUF) {
+            // the same copy as a buffer instruction: the lane's offset is range-checked against the partition's
+            // size by the memory pipeline, a lane outside delivers zeros to the LDS (measured: lane l lands in the
+            // 16-byte slot l behind M0, as with the global form).  The partition base is a multiple of 256, so
+            // bit 6 of the offset is bit 6 of the raw address and OFF can be ORed in as below.
+            typedef uint32_t words_t __attribute__((ext_vector_type(4)));
+            const words_t r = {(uint32_t)base, (uint32_t)(base >> 32) & 0xffffu, (uint32_t)mask, 0x00020000u};   // mask holds the size
+            const uint32_t off = (uint32_t)h | (uint32_t)OFF;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                         :
+                         : "s"(lds_addr), "v"(off), "s"(r)
                          : "memory");
         } else {
             const uint64_t a = h | (uint64_t)OFF;

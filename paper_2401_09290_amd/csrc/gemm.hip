@@ -306,11 +306,27 @@ __device__ __forceinline__ uint32_t ring_swizzle(uint32_t row_div4)
         asm volatile("" ::: "memory");          \
     } while (0)
 
-template <int V>
+// WHOLE (modulo rule and address checking): the launcher has found that the fence maps A, B and C each to one
+// contiguous range (Fence::whole_run; under address checking: that all three lie inside the partition, so that no
+// logical thread can be refused).  The kernel repeats that test, fences the first byte of A and of B once on the
+// scalar unit and addresses their tiles as "fenced start + offset" with the native kernel's DMA form -- the per-array
+// fence of the streaming kernels applied to a matrix.  Without it these two rules pay per DMA address: the modulo
+// rule 25 vector instructions (+17 % at 8192^3), address checking a predicated, register-staged kernel (+60 %).
+template <int V, bool WHOLE = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_n)
 {
     const Fence<V> F(fa);
+    using DmaFence = Fence<WHOLE ? (int)V_NONE : V>;        // WHOLE: the tile addresses are sums with a fenced start
+    const DmaFence D(fa);
+    uint64_t a_start = p.A, b_start = p.B;
+    if constexpr (WHOLE) {
+        if (!(F.whole_run(p.A, 2 * (uint64_t)p.M * p.K) && F.whole_run(p.B, 2 * (uint64_t)p.N * p.K) &&
+              F.whole_run(p.C, 2 * (uint64_t)p.M * p.N)))
+            return;                                             // never taken: the launcher tested the same
+        a_start = F.scalar_fence(p.A);
+        b_start = F.scalar_fence(p.B);
+    }
     // Separate arrays, so that the compiler can tell a fragment load from one stage
     // apart from a DMA into another and does not wait for the DMA.
     __shared__ __attribute__((aligned(1024))) uint8_t ring0[RSTAGE];
@@ -341,25 +357,25 @@ void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_
     const uint32_t drow = wave * 64 + (lane >> 2);
     const uint32_t dgran = (lane & 3) ^ ring_swizzle(lane >> 4);
     const uint32_t lane_off = 2 * (drow * p.K + dgran * 8);     // below 2^32: the launcher bounds K
-    const uint64_t a_tile = p.A + 2 * (uint64_t)m0 * p.K;
-    const uint64_t b_tile = p.B + 2 * (uint64_t)n0 * p.K;
+    const uint64_t a_tile = a_start + 2 * (uint64_t)m0 * p.K;
+    const uint64_t b_tile = b_start + 2 * (uint64_t)n0 * p.K;
     const uint64_t chunk_step = 2 * 16 * (uint64_t)p.K;      // 16 rows further down
     // The two DMAs of a cache line share one fenced address: A, B and the row pitch
     // 2*K are multiples of 128 bytes and k_pair of 64 elements, so the address of the
     // first half is a multiple of 128 plus the lane's granule (bits 4..5), and the
     // second half, 64 bytes further, lies in the same fenced line (see
     // Fence::dma16_unordered).
-    typename Fence<V>::SplitHandle pre[8];                 // one fenced address per DMA pair of the set
+    typename DmaFence::SplitHandle pre[8];                 // one fenced address per DMA pair of the set
     auto pre_one = [&](uint32_t k_pair, int pr) {
         const uint64_t uni = (pr < 4 ? a_tile : b_tile) + (pr & 3) * chunk_step + 2 * (uint64_t)k_pair;
-        pre[pr] = F.template fenced_split<16>(uni, lane_off);
+        pre[pr] = D.template fenced_split<16>(uni, lane_off);
     };
     auto dma_one = [&](uint8_t *stage_even, uint8_t *stage_odd, int d) {
         const int c = d >> 1;
         uint8_t *stage = (d & 1) ? stage_odd : stage_even;
         GD_LDS uint8_t *dst = (GD_LDS uint8_t *)stage + wave * 4096 + (c & 3) * 1024 + (c < 4 ? 0 : RA);
-        if (d & 1) F.template dma16_unordered<2 * RK>(pre[c], (uint32_t)(uintptr_t)dst);
-        else F.template dma16_unordered<0>(pre[c], (uint32_t)(uintptr_t)dst);
+        if (d & 1) D.template dma16_unordered<2 * RK>(pre[c], (uint32_t)(uintptr_t)dst);
+        else D.template dma16_unordered<0>(pre[c], (uint32_t)(uintptr_t)dst);
     };
 
     // 8 x 8 tiles of 16 x 16 per wavefront, v_mfma_f32_16x16x32_bf16: one instruction
@@ -776,6 +792,16 @@ int launch_mfma_probe(uint64_t operands, uint64_t out, uint32_t blocks, uint32_t
 
 // ---- launcher ---------------------------------------------------------------------------
 
+// Host twin of Fence<V>::whole_run for the two rules whose GEMM uses it (mask holds the partition size there).
+static bool whole_run_host(const FenceArgs &f, int variant, uint64_t start, uint64_t bytes)
+{
+    const uint64_t size = f.mask;
+    if (bytes > size) return false;
+    const uint64_t diff = start - f.base;                       // wrap-around, as on the device
+    if (variant == V_CHECK) return diff <= size - bytes;
+    return diff % size <= size - bytes;                          // V_MOD: the image of the first byte has `bytes` bytes behind it
+}
+
 int launch_gemm_bf16(const void *args, const FenceArgs &f, int variant, const Shape &shape,
                      hipStream_t stream)
 {
@@ -796,6 +822,21 @@ int launch_gemm_bf16(const void *args, const FenceArgs &f, int variant, const Sh
             constexpr int V = decltype(v)::value;
             // address checking needs predicated loads, and the hardware-checked rule buffer
             // instructions: the register-staged kernel has both
+            if constexpr (V == V_MOD || V == V_CHECK) {
+                // every operand mapped to one contiguous range (all inside, for address checking): fence each once
+                if (ring && !edge && whole_run_host(f, V, p.A, 2 * (uint64_t)p.M * p.K) && whole_run_host(f, V, p.B, 2 * (uint64_t)p.N * p.K) &&
+                    whole_run_host(f, V, p.C, 2 * (uint64_t)p.M * p.N)) {
+                    hipLaunchKernelGGL((k_gemm_ring<V, true>), grid, block, 0, stream, p, f, tiles_m, tiles_n);
+                    return;
+                }
+            }
+            if constexpr (V == V_BUF) {
+                // buffer offsets add up by definition: the ring's copies become buffer loads to the LDS, range-checked per lane
+                if (ring && !edge) {
+                    hipLaunchKernelGGL((k_gemm_ring<V, false>), grid, block, 0, stream, p, f, tiles_m, tiles_n);
+                    return;
+                }
+            }
             if (V == V_CHECK || V == V_BUF || edge) {
                 hipLaunchKernelGGL((k_gemm_nk256<V, true>), grid, block, 0, stream, p, f, tiles_m, tiles_n);
             } else if constexpr (V != V_CHECK && V != V_BUF) {

@@ -572,7 +572,9 @@ def dependency_problems(flow, pretty, variant, fence_offset, explicit_end, own_w
             continue                                      # the library's own partial-sum array
         words = kernarg_bytes(flow, flow.slice_of(i, regs))
         if variant == 4:
-            mine = {w for w in words if w is not None and w < explicit_end and not fence_offset <= w < fence_offset + 40}
+            # the tenant's argument block is what precedes the fence's parameters; what the library appends behind them
+            # (launch geometry) is the manager's own
+            mine = {w for w in words if w is not None and w < fence_offset}
             if not guarded_by_bounds(flow, i, mine, fence_offset):
                 problems.append(f"{pretty}: `{ln.strip()}` does not run under a comparison of its address with the partition's bounds")
         else:

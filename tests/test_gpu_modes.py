@@ -203,7 +203,9 @@ def test_modulo_mode_rmsnorm_and_gemm_match_the_oracle():
         r.sim.run("rmsnorm_bf16", (base, size), ok.MODE_MODULO, y + size, x - size, gain, rows, cols, 1e-6)
         got, want = r.download(y, np.uint16, rows * cols), r.sim.view(y, np.uint16, rows * cols)
         assert_bf16_close(got, want, what="modulo rmsnorm")
-        for (M, N, K) in ((256, 256, 128), (100, 72, 40)):
+        # (512, 256, 384): the per-array form of the DMA-ring kernel (operands mapped to one contiguous range each),
+        # here through a pointer one partition too high and one that is not mapped contiguously (fallback per lane)
+        for (M, N, K) in ((256, 256, 128), (512, 256, 384), (100, 72, 40)):
             A, B, Cc = r.alloc(0, 2 * M * K), r.alloc(0, 2 * K * N), r.alloc(0, 2 * M * N)
             r.upload(0, A, si.f32_to_bf16_bits(si.normal_f32(g, M * K) * np.float32(K ** -0.5)))
             r.upload(0, B, si.f32_to_bf16_bits(si.normal_f32(g, K * N)))
@@ -211,6 +213,18 @@ def test_modulo_mode_rmsnorm_and_gemm_match_the_oracle():
             r.sim.run("gemm_bf16", (base, size), ok.MODE_MODULO, Cc, A + size, B - 2 * size, M, N, K, 1, 0, M, 0, N)
             got, want = r.download(Cc, np.uint16, M * N), r.sim.view(Cc, np.uint16, M * N)
             assert_bf16_close(got, want, abs_tol=3e-5, what=f"modulo gemm {M}x{N}x{K}")
+            # all three operands plainly inside, and all three one partition too high
+            r.sim.run("gemm_bf16", (base, size), ok.MODE_MODULO, Cc, A, B, M, N, K, 1, 0, M, 0, N)
+            want = r.sim.view(Cc, np.uint16, M * N).copy()
+            plain = None
+            for k in (0, 1):
+                r.dev[Cc - r.base:Cc - r.base + 2 * M * N].fill_(0)
+                gd.gd_launch_fenced(r.pool, 0, gd.GD_K_GEMM_BF16, gd.gd_args_gemm(Cc + k * size, A + k * size, B + k * size, M, N, K, 1), mode=gd.GD_FENCE_MODULO)
+                got = r.download(Cc, np.uint16, M * N).copy()
+                assert_bf16_close(got, want, abs_tol=3e-5, what=f"modulo gemm {M}x{N}x{K}, operands {k} partitions up")
+                plain = got if plain is None else plain
+                assert np.array_equal(got, plain), (M, N, K, k)
+            r.dev[Cc - r.base:Cc - r.base + 2 * M * N].copy_(torch.from_numpy(want.view(np.uint8)))     # device = oracle again
         # nothing outside tenant 0's partition changed
         lo = r.table[1][0] - r.base
         assert np.all(r.dev[lo:].cpu().numpy() == 0xA5)
@@ -388,7 +402,7 @@ def test_checking_gemm_stops_threads_with_a_refused_operand_row_or_column(checke
     end = base + size
     g = si.rng(6, 91)
     total = 0
-    for (M, N, K, b_is_nk) in ((256, 256, 128, 1), (300, 200, 72, 1), (64, 40, 24, 0), (50, 70, 33, 1)):
+    for (M, N, K, b_is_nk) in ((256, 256, 128, 1), (512, 256, 384, 1), (300, 200, 72, 1), (64, 40, 24, 0), (50, 70, 33, 1)):
         A_in, B_in, C_in = r.alloc(t, 2 * M * K), r.alloc(t, 2 * K * N), r.alloc(t, 2 * M * N)
         a_bits = si.f32_to_bf16_bits(si.normal_f32(g, M * K) * np.float32(K ** -0.5))
         b_bits = si.f32_to_bf16_bits(si.normal_f32(g, K * N))
@@ -546,14 +560,19 @@ def test_hwcheck_rmsnorm_and_gemm_read_zero_outside_and_drop_stores():
             assert r.sim.last[1] > 0
             images_close_bf16(r, "hwcheck rmsnorm", 0.02 * rows * cols + 2)
             r.dview(base, np.uint8, size).copy_(torch.from_numpy(r.sim.view(base, np.uint8, size)))
-        for (M, N, K, b_is_nk) in ((256, 256, 128, 1), (300, 200, 72, 1), (50, 70, 33, 0)):
+        for (M, N, K, b_is_nk) in ((256, 256, 128, 1), (512, 256, 384, 1), (300, 200, 72, 1), (50, 70, 33, 0)):
             A, B, Cc = r.alloc(t, 2 * M * K), r.alloc(t, 2 * K * N), r.alloc(t, 2 * M * N)
             a_bits = si.f32_to_bf16_bits(si.normal_f32(g, M * K) * np.float32(K ** -0.5))
             r.upload(t, A, a_bits)
             r.upload(t, B, si.f32_to_bf16_bits(si.normal_f32(g, K * N)))
             a_cut = 2 * (K * (M - M // 3) + 16)
             r.upload(t, end - a_cut, a_bits[: a_cut // 2])
-            for (cc, aa, bb) in ((Cc, A, B), (Cc, end - a_cut, B), (end - 2 * (N * (M // 2) + N // 4), A, B)):
+            cases = [(Cc, A, B), (Cc, end - a_cut, B), (end - 2 * (N * (M // 2) + N // 4), A, B)]
+            if (2 * K) % 128 == 0:
+                # the same cut at a whole row, so that the pointer keeps the 128-byte alignment of the DMA-ring kernel:
+                # its buffer loads to the LDS deliver zeros for the rows behind the partition's end
+                cases.append((Cc, end - 2 * K * (M - M // 3), B))
+            for (cc, aa, bb) in cases:
                 gd.gd_launch_fenced(r.pool, t, gd.GD_K_GEMM_BF16, gd.gd_args_gemm(cc, aa, bb, M, N, K, b_is_nk), mode=mode)
                 r.oracle("gemm_bf16", t, cc, aa, bb, M, N, K, b_is_nk, 0, M, 0, N, mode=omode)
                 images_close_bf16(r, f"hwcheck gemm {M}x{N}x{K}", 0.02 * M * N + 2)
