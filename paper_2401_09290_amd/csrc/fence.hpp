@@ -186,8 +186,10 @@ struct Fence {
             fenced = start;
             return !inside<TILE>(start);
         } else if constexpr (V == V_MOD) {
-            fenced = address<1>(start);
-            return !(fenced - base <= mask - TILE);              // mask holds the size
+            // a start that is inside the partition already is its own image: the division is skipped (scalar branch)
+            if (start - base < mask) fenced = start;             // mask holds the size
+            else fenced = address<1>(start);
+            return !(fenced - base <= mask - TILE);
         } else {
             asm("s_and_b64 %0, %1, %2\n\ts_or_b64 %0, %0, %3" : "=&s"(fenced) : "s"(start), "s"(mask), "s"(base) : "scc");
             // offset + TILE - 1 <= mask, as "no bit above the mask" (scalar unit: no 64-bit ordered compare)
@@ -206,7 +208,10 @@ struct Fence {
     {
         if constexpr (V == V_NONE || V == V_BUF) return true;       // V_BUF: offsets wrap at 2^32 by definition
         else if constexpr (V == V_CHECK) return inside_run(start, bytes);
-        else if constexpr (V == V_MOD) return bytes <= mask && address<1>(start) - base <= mask - bytes;
+        else if constexpr (V == V_MOD) {
+            const uint64_t image = (start - base < mask) ? start : address<1>(start);
+            return bytes <= mask && image - base <= mask - bytes;
+        }
         else return (((start & mask) + (bytes ? bytes - 1 : 0)) & ~mask) == 0;    // last byte's offset <= mask, in a form the scalar unit has
     }
     __device__ __forceinline__ uint64_t scalar_fence(uint64_t start) const
