@@ -567,11 +567,22 @@ __device__ __forceinline__ uint32_t unit_swizzle(uint32_t row)
     return 2 * ((x & 1) | ((x >> 1) & 2));
 }
 
-template <int V>
+// WHOLE: as in k_gemm_ring.
+template <int V, bool WHOLE = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void k_gemm_units(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_n)
 {
     const Fence<V> F(fa);
+    using DmaFence = Fence<WHOLE ? (int)V_NONE : V>;
+    const DmaFence D(fa);
+    uint64_t a_start = p.A, b_start = p.B;
+    if constexpr (WHOLE) {
+        if (!(F.whole_run(p.A, 2 * (uint64_t)p.M * p.K) && F.whole_run(p.B, 2 * (uint64_t)p.N * p.K) &&
+              F.whole_run(p.C, 2 * (uint64_t)p.M * p.N)))
+            return;                                             // never taken: the launcher tested the same
+        a_start = F.scalar_fence(p.A);
+        b_start = F.scalar_fence(p.B);
+    }
     __shared__ __attribute__((aligned(1024))) uint8_t u0[UBYTES];
     __shared__ __attribute__((aligned(1024))) uint8_t u1[UBYTES];
     __shared__ __attribute__((aligned(1024))) uint8_t u2[UBYTES];
@@ -602,15 +613,15 @@ void k_gemm_units(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles
         const uint32_t gran = (lane & 7) ^ unit_swizzle(8 * par + (lane >> 3));
         lane_off[par] = 2 * (drow * p.K + gran * 8);           // below 2^32: the launcher bounds K
     }
-    const uint64_t a_tile = p.A + 2 * (uint64_t)m0 * p.K;
-    const uint64_t b_tile = p.B + 2 * (uint64_t)n0 * p.K;
+    const uint64_t a_tile = a_start + 2 * (uint64_t)m0 * p.K;
+    const uint64_t b_tile = b_start + 2 * (uint64_t)n0 * p.K;
     const uint64_t chunk_step = 2 * 8 * (uint64_t)p.K;           // 8 rows further down
-    typename Fence<V>::SplitHandle pre;
+    typename DmaFence::SplitHandle pre;
     auto dma = [&](bool is_b, uint32_t k0, uint8_t *unit, int c) {
         const uint64_t uni = (is_b ? b_tile : a_tile) + c * chunk_step + 2 * (uint64_t)k0;
-        pre = F.template fenced_split<16>(uni, lane_off[c & 1]);
+        pre = D.template fenced_split<16>(uni, lane_off[c & 1]);
         GD_LDS uint8_t *dst = (GD_LDS uint8_t *)unit + wave * 8192 + c * 1024;
-        F.template dma16_unordered<0>(pre, (uint32_t)(uintptr_t)dst);
+        D.template dma16_unordered<0>(pre, (uint32_t)(uintptr_t)dst);
     };
 
     f32x4 acc[RT][RT];
@@ -824,16 +835,18 @@ int launch_gemm_bf16(const void *args, const FenceArgs &f, int variant, const Sh
             // instructions: the register-staged kernel has both
             if constexpr (V == V_MOD || V == V_CHECK) {
                 // every operand mapped to one contiguous range (all inside, for address checking): fence each once
-                if (ring && !edge && whole_run_host(f, V, p.A, 2 * (uint64_t)p.M * p.K) && whole_run_host(f, V, p.B, 2 * (uint64_t)p.N * p.K) &&
+                if (!edge && whole_run_host(f, V, p.A, 2 * (uint64_t)p.M * p.K) && whole_run_host(f, V, p.B, 2 * (uint64_t)p.N * p.K) &&
                     whole_run_host(f, V, p.C, 2 * (uint64_t)p.M * p.N)) {
-                    hipLaunchKernelGGL((k_gemm_ring<V, true>), grid, block, 0, stream, p, f, tiles_m, tiles_n);
+                    if (ring) hipLaunchKernelGGL((k_gemm_ring<V, true>), grid, block, 0, stream, p, f, tiles_m, tiles_n);
+                    else hipLaunchKernelGGL((k_gemm_units<V, true>), grid, block, 0, stream, p, f, tiles_m, tiles_n);
                     return;
                 }
             }
             if constexpr (V == V_BUF) {
                 // buffer offsets add up by definition: the ring's copies become buffer loads to the LDS, range-checked per lane
-                if (ring && !edge) {
-                    hipLaunchKernelGGL((k_gemm_ring<V, false>), grid, block, 0, stream, p, f, tiles_m, tiles_n);
+                if (!edge) {
+                    if (ring) hipLaunchKernelGGL((k_gemm_ring<V, false>), grid, block, 0, stream, p, f, tiles_m, tiles_n);
+                    else hipLaunchKernelGGL((k_gemm_units<V, false>), grid, block, 0, stream, p, f, tiles_m, tiles_n);
                     return;
                 }
             }

@@ -205,7 +205,7 @@ def test_modulo_mode_rmsnorm_and_gemm_match_the_oracle():
         assert_bf16_close(got, want, what="modulo rmsnorm")
         # (512, 256, 384): the per-array form of the DMA-ring kernel (operands mapped to one contiguous range each),
         # here through a pointer one partition too high and one that is not mapped contiguously (fallback per lane)
-        for (M, N, K) in ((256, 256, 128), (512, 256, 384), (100, 72, 40)):
+        for (M, N, K) in ((256, 256, 128), (512, 256, 384), (256, 512, 320), (100, 72, 40)):      # K = 320: the ring of K = 64 blocks
             A, B, Cc = r.alloc(0, 2 * M * K), r.alloc(0, 2 * K * N), r.alloc(0, 2 * M * N)
             r.upload(0, A, si.f32_to_bf16_bits(si.normal_f32(g, M * K) * np.float32(K ** -0.5)))
             r.upload(0, B, si.f32_to_bf16_bits(si.normal_f32(g, K * N)))
@@ -402,7 +402,7 @@ def test_checking_gemm_stops_threads_with_a_refused_operand_row_or_column(checke
     end = base + size
     g = si.rng(6, 91)
     total = 0
-    for (M, N, K, b_is_nk) in ((256, 256, 128, 1), (512, 256, 384, 1), (300, 200, 72, 1), (64, 40, 24, 0), (50, 70, 33, 1)):
+    for (M, N, K, b_is_nk) in ((256, 256, 128, 1), (512, 256, 384, 1), (256, 256, 320, 1), (300, 200, 72, 1), (64, 40, 24, 0), (50, 70, 33, 1)):
         A_in, B_in, C_in = r.alloc(t, 2 * M * K), r.alloc(t, 2 * K * N), r.alloc(t, 2 * M * N)
         a_bits = si.f32_to_bf16_bits(si.normal_f32(g, M * K) * np.float32(K ** -0.5))
         b_bits = si.f32_to_bf16_bits(si.normal_f32(g, K * N))
@@ -560,7 +560,7 @@ def test_hwcheck_rmsnorm_and_gemm_read_zero_outside_and_drop_stores():
             assert r.sim.last[1] > 0
             images_close_bf16(r, "hwcheck rmsnorm", 0.02 * rows * cols + 2)
             r.dview(base, np.uint8, size).copy_(torch.from_numpy(r.sim.view(base, np.uint8, size)))
-        for (M, N, K, b_is_nk) in ((256, 256, 128, 1), (512, 256, 384, 1), (300, 200, 72, 1), (50, 70, 33, 0)):
+        for (M, N, K, b_is_nk) in ((256, 256, 128, 1), (512, 256, 384, 1), (256, 256, 320, 1), (300, 200, 72, 1), (50, 70, 33, 0)):
             A, B, Cc = r.alloc(t, 2 * M * K), r.alloc(t, 2 * K * N), r.alloc(t, 2 * M * N)
             a_bits = si.f32_to_bf16_bits(si.normal_f32(g, M * K) * np.float32(K ** -0.5))
             r.upload(t, A, a_bits)

@@ -19,7 +19,9 @@ def test_every_global_access_of_the_fenced_kernels_is_fenced():
         assert f"k_rmsnorm_bf16<{v}>" in names and f"k_gemm_nk256<{v}, true>" in names
     for v in range(4):
         assert f"k_gemm_ring<{v}, false>" in names
-    assert "k_gemm_ring<3, true>" in names and "k_gemm_ring<4, true>" in names      # the per-array form of the modulo and checking rules
+    # the per-array form of the modulo and checking rules, the buffer-load form of the hardware-checked rule
+    for kern in ("k_gemm_ring", "k_gemm_units"):
+        assert f"{kern}<3, true>" in names and f"{kern}<4, true>" in names and f"{kern}<5, false>" in names
     fenced = [r for r in rows if r[1] in (1, 2) and (r[2] + r[3]) > 0]
     assert fenced and all(r[4] > 0 for r in fenced if r[1] == 1)        # the 32-bit fence shows up as v_and_b32
     # the fence costs at most a handful of registers (the paper: up to two at -O3)
