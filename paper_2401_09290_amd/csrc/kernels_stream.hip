@@ -84,7 +84,6 @@ __global__ __launch_bounds__(1024) void k_stream(uint64_t pa, uint64_t pb, uint6
     const uint64_t n4 = n >> 2;
     const bool whole = F.whole_run(pb, 16 * n4) && (!OP || F.whole_run(pc, 16 * n4)) && F.whole_run(pa, 16 * n4);
     const uint64_t fb = F.scalar_fence(pb), fc = OP ? F.scalar_fence(pc) : 0, fa_ = F.scalar_fence(pa);   // used only if `whole`
-  for (uint32_t rep = 0; rep < repeat; ++rep) {      // repeat > 1: the cache-resident regime in one launch
     // one logical thread: accesses in the order load b, load c, store a
     auto element = [&](uint64_t i) {
         if (!F.template inside<4>(pb + 4 * i)) { F.fault(); return; }
@@ -96,12 +95,22 @@ __global__ __launch_bounds__(1024) void k_stream(uint64_t pa, uint64_t pb, uint6
         if (!F.template inside<4>(pa + 4 * i)) { F.fault(); return; }
         F.template st<float>(pa + 4 * i, r);
     };
-    if ((ptr_bits & 15) == 0) {
+    auto tail = [&]() {                                   // at most three elements behind the last whole vector
+        if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
+            uint64_t i = 4 * n4 + threadIdx.x;
+            asm volatile("" : "+v"(i));                   // nothing of this is hoisted in front of the vectors
+            element(i);
+        }
+    };
+    const bool aligned = (ptr_bits & 15) == 0;
+    const uint64_t step = (uint64_t)gridDim.x * blockDim.x;
+    // repeat > 1 runs the pass again (the cache-resident regime in one launch); the loop over the passes sits inside
+    // the choice of the path, so that a pass jumps over no code of the paths it does not take
+    if (aligned && whole) {
+        // every array is mapped to one contiguous range and its first byte is fenced: address it like a native kernel
         const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        const uint64_t step = (uint64_t)gridDim.x * blockDim.x;
-        if (whole) {
-            // every array is mapped to one contiguous range and its first byte is fenced: address it like a native kernel
-            const uint32_t lane_off = Fence<V>::template tile_lane_offset<STREAM_TILE>(16 * threadIdx.x);
+        const uint32_t lane_off = Fence<V>::template tile_lane_offset<STREAM_TILE>(16 * threadIdx.x);
+        for (uint32_t rep = 0; rep < repeat; ++rep) {
             for (uint64_t w0 = (uint64_t)blockIdx.x * blockDim.x + 64 * wave; w0 < n4; w0 += step) {   // w0: the tile's first vector
                 if (w0 + (threadIdx.x & 63) >= n4) continue;
                 f32x4 vb = F.template ld_tile16<f32x4, NT>(fb + 16 * w0, lane_off);
@@ -114,9 +123,12 @@ __global__ __launch_bounds__(1024) void k_stream(uint64_t pa, uint64_t pb, uint6
                 }
                 F.template st_tile16<f32x4, NT, true>(fa_ + 16 * w0, lane_off, vb);
             }
-        } else {
-            // a pointer wraps at the partition end inside its array (or, under address checking, an array is
-            // not wholly inside): every vector is fenced (checked) per lane
+            tail();
+        }
+    } else if (aligned) {
+        // a pointer wraps at the partition end inside its array (or, under address checking, an array is
+        // not wholly inside): every vector is fenced (checked) per lane
+        for (uint32_t rep = 0; rep < repeat; ++rep) {
             for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += step) {
                 if (F.CHECKED &&
                     !(F.template inside<16>(pb + 16 * i) && (!OP || F.template inside<16>(pc + 16 * i)) &&
@@ -128,17 +140,12 @@ __global__ __launch_bounds__(1024) void k_stream(uint64_t pa, uint64_t pb, uint6
                     F.template st<f32x4, NT>(pa + 16 * i, v);
                 }
             }
-        }
-        if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {          // at most three elements left
-            uint64_t i = 4 * n4 + threadIdx.x;
-            asm volatile("" : "+v"(i));              // as above: nothing of this is hoisted in front of the tiles
-            element(i);
+            tail();
         }
     } else {
-        const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-        for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) element(i);
+        for (uint32_t rep = 0; rep < repeat; ++rep)
+            for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += step) element(i);
     }
-  }
 }
 
 // ---- launchers -------------------------------------------------------------------
