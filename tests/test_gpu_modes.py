@@ -1,7 +1,9 @@
-"""GPU parity for the two other bounds-checking rules of Section 4.4: the modulo
+"""GPU parity for the two other bounds-checking rules of Section 4.4 -- the modulo
 fence (partitions of any size and alignment) and address checking (an offending
-logical thread stops and is counted).  Same bars as test_gpu_parity.py; the
-fault counters must equal the oracle's violation counts exactly.
+logical thread stops and is counted) -- and for address checking done by the
+memory pipeline (buffer instructions: an access outside reads zero or is dropped).
+Same bars as test_gpu_parity.py; the fault counters must equal the oracle's
+violation counts exactly.
 """
 import numpy as np
 import pytest
