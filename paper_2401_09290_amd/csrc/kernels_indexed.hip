@@ -163,15 +163,18 @@ __global__ __launch_bounds__(1024) void k_scatter_f32_i64(gd_args_scatter p, Fen
     if (!F.CHECKED && ((p.idx | p.src) & 15) == 0) {
         const uint64_t n4 = p.n >> 2;
         // all four fenced addresses and values first, in registers of their own, then the four stores back to back
-        auto four = [&](const u64x2 k01, const u64x2 k23, const f32x4 v) {
-            typename Fence<V>::Handle h0 = F.template fenced<4>(p.dst + 4 * k01[0]), h1 = F.template fenced<4>(p.dst + 4 * k01[1]),
-                                      h2 = F.template fenced<4>(p.dst + 4 * k23[0]), h3 = F.template fenced<4>(p.dst + 4 * k23[1]);
+        using Handle = typename Fence<V>::Handle;
+        auto stores = [&](Handle h0, Handle h1, Handle h2, Handle h3, const f32x4 v) {
             float d0 = p.scale * v[0], d1 = p.scale * v[1], d2 = p.scale * v[2], d3 = p.scale * v[3];
             Fence<V>::keep_apart(h0, h1, h2, h3, d0, d1, d2, d3);
             F.template st_fenced<float>(h0, d0);
             F.template st_fenced<float>(h1, d1);
             F.template st_fenced<float>(h2, d2);
             F.template st_fenced<float>(h3, d3);
+        };
+        auto four = [&](const u64x2 k01, const u64x2 k23, const f32x4 v) {
+            stores(F.template fenced<4>(p.dst + 4 * k01[0]), F.template fenced<4>(p.dst + 4 * k01[1]),
+                   F.template fenced<4>(p.dst + 4 * k23[0]), F.template fenced<4>(p.dst + 4 * k23[1]), v);
         };
         // measured: the nontemporal hint on the source stream slows the scattered stores
         if (F.whole_run(p.idx, 32 * n4) && F.whole_run(p.src, 16 * n4)) {
@@ -186,9 +189,13 @@ __global__ __launch_bounds__(1024) void k_scatter_f32_i64(gd_args_scatter p, Fen
                 u64x2 k01 = F.template ld_tile16<u64x2, true>(t_idx, lane32);
                 u64x2 k23 = F.template ld_tile16<u64x2, true, 16>(t_idx, lane32);
                 f32x4 v = F.template ld_tile16<f32x4>(f_src + 16 * q0, lane16);
-                F.tile_wait(k01, k23);
+                // the indices are back first: their four addresses are fenced while the values are still on the way
+                F.tile_wait_all_but_last(k01, k23);
+                Handle h0 = F.template fenced<4>(p.dst + 4 * k01[0]), h1 = F.template fenced<4>(p.dst + 4 * k01[1]),
+                       h2 = F.template fenced<4>(p.dst + 4 * k23[0]), h3 = F.template fenced<4>(p.dst + 4 * k23[1]);
+                Fence<V>::keep_apart(h0, h1, h2, h3);
                 F.tile_wait(v);
-                four(k01, k23, v);
+                stores(h0, h1, h2, h3, v);
             }
         } else {
             for (uint64_t q = tid; q < n4; q += stride)
