@@ -280,12 +280,15 @@ struct Fence {
         asm volatile("s_waitcnt vmcnt(0)" : "+v"(a), "+v"(b) : : "memory");
     }
     // All but the youngest ld_tile16 have landed (they return in issue order): lets the arithmetic on the first
-    // results run while the last load is still in flight.
+    // results run while the last load is still in flight.  Only in straight-line code, with the number of loads in
+    // flight fixed: between a ld_tile16 and the wait that covers it the compiler must have no reason to touch the
+    // load's registers (the ISA audit checks that no instruction does).
     template <typename T>
     static __device__ __forceinline__ void tile_wait_all_but_last(T &a, T &b)
     {
         asm volatile("s_waitcnt vmcnt(1)" : "+v"(a), "+v"(b) : : "memory");
     }
+
 
     // ---- V_BUF: the partition as a raw buffer --------------------------------------------
     // Descriptor words: base (48 bits), stride 0, num_records = size in bytes, and the

@@ -34,6 +34,9 @@ the same guarantee is checked after the fact, on the assembly text produced by
   base, size and on every kernel argument its own address depends on.  This shows that no
   access bypasses its rule; that the rule's arithmetic and the comparison's sense are right
   is what the parity tests show (images, neighbours' bytes, exact fault counts);
+* in every kernel: no instruction names the result registers of a vector-memory load before an
+  s_waitcnt vmcnt covers that load (some waits are placed by hand, and the compiler does not
+  know that those registers are still in flight);
 * per kernel: loads, stores, fence instructions, VGPR/SGPR counts and the
   register delta against the unfenced build of the same kernel.
 
@@ -584,6 +587,70 @@ def dependency_problems(flow, pretty, variant, fence_offset, explicit_end, own_w
     return problems
 
 
+VMEM_COUNTED = re.compile(r"^(global_load|global_store|global_atomic|buffer_load|buffer_store|buffer_atomic|flat_load|flat_store)")
+VMEM_LOAD_TO_REG = re.compile(r"^(global_load_(?!lds)|buffer_load_)")
+
+
+def vmcnt_of(text):
+    """The vmcnt a wait instruction asks for (gfx9 encoding of the numeric form), or None if it does not wait on it."""
+    m = re.match(r"^s_waitcnt\s+(.*)$", text)
+    if not m:
+        return None
+    arg = m.group(1).strip()
+    v = re.search(r"vmcnt\((\d+)\)", arg)
+    if v:
+        return int(v.group(1))
+    if re.match(r"^(0x[0-9a-f]+|\d+)$", arg):
+        imm = int(arg, 0)
+        return (imm & 0xF) | ((imm >> 14) & 0x3) << 4
+    return None
+
+
+def pending_load_problems(flow, pretty):
+    """No instruction reads or writes the result registers of a vector-memory load before a wait covers it.
+
+    The kernels place some waits by hand (Fence::ld_tile16 / tile_wait): the compiler does not know that the
+    result registers of such a load are still in flight and may copy or reuse them.  From every load to
+    registers the audit walks every path forward, counting the vector-memory instructions issued behind it,
+    until an s_waitcnt vmcnt(k) with k not above that count (the counter runs in issue order, so the load has
+    landed then); any instruction met before that which names one of the load's result registers is reported,
+    except a younger load that only writes them (loads return in issue order)."""
+    problems = []
+    waits = [vmcnt_of(ln.strip()) for ln in flow.body]
+    cap = max([k for k in waits if k is not None], default=0) + 1     # counts above every wait are alike
+    for i, ln in enumerate(flow.body):
+        text = ln.strip()
+        if not VMEM_LOAD_TO_REG.match(text) or re.search(r"\blds\b", text):
+            continue
+        dst = flow.dst[i]
+        if not dst:
+            continue
+        kind, lo, hi = dst[0]
+        seen, stack = set(), [(s_, 0) for s_ in flow.succs[i]]
+        while stack:
+            j, younger = stack.pop()
+            if (j, younger) in seen:
+                continue
+            seen.add((j, younger))
+            t = flow.body[j].strip()
+            k = waits[j]
+            if k is not None and k <= younger:
+                continue                                  # the load has landed on this path
+            over = lambda regs: [r for r in regs if r[0] == kind and not (r[2] < lo or r[1] > hi)]
+            # A younger load may take the same result registers: loads return in issue order, so the older
+            # result (which nothing has read on this path) is overwritten by the younger one, never the reverse.
+            younger_load = VMEM_LOAD_TO_REG.match(t) and not over(srcs(t))
+            touched = over(srcs(t)) if younger_load else over(flow.dst[j] + srcs(t))
+            if touched and not LABEL_RE.match(t):
+                problems.append(f"{pretty}: `{t}` touches v[{lo}:{hi}] of `{text}` before a wait covers the load")
+                continue
+            if flow.ops[j].startswith("s_endpgm"):
+                continue
+            nxt = min(younger + 1, cap) if VMEM_COUNTED.match(t) else younger
+            stack.extend((s_, nxt) for s_ in flow.succs[j])
+    return problems
+
+
 def lint_kernel(name, pretty, body, variant, fence_offset=None, explicit_end=None):
     """fence_offset / explicit_end: byte offset of the fence's parameter block among the kernel arguments and
     the end of the explicit arguments (from the code object's metadata); the dependency rules need them."""
@@ -664,6 +731,7 @@ def lint_kernel(name, pretty, body, variant, fence_offset=None, explicit_end=Non
         problems.append(f"{pretty}: expected an access to the library's own partial-sum array")
     if variant >= 0:
         problems += dependency_problems(flow, pretty, variant, fence_offset, explicit_end, own_ws)
+    problems += pending_load_problems(flow, pretty)
     return problems, loads, stores, fences
 
 

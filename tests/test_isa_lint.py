@@ -115,6 +115,46 @@ def test_audit_follows_fenced_start_plus_offset_chains():
     assert any("base also defined" in p for p in lint_text(low, 2))
 
 
+def test_registers_of_a_load_in_flight_are_left_alone_until_a_wait_covers_it():
+    """Hand-placed waits: between a load and the s_waitcnt vmcnt(k) that covers it (k at most the number of
+    vector-memory instructions issued behind it) nothing may read or write its result registers."""
+    good = """
+    s_and_b64 s[8:9], s[4:5], s[6:7]
+    s_or_b64 s[8:9], s[8:9], s[10:11]
+    v_and_b32 v1, 0x3ff, v0
+    global_load_dwordx4 v[2:5], v1, s[8:9]
+    global_load_dwordx4 v[6:9], v1, s[8:9] offset:1024
+    s_waitcnt vmcnt(1)
+    v_add_f32 v10, v2, v3
+    s_waitcnt vmcnt(0)
+    v_add_f32 v10, v10, v6
+    s_endpgm
+"""
+    pending = lambda text: [p for p in lint_text(text, 2) if "before a wait covers" in p]
+    assert lint_text(good, 2) == []
+    # the second load is read after a wait that only covers the first
+    assert pending(good.replace("    s_waitcnt vmcnt(0)\n", ""))
+    # a copy of the result registers placed before the wait: what a compiler that does not know of the load may do
+    moved = good.replace("    s_waitcnt vmcnt(1)\n", "    v_mov_b32 v12, v3\n    s_waitcnt vmcnt(1)\n")
+    assert moved != good and any("v_mov_b32 v12, v3" in p for p in pending(moved))
+    # so is reusing one of them as a temporary
+    assert pending(good.replace("    s_waitcnt vmcnt(1)\n", "    v_mov_b32 v4, 0\n    s_waitcnt vmcnt(1)\n"))
+    # a store issued behind the loads counts like a load (one counter for both): vmcnt(2) now covers the first
+    # load, and vmcnt(3) covers nothing
+    store = good.replace("    s_waitcnt vmcnt(1)\n", "    global_store_dword v1, v11, s[8:9]\n    s_waitcnt vmcnt(1)\n")
+    assert store != good and not pending(store) and not pending(store.replace("vmcnt(1)", "vmcnt(2)"))
+    assert any("v_add_f32 v10, v2, v3" in p for p in pending(store.replace("vmcnt(1)", "vmcnt(3)")))
+    # one path of two skips the wait
+    branch = good.replace("    s_waitcnt vmcnt(1)\n", "    s_cbranch_scc1 .LBB0_1\n    s_waitcnt vmcnt(1)\n.LBB0_1:\n")
+    assert any("v_add_f32 v10, v2, v3" in p for p in pending(branch))
+    # a younger load into the same registers is in order (loads return in issue order); reading them before its own wait is not
+    again = good.replace("    s_waitcnt vmcnt(1)\n", "    global_load_dwordx4 v[2:5], v1, s[8:9] offset:2048\n    s_waitcnt vmcnt(0)\n")
+    assert lint_text(again, 2) == []
+    assert pending(again.replace("    s_waitcnt vmcnt(0)\n    v_add_f32 v10, v2, v3", "    s_waitcnt vmcnt(1)\n    v_add_f32 v10, v2, v3"))
+    # the numeric form of the wait is read as well: 0x0f70 is vmcnt(0) with the other counters open
+    assert lint_text(good.replace("s_waitcnt vmcnt(0)", "s_waitcnt 0x0f70"), 2) == []
+
+
 # ---- dependency rules (all five rules), on real compiler output with planted mistakes -------
 
 @pytest.mark.skipif(shutil.which("hipcc") is None, reason="needs hipcc")
