@@ -262,9 +262,11 @@ struct Fence {
             buf_store<T, STREAM>((uint32_t)fenced + lane_off, v);
             return;
         }
-        if constexpr (STREAM && THROUGH) asm volatile("global_store_dwordx4 %0, %1, %2 sc1 nt" : : "v"(lane_off), "v"(v), "s"(fenced) : "memory");
-        else if constexpr (STREAM) asm volatile("global_store_dwordx4 %0, %1, %2 nt" : : "v"(lane_off), "v"(v), "s"(fenced) : "memory");
-        else asm volatile("global_store_dwordx4 %0, %1, %2" : : "v"(lane_off), "v"(v), "s"(fenced) : "memory");
+        // s_nop 1: a store of more than 64 bits reads its data up to two wait states late, and the compiler, which
+        // pads its own stores, does not see this one
+        if constexpr (STREAM && THROUGH) asm volatile("global_store_dwordx4 %0, %1, %2 sc1 nt\n\ts_nop 1" : : "v"(lane_off), "v"(v), "s"(fenced) : "memory");
+        else if constexpr (STREAM) asm volatile("global_store_dwordx4 %0, %1, %2 nt\n\ts_nop 1" : : "v"(lane_off), "v"(v), "s"(fenced) : "memory");
+        else asm volatile("global_store_dwordx4 %0, %1, %2\n\ts_nop 1" : : "v"(lane_off), "v"(v), "s"(fenced) : "memory");
     }
 
     // All ld_tile16 issued so far have landed; the values pass through so that no use
@@ -288,8 +290,6 @@ struct Fence {
     {
         asm volatile("s_waitcnt vmcnt(1)" : "+v"(a), "+v"(b) : : "memory");
     }
-
-
     // ---- V_BUF: the partition as a raw buffer --------------------------------------------
     // Descriptor words: base (48 bits), stride 0, num_records = size in bytes, and the
     // gfx9-family data-format word for untyped accesses.  Wave-uniform: built on the

@@ -223,11 +223,11 @@ void k_gemm_nk256(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles
         const u32x4 v = *(const u32x4 *)(park + row * 256 + og * 16);
         const uint64_t dst = p.C + 2 * ((uint64_t)m * p.N + n);
         if (!EDGE) {
-            F.template st<u32x4>(dst, v);
+            F.template st<u32x4, true>(dst, v);
         } else if (m < p.M && n < p.N) {
             const bool row_live = F.inside_run(p.A + (uint64_t)m * run_bytes, run_bytes);
             if (vec_ok && n + 8 <= p.N && row_live && col_live == 0xff && F.template inside<16>(dst)) {
-                F.template st<u32x4>(dst, v);
+                F.template st<u32x4, true>(dst, v);
             } else {
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
@@ -517,7 +517,8 @@ void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_
     // 256 bytes = 32 units of 8 bytes; unit u of row q is kept at u ^ 2*(q%16), so
     // that the 16 rows written together spread over the banks and the two units of
     // a 16-byte granule stay neighbours), then streams it out as 16-byte runs, 16
-    // lanes per row.
+    // lanes per row, with nontemporal stores: C is not read again, and written with plain
+    // stores it takes cache space from the operand panels, which are (8192^3: +2 %).
     uint8_t *park = wave == 0 ? ring0 : wave == 1 ? ring1 : wave == 2 ? ring2 : ring3;
 #pragma unroll
     for (int i = 0; i < RT; ++i)
@@ -539,7 +540,7 @@ void k_gemm_ring(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles_
         const uint32_t row = orow + 4 * it;
         const uint32_t m = m0 + wm * 128 + row, n = n0 + wn * 128 + og * 8;
         const u32x4 v = *(const u32x4 *)(park + row * 256 + ((og ^ (row & 15)) << 4));
-        F.template st<u32x4>(p.C + 2 * ((uint64_t)m * p.N + n), v);
+        F.template st<u32x4, true>(p.C + 2 * ((uint64_t)m * p.N + n), v);
     }
 }
 
@@ -749,7 +750,7 @@ void k_gemm_units(gd_args_gemm p, FenceArgs fa, uint32_t tiles_m, uint32_t tiles
         const uint32_t row = orow + 4 * it;
         const uint32_t m = m0 + wm * 128 + row, n = n0 + wn * 128 + og * 8;
         const u32x4 v = *(const u32x4 *)(park + row * 256 + ((og ^ (row & 15)) << 4));
-        F.template st<u32x4>(p.C + 2 * ((uint64_t)m * p.N + n), v);
+        F.template st<u32x4, true>(p.C + 2 * ((uint64_t)m * p.N + n), v);
     }
 }
 

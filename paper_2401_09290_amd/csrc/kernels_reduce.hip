@@ -163,6 +163,11 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 
 // 512 threads per row (measured against 128, 256 and 1024: 5.5, 5.8 and 5.1 TB/s
 // against 6.05 at the bench shape): two 16-byte chunks per thread cover 8192 columns.
+// The output is written with nontemporal stores: it is not read again, and with plain stores it
+// displaces the input from the caches (4096 x 8192: 6.25 -> 6.6 TB/s, 16384 x 8192: 5.95 -> 7.2,
+// 32768 x 4096: 5.55 -> 6.5; nontemporal loads as well as stores are slower than either alone).
+// A kernel that keeps several rows per workgroup in flight (gains held in registers, rows copied
+// global -> LDS two ahead) was built and measured as well: no faster than this one at any shape.
 constexpr int RMS_WG = 512;
 constexpr int RMS_MAX_CHUNKS = 2;   // 16-byte chunks (8 values) per thread held in registers
 
@@ -239,7 +244,7 @@ __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, Fenc
                 for (int e = 0; e < 4; ++e)
                     o[e] = pack_bf16(bf16_lo(xv[c][e]) * inv * bf16_lo(gv[c][e]),
                                      bf16_hi(xv[c][e]) * inv * bf16_hi(gv[c][e]));
-                F.template st_tile16<u32x4>(fy + 16 * (uint64_t)q0, lane16, o);
+                F.template st_tile16<u32x4, true>(fy + 16 * (uint64_t)q0, lane16, o);
             }
         }
     } else if (vec) {
@@ -281,7 +286,7 @@ __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, Fenc
                 for (int e = 0; e < 4; ++e)
                     o[e] = pack_bf16(bf16_lo(xv[c][e]) * inv * bf16_lo(gv[c][e]),
                                      bf16_hi(xv[c][e]) * inv * bf16_hi(gv[c][e]));
-                F.template st<u32x4>(yrow + 16 * (uint64_t)q, o);
+                F.template st<u32x4, true>(yrow + 16 * (uint64_t)q, o);
             } else {
                 for (int e = 0; e < 8; ++e) {
                     const uint32_t w = xv[c][e >> 1];

@@ -587,7 +587,7 @@ def dependency_problems(flow, pretty, variant, fence_offset, explicit_end, own_w
     return problems
 
 
-VMEM_COUNTED = re.compile(r"^(global_load|global_store|global_atomic|buffer_load|buffer_store|buffer_atomic|flat_load|flat_store)")
+VMEM_LOAD = re.compile(r"^(global_load|buffer_load|flat_load)")
 VMEM_LOAD_TO_REG = re.compile(r"^(global_load_(?!lds)|buffer_load_)")
 
 
@@ -611,10 +611,11 @@ def pending_load_problems(flow, pretty):
 
     The kernels place some waits by hand (Fence::ld_tile16 / tile_wait): the compiler does not know that the
     result registers of such a load are still in flight and may copy or reuse them.  From every load to
-    registers the audit walks every path forward, counting the vector-memory instructions issued behind it,
-    until an s_waitcnt vmcnt(k) with k not above that count (the counter runs in issue order, so the load has
-    landed then); any instruction met before that which names one of the load's result registers is reported,
-    except a younger load that only writes them (loads return in issue order)."""
+    registers the audit walks every path forward, counting the loads issued behind it, until an
+    s_waitcnt vmcnt(k) with k not above that count: loads complete in issue order, so with the load still in
+    flight more than k instructions would be outstanding.  Stores share the counter but complete in an order of
+    their own, so a store behind the load does not count.  Any instruction met before that which names one of
+    the load's result registers is reported, except a younger load that only writes them."""
     problems = []
     waits = [vmcnt_of(ln.strip()) for ln in flow.body]
     cap = max([k for k in waits if k is not None], default=0) + 1     # counts above every wait are alike
@@ -646,8 +647,42 @@ def pending_load_problems(flow, pretty):
                 continue
             if flow.ops[j].startswith("s_endpgm"):
                 continue
-            nxt = min(younger + 1, cap) if VMEM_COUNTED.match(t) else younger
+            nxt = min(younger + 1, cap) if VMEM_LOAD.match(t) else younger
             stack.extend((s_, nxt) for s_ in flow.succs[j])
+    return problems
+
+
+WIDE_STORE = re.compile(r"^(global_store_dwordx[34]|buffer_store_dwordx[34]|flat_store_dwordx[34])\b")
+
+
+def store_data_problems(flow, pretty):
+    """No vector-ALU instruction overwrites the data registers of a store of more than 64 bits in the two
+    wait states behind it (the store reads its data late; the compiler pads its own stores, but it cannot
+    see the ones written as inline assembly)."""
+    problems = []
+    for i, ln in enumerate(flow.body):
+        text = ln.strip()
+        if not WIDE_STORE.match(text):
+            continue
+        op, ops = _split(text)
+        data = _regs(ops[0]) if op.startswith("buffer_store") else _regs(ops[1])
+        if not data or data[0] != "v":
+            continue
+        stack, seen = [(s_, 2) for s_ in flow.succs[i]], set()
+        while stack:
+            j, left = stack.pop()
+            if left <= 0 or (j, left) in seen:
+                continue
+            seen.add((j, left))
+            t = flow.body[j].strip()
+            if LABEL_RE.match(t):
+                stack.extend((s_, left) for s_ in flow.succs[j])
+                continue
+            if t.startswith("v_") and any(r[0] == "v" and not (r[2] < data[1] or r[1] > data[2]) for r in flow.dst[j]):
+                problems.append(f"{pretty}: `{t}` overwrites the data of `{text}` within two wait states")
+            m = re.match(r"^s_nop\s+(\d+)", t)
+            spent = int(m.group(1)) + 1 if m else 1
+            stack.extend((s_, left - spent) for s_ in flow.succs[j])
     return problems
 
 
@@ -732,6 +767,7 @@ def lint_kernel(name, pretty, body, variant, fence_offset=None, explicit_end=Non
     if variant >= 0:
         problems += dependency_problems(flow, pretty, variant, fence_offset, explicit_end, own_ws)
     problems += pending_load_problems(flow, pretty)
+    problems += store_data_problems(flow, pretty)
     return problems, loads, stores, fences
 
 

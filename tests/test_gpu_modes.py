@@ -456,6 +456,69 @@ def images_close_bf16(r, what, budget):
         assert pos.size <= budget, (what, pos.size)
 
 
+def test_rmsnorm_of_many_rows_in_every_rule():
+    """Matrices of a few thousand rows (more workgroups than the chip holds at once) with 4096 or 8192 columns,
+    in every rule, against the oracle: whole pool image, bf16 results within a unit, exact fault counts; through
+    pointers the rule maps back, with the output leaving the partition and the input starting in front of it."""
+    r = Rig([128 * MiB, 4 * MiB])
+    counters = torch.zeros(8, dtype=torch.int64, device="cuda")
+    gd.gd_pool_set_fault_counters(r.pool, counters.data_ptr(), 8)
+    try:
+        g = si.rng(6, 97)
+        t = 0
+        base, size = r.row(t)
+        end = base + size
+        total = 0
+        for rows, cols in ((2050, 8192), (2049, 4096), (3077, 4096)):
+            nbytes = 2 * rows * cols
+            pad = r.alloc(t, 64 * KiB)                # where stores that wrap under the bitwise rule land: nothing reads it
+            x, y, gain = r.alloc(t, nbytes), r.alloc(t, nbytes), r.alloc(t, 2 * cols)
+            r.upload(t, x, si.f32_to_bf16_bits(si.normal_f32(g, rows * cols)))
+            r.upload(t, gain, si.f32_to_bf16_bits(si.uniform_f32(g, cols, 0.5, 1.5)))
+            args = gd.gd_args_rmsnorm(y, x, gain, rows, cols, 1e-6, 0)
+            # every rule on plain operands, and the unfenced kernel bit for bit equal to the bitwise rule
+            r.oracle("rmsnorm_bf16", t, y, x, gain, rows, cols, 1e-6)
+            first = None
+            for mode in (gd.GD_FENCE_BITWISE, gd.GD_FENCE_MODULO, gd.GD_FENCE_CHECK, gd.GD_FENCE_HWCHECK, gd.GD_FENCE_NONE):
+                r.dview(y, np.uint8, nbytes).fill_(0x33)
+                r.launch(t, gd.GD_K_RMSNORM_BF16, args, mode=mode)
+                images_close_bf16(r, f"rmsnorm {rows}x{cols} mode {mode}", 0.02 * rows * cols + 2)
+                got = r.download(y, np.uint16, rows * cols)
+                first = got if first is None else first
+                assert np.array_equal(got, first), mode
+            assert faults(counters, t) == total
+            # pointers that the rule maps back: one partition too high or too low (bitwise and modulo)
+            for mode, omode in ((gd.GD_FENCE_BITWISE, ok.MODE_BITWISE), (gd.GD_FENCE_MODULO, ok.MODE_MODULO)):
+                r.dview(y, np.uint8, nbytes).fill_(0x33)
+                r.launch(t, gd.GD_K_RMSNORM_BF16, gd.gd_args_rmsnorm(y + size, x - size, gain + 3 * size, rows, cols, 1e-6, 0), mode=mode)
+                assert np.array_equal(r.download(y, np.uint16, rows * cols), first), mode
+            if cols == 8192:
+                # the output leaves the partition in its last rows: address checking refuses those threads, the
+                # hardware-checked rule drops their stores, the bitwise rule wraps them to the partition's start
+                hang = 2 * (2 * cols + 24)
+                y_end = end - nbytes + hang
+                for mode, omode in ((gd.GD_FENCE_CHECK, ok.MODE_CHECK), (gd.GD_FENCE_HWCHECK, ok.MODE_HWCHECK), (gd.GD_FENCE_BITWISE, ok.MODE_BITWISE)):
+                    r.launch(t, gd.GD_K_RMSNORM_BF16, gd.gd_args_rmsnorm(y_end, x, gain, rows, cols, 1e-6, 0), mode=mode)
+                    r.oracle("rmsnorm_bf16", t, y_end, x, gain, rows, cols, 1e-6, mode=omode)
+                    assert r.sim.last[2 if mode == gd.GD_FENCE_BITWISE else 1] == hang // 2       # wrapped, resp. refused
+                    if mode == gd.GD_FENCE_CHECK:
+                        total += r.sim.last[1]
+                        assert faults(counters, t) == total
+                    images_close_bf16(r, f"rmsnorm over the end, mode {mode}", 0.02 * rows * cols + 2)
+                    r.dview(base, np.uint8, size).copy_(torch.from_numpy(r.sim.view(base, np.uint8, size)))
+                # the input starts in front of the partition: the hardware-checked rule reads zeros there
+                x_front = base - 2 * (cols + 40)
+                r.launch(t, gd.GD_K_RMSNORM_BF16, gd.gd_args_rmsnorm(y, x_front, gain, rows, cols, 1e-6, 0), mode=gd.GD_FENCE_HWCHECK)
+                r.oracle("rmsnorm_bf16", t, y, x_front, gain, rows, cols, 1e-6, mode=ok.MODE_HWCHECK)
+                assert r.sim.last[1] > 0
+                images_close_bf16(r, "rmsnorm from in front, hardware checked", 0.02 * rows * cols + 2)
+            for ptr in (pad, x, y, gain):
+                r.free(t, ptr)
+            r.dview(base, np.uint8, size).copy_(torch.from_numpy(r.sim.view(base, np.uint8, size)))
+    finally:
+        r.close()
+
+
 def test_hwcheck_on_odd_sized_partitions_matches_the_oracle():
     sizes = [3 * MiB + 256, 5 * MiB + 768, MiB + 256 * 17]
     r = FlexRig(sizes)
