@@ -34,9 +34,11 @@ the same guarantee is checked after the fact, on the assembly text produced by
   base, size and on every kernel argument its own address depends on.  This shows that no
   access bypasses its rule; that the rule's arithmetic and the comparison's sense are right
   is what the parity tests show (images, neighbours' bytes, exact fault counts);
-* in every kernel: no instruction names the result registers of a vector-memory load before an
-  s_waitcnt vmcnt covers that load (some waits are placed by hand, and the compiler does not
-  know that those registers are still in flight);
+* in every kernel (some loads, stores and waits are written by hand, and the compiler neither counts
+  nor pads those): no instruction names the result registers of a vector-memory load before an
+  s_waitcnt vmcnt covers that load; no vector-ALU write to the data registers of a 128-bit store
+  within two wait states; five wait states between a vector-ALU write to a scalar register and a
+  vector-memory instruction that reads it;
 * per kernel: loads, stores, fence instructions, VGPR/SGPR counts and the
   register delta against the unfenced build of the same kernel.
 
@@ -686,6 +688,40 @@ def store_data_problems(flow, pretty):
     return problems
 
 
+VMEM_ANY = re.compile(r"^(global_|buffer_|flat_)(load|store|atomic)")
+
+
+def sgpr_hazard_problems(flow, pretty):
+    """A vector-memory instruction that reads a scalar register written by the vector ALU (v_readfirstlane,
+    a comparison into a register pair, a carry-out) needs five wait states between the two.  The compiler
+    keeps that distance for its own instructions; the audit checks it for all, the hand-written ones included."""
+    problems = []
+    for i, ln in enumerate(flow.body):
+        text = ln.strip()
+        if not VMEM_ANY.match(text):
+            continue
+        used = [r for r in srcs(text) if r[0] == "s"]
+        if not used:
+            continue
+        stack, seen = [(j, 5) for j in flow.preds[i]], set()
+        while stack:
+            j, left = stack.pop()
+            if left <= 0 or (j, left) in seen:
+                continue
+            seen.add((j, left))
+            t = flow.body[j].strip()
+            if LABEL_RE.match(t):
+                stack.extend((k, left) for k in flow.preds[j])
+                continue
+            if t.startswith("v_") and any(d[0] == "s" and any(not (d[2] < u[1] or d[1] > u[2]) for u in used) for d in flow.dst[j]):
+                problems.append(f"{pretty}: `{text}` reads a scalar register that `{t}` wrote fewer than five wait states earlier")
+                continue
+            m = re.match(r"^s_nop\s+(\d+)", t)
+            spent = int(m.group(1)) + 1 if m else 1
+            stack.extend((k, left - spent) for k in flow.preds[j])
+    return problems
+
+
 def lint_kernel(name, pretty, body, variant, fence_offset=None, explicit_end=None):
     """fence_offset / explicit_end: byte offset of the fence's parameter block among the kernel arguments and
     the end of the explicit arguments (from the code object's metadata); the dependency rules need them."""
@@ -768,6 +804,7 @@ def lint_kernel(name, pretty, body, variant, fence_offset=None, explicit_end=Non
         problems += dependency_problems(flow, pretty, variant, fence_offset, explicit_end, own_ws)
     problems += pending_load_problems(flow, pretty)
     problems += store_data_problems(flow, pretty)
+    problems += sgpr_hazard_problems(flow, pretty)
     return problems, loads, stores, fences
 
 

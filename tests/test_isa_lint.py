@@ -178,6 +178,34 @@ def test_data_registers_of_a_wide_store_are_left_alone_for_two_wait_states():
     assert not hazard(good.replace("    s_nop 1\n", "").replace("v_mov_b32 v3, 0", "global_load_dword v3, v1, s[8:9]\n    s_waitcnt vmcnt(0)"))
 
 
+def test_scalar_registers_written_by_the_vector_alu_rest_five_wait_states_before_a_memory_instruction_reads_them():
+    text = """
+    v_readfirstlane_b32 s2, v1
+    s_nop 3
+    s_mov_b32 s3, 0
+    global_load_dword v2, v0, s[2:3]
+    s_waitcnt vmcnt(0)
+    s_endpgm
+"""
+    hazard = lambda t: [p for p in lint_text(t, 0) if "fewer than five wait states" in p]
+    assert not hazard(text)                                            # s_nop 3 = four wait states, plus the s_mov
+    assert hazard(text.replace("s_nop 3", "s_nop 2"))
+    assert hazard(text.replace("    s_nop 3\n", ""))
+    assert not hazard(text.replace("    s_nop 3\n", "").replace("v_readfirstlane_b32 s2, v1", "s_mov_b32 s2, s9"))    # scalar writes are interlocked
+    assert not hazard(text.replace("    s_nop 3\n", "").replace("v_readfirstlane_b32 s2, v1", "v_readfirstlane_b32 s6, v1"))
+    # through a branch: the distance is counted along every path to the access
+    branch = """
+    v_cmp_lt_u32_e64 s[2:3], v1, v2
+    s_cbranch_scc1 .LBB0_2
+    s_nop 4
+.LBB0_2:
+    buffer_load_dword v2, v0, s[0:3], 0 offen
+    s_waitcnt vmcnt(0)
+    s_endpgm
+"""
+    assert hazard(branch) and not hazard(branch.replace("    s_cbranch_scc1 .LBB0_2\n", ""))
+
+
 # ---- dependency rules (all five rules), on real compiler output with planted mistakes -------
 
 @pytest.mark.skipif(shutil.which("hipcc") is None, reason="needs hipcc")
