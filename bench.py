@@ -723,9 +723,42 @@ def run_modes(torch, gd, si, args):
     A, B, Cc = (dp.alloc(0, 2 * M * M) for _ in range(3))
     dp.view(A, 2 * M * M).view(torch.bfloat16).normal_(0.0, M ** -0.5)
     dp.view(B, 2 * M * M).view(torch.bfloat16).normal_()
-    # bitwise and modulo run the DMA-ring kernel; checking and hardware checking need predicated resp. buffer loads
-    # and run the register-staged kernel
+    # every rule runs the DMA-ring kernel here (modulo and checking with A, B and C fenced once each, hardware
+    # checking with buffer loads to the LDS)
     sweep("gemm_8192^3_bf16", gd.GD_K_GEMM_BF16, gd.gd_args_gemm(Cc, A, B, M, M, M, 1), 2.0 * M ** 3, max(3, args.steps // 2), unit="TFLOPs", scale=1e12)
+    # Section 4.4's latency model (Figure 5: cycles of the fence against cycles of an access that hits L1, L2 or
+    # goes to memory): one thread follows a random cycle over the cache lines of a footprint, every load fenced
+    # per lane and dependent on the one before.  The table overwrites a (and b, c for the largest footprint).
+    clk, cout = dp.alloc(0, 256), dp.alloc(0, 256)
+    lat = {}
+    for label, footprint, steps, warm in (("L1_16KiB", 16 << 10, 100000, False), ("L2_1MiB", 1 << 20, 100000, False),
+                                          ("infinity_cache_64MiB", 64 << 20, 50000, True), ("hbm_512MiB", 512 << 20, 20000, False)):
+        tab_host, first = si.chase_table(g, footprint)
+        dp.upload(0, a, tab_host)
+        del tab_host
+        if warm:        # one walk over the whole cycle brings every line into the Infinity Cache
+            gd.gd_launch_fenced(dp.pool, 0, gd.GD_K_CHASE, gd.gd_args_chase(cout, clk, a, footprint // 128, first, 0, 1, 0), stream=st.cuda_stream)
+        else:           # nothing of the table is left in a cache by the upload: 512 MiB of other traffic in between
+            gd.gd_launch_fenced(dp.pool, 0, gd.GD_K_GEMM_BF16, gd.gd_args_gemm(Cc, A, B, M, M, M, 1), stream=st.cuda_stream)
+            gd.gd_launch_fenced(dp.pool, 0, gd.GD_K_RMSNORM_BF16, gd.gd_args_rmsnorm(y, x, gain, rows, cols, 1e-6, 0), stream=st.cuda_stream)
+        row = {}
+        at = first
+        for name, mode in modes:
+            best = None
+            for _ in range(3):
+                # every walk goes on where the last one ended: in the large footprints it meets lines no cache holds yet
+                gd.gd_launch_fenced(dp.pool, 0, gd.GD_K_CHASE, gd.gd_args_chase(cout, clk, a, steps, at, 0, 1, 0), stream=st.cuda_stream, mode=mode)
+                torch.cuda.synchronize()
+                at = int(dp.view(cout, 4).cpu().numpy().view(np.uint32)[0])
+                cycles, ticks = (int(v) for v in dp.view(clk, 16).cpu().numpy().view(np.uint64))
+                if best is None or cycles < best[0]:
+                    best = (cycles, ticks)
+            row[name] = {"cycles_per_access": best[0] / steps, "ns_per_access": best[1] * 10.0 / steps}
+        for name, _ in modes[1:]:
+            row[name]["fence_cycles"] = row[name]["cycles_per_access"] - row["none"]["cycles_per_access"]
+        lat[label] = row
+        log(f"[modes] dependent fenced load, {label}: " + ", ".join(f"{n} {row[n]['cycles_per_access']:.0f} cycles ({row[n]['ns_per_access']:.0f} ns)" for n, _ in modes))
+    res["latency_of_a_fenced_access"] = lat
     res["check_faults_counted"] = int(counters.sum().item())       # all accesses were in bounds: must be 0
 
     # host path, per call, Python binding included (the trivial call shows the binding's own share)

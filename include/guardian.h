@@ -148,7 +148,8 @@ typedef enum {
     GD_K_SUM_F32 = 8,      /* out[0] = sum of in[0..n), fp32 */
     GD_K_RMSNORM_BF16 = 9, /* y[r,:] = x[r,:] / sqrt(mean(x[r,:]^2) + eps) * g, bf16 in/out, fp32 math */
     GD_K_GEMM_BF16 = 10,   /* C = A*B, bf16 in/out, fp32 accumulate on MFMA */
-    GD_K_COUNT = 11
+    GD_K_CHASE = 11,       /* i = tab[i], steps times, per logical thread (latency of a fenced access: Section 4.4, Figure 5) */
+    GD_K_COUNT = 12
 } gd_kernel_id;
 
 /* Argument blocks.  Pointers are tenant-supplied device addresses; they are NOT
@@ -170,6 +171,16 @@ typedef struct { uint64_t y; uint64_t x; uint64_t g; uint32_t rows; uint32_t col
 /* A row-major M x K.  B row-major K x N (b_is_nk == 0) or stored N x K, K contiguous
  * (b_is_nk != 0).  C row-major M x N. */
 typedef struct { uint64_t C; uint64_t A; uint64_t B; uint32_t M; uint32_t N; uint32_t K; uint32_t b_is_nk; } gd_args_gemm;
+
+/* Pointer chase: logical thread t < threads (at most 64: one wavefront) starts at index start + t*lane_step and
+ * replaces its index `steps` times by the uint32 entry tab[index]; every access is fenced like any other, and
+ * each depends on the one before, so steps / elapsed time is the latency of one fenced access (Section 4.4's
+ * model: cycles of the fence against cycles of the access, Figure 5; Section 7.4's cache-resident regime is
+ * chosen by the footprint of the entries the chain visits).  out[t] (uint32) receives thread t's last index.
+ * Thread 0 then stores two uint64 at clk: the shader-clock cycles and the ticks of the constant 100 MHz
+ * counter that its chain took (measurements, not results: no other call defines their value).  Fixed launch
+ * shape (one wavefront); threads == 0 or > 64: GD_ESHAPE. */
+typedef struct { uint64_t out; uint64_t clk; uint64_t tab; uint64_t steps; uint32_t start; uint32_t lane_step; uint32_t threads; uint32_t pad; } gd_args_chase;
 
 #define GD_SUM_WORKSPACE 16384u /* bytes */
 

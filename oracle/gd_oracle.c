@@ -261,6 +261,28 @@ void gdo_saxpy_idx(gdo_ctx *c, uint64_t x, uint64_t y, uint64_t off, double alph
     }
 }
 
+/* Pointer chase (the dependent-access chain behind the latency model of Section 4.4, Figure 5, and the
+ * cache-resident regime of Section 7.4): logical thread t starts at index start + t * lane_step and replaces
+ * its index `steps` times by the 4-byte table entry it points at, every access through the rule like any
+ * other; out[t] receives the last index.  Thread 0 then stores two 8-byte counters at clk (elapsed time on
+ * the device: what they hold is not part of the result; the oracle stores zeros). */
+void gdo_chase(gdo_ctx *c, uint64_t out, uint64_t clk, uint64_t tab, uint64_t steps, uint32_t start,
+               uint32_t lane_step, uint32_t threads)
+{
+    for (uint32_t t = 0; t < threads; t++) {
+        uint32_t idx = start + t * lane_step;
+        uint64_t zero = 0, s;
+        int alive = 1;
+        for (s = 0; s < steps && alive; s++)
+            alive = ld(c, tab + 4 * (uint64_t)idx, 4, &idx);
+        if (!alive) continue;
+        if (!st(c, out + 4 * (uint64_t)t, 4, &idx)) continue;
+        if (t != 0) continue;
+        if (!st(c, clk, 8, &zero)) continue;
+        if (!st(c, clk + 8, 8, &zero)) continue;
+    }
+}
+
 /* Gather of 4-byte values with 64-bit indices: out[i] = tab[idx[i]]. */
 void gdo_gather32_i64(gdo_ctx *c, uint64_t out, uint64_t tab, uint64_t idx, uint64_t n)
 {

@@ -59,6 +59,7 @@ def lib(openmp=False):
             "gdo_bf16_to_double": (dbl, [C.c_uint16]),
             "gdo_store_tid": (None, [ctx, u64, u32, u64]),
             "gdo_fence_addrs": (None, [ctx, u64, u64, u32, u64]),
+            "gdo_chase": (None, [ctx, u64, u64, u64, u64, u32, u32, u32]),
             "gdo_copy": (None, [ctx, u64, u64, u64]),
             "gdo_triad": (None, [ctx, u64, u64, u64, dbl, u64]),
             "gdo_saxpy_idx": (None, [ctx, u64, u64, u64, dbl, u64]),

@@ -16,7 +16,7 @@ GD_OK, GD_EINVAL, GD_ENOTPOW2, GD_ENOMEM, GD_ERANGE, GD_ENOTENANT, GD_EBUSY, GD_
 GD_FENCE_NONE, GD_FENCE_BITWISE, GD_FENCE_MODULO, GD_FENCE_CHECK, GD_FENCE_HWCHECK = range(5)
 (GD_K_STORE_TID, GD_K_FENCE_ADDRS, GD_K_COPY, GD_K_TRIAD, GD_K_SAXPY_IDX, GD_K_GATHER32_I64,
  GD_K_SCATTER_F32_I64, GD_K_GATHER32_I32, GD_K_SUM_F32, GD_K_RMSNORM_BF16, GD_K_GEMM_BF16,
- GD_K_COUNT) = range(12)
+ GD_K_CHASE, GD_K_COUNT) = range(13)
 GD_MIN_PARTITION = 4096
 GD_GRANULE = 256
 GD_SUM_WORKSPACE = 16384
@@ -30,6 +30,8 @@ def _struct(name, fields):
 
 
 gd_args_store_tid = _struct("gd_args_store_tid", [("A", _u64), ("n", _u64), ("j", _u32), ("pad", _u32)])
+gd_args_chase = _struct("gd_args_chase", [("out", _u64), ("clk", _u64), ("tab", _u64), ("steps", _u64), ("start", _u32),
+                                          ("lane_step", _u32), ("threads", _u32), ("pad", _u32)])
 gd_args_fence_addrs = _struct("gd_args_fence_addrs", [("out", _u64), ("in_", _u64), ("n", _u64), ("width", _u32), ("pad", _u32)])
 gd_args_copy = _struct("gd_args_copy", [("a", _u64), ("b", _u64), ("n", _u64)])
 gd_args_triad = _struct("gd_args_triad", [("a", _u64), ("b", _u64), ("c", _u64), ("n", _u64), ("s", _f32), ("repeat", _u32)])

@@ -37,6 +37,7 @@ static const KernelEntry g_registry[GD_K_COUNT] = {
     /* GD_K_SUM_F32         */ {"sum_f32", sizeof(gd_args_sum), launch_sum_f32},
     /* GD_K_RMSNORM_BF16    */ {"rmsnorm_bf16", sizeof(gd_args_rmsnorm), launch_rmsnorm_bf16},
     /* GD_K_GEMM_BF16       */ {"gemm_bf16", sizeof(gd_args_gemm), launch_gemm_bf16},
+    /* GD_K_CHASE           */ {"chase", sizeof(gd_args_chase), launch_chase},
 };
 
 }  // namespace gd

@@ -57,6 +57,40 @@ __global__ __launch_bounds__(1024) void k_fence_addrs(gd_args_fence_addrs p, Fen
     }
 }
 
+// ---- pointer chase: the latency of one fenced access (Section 4.4's model, Figure 5) ----
+// Every load depends on the one before it and goes through the per-lane fence, so the time per step is the
+// latency of the access plus what the rule adds to the dependent chain.  The first index passes through a vector
+// register the compiler knows nothing about: the chain stays on the vector memory path also for one thread.
+template <int V>
+__global__ __launch_bounds__(64) void k_chase(gd_args_chase p, FenceArgs fa)
+{
+    const Fence<V> F(fa);
+    const uint32_t t = threadIdx.x;
+    if (t >= p.threads) return;
+    uint32_t idx;
+    {
+        const uint32_t first = p.start + t * p.lane_step;
+        asm volatile("v_mov_b32 %0, %1" : "=v"(idx) : "v"(first));
+    }
+    const uint64_t cycles0 = __builtin_readcyclecounter();
+    const uint64_t ticks0 = __builtin_amdgcn_s_memrealtime();
+    for (uint64_t s = 0; s < p.steps; ++s) {
+        const uint64_t a = p.tab + 4 * (uint64_t)idx;
+        if (!F.template inside<4>(a)) { F.fault(); return; }
+        idx = F.template ld<uint32_t>(a);
+    }
+    asm volatile("" : "+v"(idx));                        // the last load has landed before the clocks are read again
+    const uint64_t cycles = __builtin_readcyclecounter() - cycles0;
+    const uint64_t ticks = __builtin_amdgcn_s_memrealtime() - ticks0;
+    if (!F.template inside<4>(p.out + 4 * (uint64_t)t)) { F.fault(); return; }
+    F.template st<uint32_t>(p.out + 4 * (uint64_t)t, idx);
+    if (t != 0) return;
+    if (!F.template inside<8>(p.clk)) { F.fault(); return; }
+    F.template st<uint64_t>(p.clk, cycles);
+    if (!F.template inside<8>(p.clk + 8)) { F.fault(); return; }
+    F.template st<uint64_t>(p.clk + 8, ticks);
+}
+
 // ---- copy / triad ------------------------------------------------------------------
 // OP 0: a = b.  OP 1: a = b + s*c (one fused multiply-add per element).
 // Vector path when all pointers are 16-byte aligned (then a 16-byte access equals
@@ -176,6 +210,19 @@ int probe_raw_launches(const gd_args_store_tid &p, const FenceArgs &f, int varia
     const auto t1 = std::chrono::steady_clock::now();
     GD_CHECK_LAUNCH();
     *ns_per_call = std::chrono::duration<double, std::nano>(t1 - t0).count() / iters;
+    return GD_OK;
+}
+
+int launch_chase(const void *args, const FenceArgs &f, int variant, const Shape &shape, hipStream_t stream)
+{
+    const gd_args_chase &p = *(const gd_args_chase *)args;
+    if (shape.grid || shape.block) return GD_EINVAL;
+    if (p.threads == 0 || p.threads > 64) return GD_ESHAPE;
+    const int rc = with_variant(variant, [&](auto v) {
+        hipLaunchKernelGGL((k_chase<decltype(v)::value>), dim3(1), dim3(64), 0, stream, p, f);
+    });
+    if (rc != GD_OK) return rc;
+    GD_CHECK_LAUNCH();
     return GD_OK;
 }
 

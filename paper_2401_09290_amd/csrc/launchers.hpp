@@ -22,6 +22,7 @@ using Launcher = int (*)(const void *args, const FenceArgs &f, int variant, cons
 
 int launch_store_tid(const void *, const FenceArgs &, int, const Shape &, hipStream_t);
 int launch_fence_addrs(const void *, const FenceArgs &, int, const Shape &, hipStream_t);
+int launch_chase(const void *, const FenceArgs &, int, const Shape &, hipStream_t);
 int launch_copy(const void *, const FenceArgs &, int, const Shape &, hipStream_t);
 int launch_triad(const void *, const FenceArgs &, int, const Shape &, hipStream_t);
 int launch_saxpy_idx(const void *, const FenceArgs &, int, const Shape &, hipStream_t);

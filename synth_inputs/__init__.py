@@ -112,6 +112,20 @@ def c5_indices_i32(g, n, table_elems, frac=0.005, oob_hi=1 << 31):
 
 # ---- canaries --------------------------------------------------------------------
 
+def chase_table(g, footprint_bytes, line=128):
+    """uint32 table for the pointer chase: one entry per ``line`` bytes of the footprint is in use, and the
+    used entries form ONE random cycle (entry -> index of the next used entry), so that a walk of any length
+    visits a new cache line at every step and the whole footprint before it repeats.  Unused entries hold
+    their own index.  Returns (table, index of a used entry to start from)."""
+    per = line // 4
+    slots = footprint_bytes // line
+    assert slots >= 2 and footprint_bytes // 4 <= 1 << 32
+    order = g.permutation(slots).astype(np.int64)                 # visiting order of the lines
+    tab = np.arange(footprint_bytes // 4, dtype=np.uint32)
+    tab[order * per] = (np.roll(order, -1) * per).astype(np.uint32)
+    return tab, int(order[0] * per)
+
+
 def canary_pattern(nbytes, byte=0xA5):
     return np.full(nbytes, byte, dtype=np.uint8)
 

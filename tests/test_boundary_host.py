@@ -35,7 +35,7 @@ def test_registry_matches_argument_blocks():
         gd.GD_K_SAXPY_IDX: gd.gd_args_saxpy_idx, gd.GD_K_GATHER32_I64: gd.gd_args_gather,
         gd.GD_K_SCATTER_F32_I64: gd.gd_args_scatter, gd.GD_K_GATHER32_I32: gd.gd_args_gather,
         gd.GD_K_SUM_F32: gd.gd_args_sum, gd.GD_K_RMSNORM_BF16: gd.gd_args_rmsnorm,
-        gd.GD_K_GEMM_BF16: gd.gd_args_gemm,
+        gd.GD_K_GEMM_BF16: gd.gd_args_gemm, gd.GD_K_CHASE: gd.gd_args_chase,
     }
     assert gd.gd_kernel_count() == gd.GD_K_COUNT == len(blocks)
     names = set()

@@ -456,6 +456,59 @@ def images_close_bf16(r, what, budget):
         assert pos.size <= budget, (what, pos.size)
 
 
+def test_pointer_chase_in_every_rule_ends_where_the_oracle_ends():
+    """The dependent chain behind the latency figures: last indices equal the oracle's bit for bit in every rule,
+    also when the walk meets entries that point outside the partition (wrapped, zero, or the thread stops and
+    is counted); the two counters are measurements and only have to be plausible."""
+    r = Rig([4 * MiB, 4 * MiB])
+    counters = torch.zeros(8, dtype=torch.int64, device="cuda")
+    gd.gd_pool_set_fault_counters(r.pool, counters.data_ptr(), 8)
+    try:
+        g = si.rng(7, 2)
+        t = 1
+        base, size = r.row(t)
+        tab_host, first = si.chase_table(g, MiB)
+        tab, out, clk = r.alloc(t, tab_host.nbytes), r.alloc(t, 256), r.alloc(t, 256)
+        total = 0
+        modes = ((gd.GD_FENCE_BITWISE, ok.MODE_BITWISE), (gd.GD_FENCE_MODULO, ok.MODE_MODULO), (gd.GD_FENCE_CHECK, ok.MODE_CHECK),
+                 (gd.GD_FENCE_HWCHECK, ok.MODE_HWCHECK), (gd.GD_FENCE_NONE, ok.MODE_NONE))
+        for planted in (False, True):
+            host = tab_host.copy()
+            if planted:
+                # every 7th line in use points somewhere outside: far beyond, just behind the end, in front of the start
+                used = np.arange(0, host.size, 32)[::7]
+                host[used] = np.where(np.arange(used.size) % 3 == 0, np.uint32(0xFFFFFF00),
+                                      np.where(np.arange(used.size) % 3 == 1, np.uint32((base + size - tab) // 4 + 5), np.uint32(2**32 - 40)))
+            r.upload(t, tab, host)
+            for mode, omode in modes:
+                if planted and mode == gd.GD_FENCE_NONE:
+                    continue                                     # the unfenced kernel only ever sees in-bounds walks
+                # every start is a line in use (entry 0 is one, and so is every 32nd), so that an unfenced walk stays inside
+                for steps, threads, hop, start in ((1000, 1, 0, first), (333, 64, 32, 0), (0, 3, 1, 0)):
+                    for ptr, fill in ((out, 0x11), (clk, 0)):
+                        r.dview(ptr, np.uint8, 256).fill_(fill)
+                        r.sim.view(ptr, np.uint8, 256)[:] = fill
+                    r.launch(t, gd.GD_K_CHASE, gd.gd_args_chase(out, clk, tab, steps, start, hop, threads, 0), mode=mode)
+                    r.oracle("chase", t, out, clk, tab, steps, start, hop, threads, mode=omode)
+                    if mode == gd.GD_FENCE_CHECK:
+                        total += r.sim.last[1]
+                        assert faults(counters, t) == total
+                    if planted and steps:
+                        assert r.sim.last[1] + r.sim.last[2] > 0
+                    r.assert_images_equal(skip=[(clk, 16)], what=f"chase mode {mode} steps {steps} threads {threads}")
+                    cycles, ticks = (int(v) for v in r.download(clk, np.uint64, 2))
+                    if steps == 1000 and not planted:
+                        # a dependent load cannot take under 20 cycles, nor a microsecond; 100 MHz ticks against cycles: 0.5 .. 3 GHz
+                        assert 20 * steps < cycles < 100000 * steps and 5 * ticks < cycles < 40 * ticks + 2000, (cycles, ticks)
+        assert total > 0
+        with pytest.raises(gd.GuardianError):
+            r.launch(t, gd.GD_K_CHASE, gd.gd_args_chase(out, clk, tab, 1, first, 0, 65, 0))
+        with pytest.raises(gd.GuardianError):
+            r.launch(t, gd.GD_K_CHASE, gd.gd_args_chase(out, clk, tab, 1, first, 0, 1, 0), grid=(2, 1, 1))
+    finally:
+        r.close()
+
+
 def test_rmsnorm_of_many_rows_in_every_rule():
     """Matrices of a few thousand rows (more workgroups than the chip holds at once) with 4096 or 8192 columns,
     in every rule, against the oracle: whole pool image, bf16 results within a unit, exact fault counts; through

@@ -411,6 +411,51 @@ def test_store_through_foreign_pointer_is_redirected():
     assert np.all(pool.view(b0 + 64, np.uint32, 100) == 9)
 
 
+def test_pointer_chase_walks_the_cycle_and_every_step_goes_through_the_rule():
+    """Pins of the chase: a walk of as many steps as the table has lines in use is back at its start (the
+    generator builds one cycle), any walk equals the plain Python iteration, and an entry that points outside
+    the partition is wrapped (bitwise, modulo), stops the thread (checking) or reads as zero (hardware
+    checking) -- each computed here by hand."""
+    sizes = [64 * KiB, 64 * KiB]
+    pool, table = make_pool(sizes, fill=0xA5, pool_base=1 << 20)
+    base, size = table[1]
+    tab_host, first = si.chase_table(si.rng(7, 1), 32 * KiB)
+    slots = 32 * KiB // 128
+    assert sorted(np.flatnonzero(tab_host != np.arange(tab_host.size))) == sorted(range(0, tab_host.size, 32))
+    tab, out, clk = base, base + 40 * KiB, base + 41 * KiB
+    pool.view(tab, np.uint32, tab_host.size)[:] = tab_host
+    # one whole cycle; a partial walk against plain iteration; several threads
+    pool.run("chase", table[1], ok.MODE_BITWISE, out, clk, tab, slots, first, 0, 1)
+    assert pool.view(out, np.uint32, 1)[0] == first and pool.last == (0, 0, 0)
+    assert np.all(pool.view(clk, np.uint64, 2) == 0)
+    steps, threads, hop = 77, 5, 32
+    pool.run("chase", table[1], ok.MODE_BITWISE, out, clk, tab, steps, first, hop, threads)
+    for t in range(threads):
+        i = first + t * hop
+        for _ in range(steps):
+            i = int(tab_host[i])
+        assert pool.view(out, np.uint32, threads)[t] == i
+    # the entry after `first` sends the walk 3 entries past the partition's end
+    second = int(tab_host[first])
+    third = int(tab_host[second])
+    beyond = size // 4 + 3
+    for mode, lands in ((ok.MODE_BITWISE, 3), (ok.MODE_MODULO, 3), (ok.MODE_HWCHECK, None), (ok.MODE_CHECK, None)):
+        pool.view(tab, np.uint32, tab_host.size)[:] = tab_host
+        pool.view(tab, np.uint32, tab_host.size)[second] = beyond
+        pool.view(out, np.uint32, 1)[0] = 0xDEAD
+        pool.run("chase", table[1], mode, out, clk, tab, 3, first, 0, 1)
+        got = int(pool.view(out, np.uint32, 1)[0])
+        if mode in (ok.MODE_BITWISE, ok.MODE_MODULO):
+            # first -> second -> (beyond, wrapped to entry 3, which is unused and holds its own index) -> 3
+            assert got == int(pool.view(tab, np.uint32, tab_host.size)[3]) == 3 and pool.last[2] == 1
+        elif mode == ok.MODE_HWCHECK:
+            # the load outside reads zero: the walk continues at entry 0
+            assert got == 0 and pool.last[1] == 1
+        else:
+            assert got == 0xDEAD and pool.last[1] == 1          # the thread stopped: nothing stored
+    assert third != 3
+
+
 def test_fence_addrs_probe_and_scatter_wrap():
     sizes = [16 * KiB, 16 * KiB]
     pool, table = make_pool(sizes, fill=0xA5, pool_base=1 << 20)
