@@ -38,7 +38,12 @@
 //
 // Rules for kernels using this header:
 //   * every global access of tenant data goes through Fence::ld / Fence::st with
-//     the FINAL address of that access (never index off a fenced pointer);
+//     the FINAL address of that access (never index off a fenced pointer) -- or
+//     through the per-array form below: a kernel that has tested with whole_run()
+//     that the fence maps an array to one contiguous range may fence its first
+//     byte once (scalar_fence) and address it as fenced start + offset
+//     (ld_tile16 / st_tile16 / dma16_unordered), which then IS the fence of
+//     every final address;
 //   * a vector access (8/16 bytes) is only issued on an address the kernel has
 //     established to be naturally aligned, so it equals the per-element fence;
 //   * LDS and registers are not fenced (Section 3: not reachable by other
