@@ -125,19 +125,33 @@ __global__ __launch_bounds__(WG) void k_sum_partial(gd_args_sum p, FenceArgs fa)
 }
 
 // ---- sum, pass 2: out[0] = sum of the partials (added in fp64) ---------------------
+// One workgroup wide enough that every thread has at most FIN_PER partials, fetched before any is used: the pass
+// is one memory latency long (the two launches of a sum of 2^27 values: 79.5 us, against 80.5 with 256 threads
+// walking eight partials each).
+constexpr int FIN_WG = 1024;
+constexpr int FIN_PER = 2;
+
 template <int V, bool OWN_WS = false>
-__global__ __launch_bounds__(WG) void k_sum_final(gd_args_sum p, uint32_t n_partials, FenceArgs fa)
+__global__ __launch_bounds__(FIN_WG) void k_sum_final(gd_args_sum p, uint32_t n_partials, FenceArgs fa)
 {
     const Fence<V> F(fa);
-    __shared__ double lds[WAVES];
-    double acc = 0.0;
-    for (uint32_t i = threadIdx.x; i < n_partials; i += WG) {
+    __shared__ double lds[FIN_WG / 64];
+    float v[FIN_PER];
+#pragma unroll
+    for (int u = 0; u < FIN_PER; ++u) {
+        const uint32_t i = threadIdx.x + u * FIN_WG;
         const uint64_t a = p.partials + 4 * (uint64_t)i;
-        if constexpr (OWN_WS) acc += (double)*(const GD_GLOBAL float *)a;
-        else if (F.template inside<4>(a)) acc += (double)F.template ld<float>(a);
-        else F.fault();
+        v[u] = 0.0f;
+        if (i < n_partials) {
+            if constexpr (OWN_WS) v[u] = *(const GD_GLOBAL float *)a;
+            else if (F.template inside<4>(a)) v[u] = F.template ld<float>(a);
+            else F.fault();
+        }
     }
-    const double total = block_sum(acc, lds);
+    double acc = 0.0;
+#pragma unroll
+    for (int u = 0; u < FIN_PER; ++u) acc += (double)v[u];
+    const double total = block_sum<FIN_WG / 64>(acc, lds);
     if (threadIdx.x == 0) {
         if (F.template inside<4>(p.out)) F.template st<float>(p.out, (float)total);
         else F.fault();
@@ -314,6 +328,7 @@ __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, Fenc
 
 constexpr uint32_t SUM_MAX_BLOCKS = 2048;
 static_assert(SUM_MAX_BLOCKS * 4 <= GD_SUM_WORKSPACE, "workspace too small for the partial sums");
+static_assert(SUM_MAX_BLOCKS <= FIN_WG * FIN_PER, "the second pass reads every partial once");
 
 static uint32_t sum_blocks(uint64_t n)
 {
@@ -333,7 +348,7 @@ static int launch_sum(const gd_args_sum &p, const FenceArgs &f, int variant, hip
     if (rc != GD_OK) return rc;
     GD_CHECK_LAUNCH();
     rc = with_variant(variant, [&](auto v) {
-        hipLaunchKernelGGL((k_sum_final<decltype(v)::value, OWN_WS>), dim3(1), dim3(WG), 0, stream, p, blocks, f);
+        hipLaunchKernelGGL((k_sum_final<decltype(v)::value, OWN_WS>), dim3(1), dim3(FIN_WG), 0, stream, p, blocks, f);
     });
     if (rc != GD_OK) return rc;
     GD_CHECK_LAUNCH();
