@@ -309,6 +309,39 @@ __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, Fenc
             }
         }
         if (F.CHECKED && stopped) F.fault(stopped);
+    } else if (((p.x | p.y | p.g) & 15) == 0 && (p.cols & 7) == 0) {
+        // a row wider than the registers hold: read once for the sum and once more, from the caches, for the output
+        const uint32_t chunks = p.cols >> 3;
+        float ss = 0.0f;
+        for (uint32_t q = threadIdx.x; q < chunks; q += RMS_WG) {
+            const u32x4 xv = F.template ld<u32x4>(xrow + 16 * (uint64_t)q);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float a = bf16_lo(xv[e]), b = bf16_hi(xv[e]);
+                ss += a * a;
+                ss += b * b;
+            }
+        }
+        ss = block_sum<RMS_WG / 64>(ss, lds);
+        const float inv = 1.0f / sqrtf(ss * inv_cols + p.eps);
+        uint32_t stopped = 0;
+        for (uint32_t q = threadIdx.x; q < chunks; q += RMS_WG) {
+            const u32x4 xv = F.template ld<u32x4>(xrow + 16 * (uint64_t)q);
+            if (F.template inside<16>(p.g + 16 * (uint64_t)q) && F.template inside<16>(yrow + 16 * (uint64_t)q)) {
+                const u32x4 gv = F.template ld<u32x4>(p.g + 16 * (uint64_t)q);
+                u32x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    o[e] = pack_bf16(bf16_lo(xv[e]) * inv * bf16_lo(gv[e]), bf16_hi(xv[e]) * inv * bf16_hi(gv[e]));
+                F.template st<u32x4, true>(yrow + 16 * (uint64_t)q, o);
+            } else {
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t w = xv[e >> 1];
+                    stopped += !put(8 * q + e, (e & 1) ? bf16_hi(w) : bf16_lo(w), inv);
+                }
+            }
+        }
+        if (F.CHECKED && stopped) F.fault(stopped);
     } else {
         float ss = 0.0f;
         for (uint32_t j = threadIdx.x; j < p.cols; j += RMS_WG) {
