@@ -183,13 +183,14 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 // A kernel that keeps several rows per workgroup in flight (gains held in registers, rows copied
 // global -> LDS two ahead) was built and measured as well: no faster than this one at any shape.
 constexpr int RMS_WG = 512;
-constexpr int RMS_MAX_CHUNKS = 2;   // 16-byte chunks (8 values) per thread held in registers
+// CH: 16-byte chunks (8 values) per thread held in registers -- 2 cover 8192 columns, 4 cover 16384 (the launcher
+// picks the smaller that fits: the wider kernel needs twice the registers for the row and the gains)
 
 // Address checking (Sections 4.3, 4.4): the logical thread of y[r,j] reads all of row r,
 // then g[j], then stores, and returns at its first refused access.  A row of x that is
 // not wholly inside the partition therefore stops -- and counts -- all `cols` threads of
 // the row; a refused g[j] or y[r,j] stops that one thread.
-template <int V>
+template <int V, int CH = 2>
 __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, FenceArgs fa)
 {
     const Fence<V> F(fa);
@@ -213,9 +214,12 @@ __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, Fenc
     };
 
     const bool vec = ((p.x | p.y | p.g) & 15) == 0 && (p.cols & 7) == 0 &&
-                     p.cols <= (uint32_t)(RMS_WG * 8 * RMS_MAX_CHUNKS);
+                     p.cols <= (uint32_t)(RMS_WG * 8 * CH);
     const uint64_t row_bytes = 2 * (uint64_t)p.cols;
-    if (vec && F.whole_run(xrow, row_bytes) && F.whole_run(p.g, row_bytes) && F.whole_run(yrow, row_bytes)) {
+    // (the per-array form only with two chunks: its loads are waited for by hand, and with four conditional loads
+    // in flight the compiler moves their registers before the wait -- the ISA audit reports it; the wider kernel
+    // fences per lane, with loads the compiler counts)
+    if (CH == 2 && vec && F.whole_run(xrow, row_bytes) && F.whole_run(p.g, row_bytes) && F.whole_run(yrow, row_bytes)) {
         // The row, the gains and the output row are each mapped to one contiguous range by the
         // fence (always, unless a pointer wraps at the partition end inside them): their first
         // bytes are fenced once, on the scalar unit, and every wavefront covers 1 KiB tiles at
@@ -224,9 +228,9 @@ __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, Fenc
         const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         const uint32_t lane16 = Fence<V>::template tile_lane_offset<1024>(16 * threadIdx.x);
         const uint64_t fx = F.scalar_fence(xrow), fg = F.scalar_fence(p.g), fy = F.scalar_fence(yrow);
-        u32x4 xv[RMS_MAX_CHUNKS], gv[RMS_MAX_CHUNKS];
+        u32x4 xv[CH], gv[CH];
 #pragma unroll
-        for (int c = 0; c < RMS_MAX_CHUNKS; ++c) {
+        for (int c = 0; c < CH; ++c) {
             const uint32_t q0 = 64 * wave + c * RMS_WG;              // the wavefront's first chunk of this pass over the row
             if (threadIdx.x + c * RMS_WG < chunks) {
                 xv[c] = F.template ld_tile16<u32x4>(fx + 16 * (uint64_t)q0, lane16);
@@ -235,10 +239,9 @@ __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, Fenc
         }
         F.tile_wait(xv[0], xv[1]);
         F.tile_wait(gv[0], gv[1]);
-        static_assert(RMS_MAX_CHUNKS == 2, "the waits above name two chunks");
         float ss = 0.0f;
 #pragma unroll
-        for (int c = 0; c < RMS_MAX_CHUNKS; ++c)
+        for (int c = 0; c < CH; ++c)
             if (threadIdx.x + c * RMS_WG < chunks) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -250,7 +253,7 @@ __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, Fenc
         ss = block_sum<RMS_WG / 64>(ss, lds);
         const float inv = 1.0f / sqrtf(ss * inv_cols + p.eps);
 #pragma unroll
-        for (int c = 0; c < RMS_MAX_CHUNKS; ++c) {
+        for (int c = 0; c < CH; ++c) {
             const uint32_t q0 = 64 * wave + c * RMS_WG;
             if (threadIdx.x + c * RMS_WG < chunks) {
                 u32x4 o;
@@ -263,10 +266,10 @@ __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, Fenc
         }
     } else if (vec) {
         const uint32_t chunks = p.cols >> 3;
-        u32x4 xv[RMS_MAX_CHUNKS];
+        u32x4 xv[CH];
         float ss = 0.0f;
 #pragma unroll
-        for (int c = 0; c < RMS_MAX_CHUNKS; ++c) {
+        for (int c = 0; c < CH; ++c) {
             const uint32_t q = threadIdx.x + c * RMS_WG;
             if (q < chunks) {
                 xv[c] = F.template ld<u32x4>(xrow + 16 * (uint64_t)q);
@@ -279,10 +282,10 @@ __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, Fenc
             }
         }
         // the gains do not depend on the row's sum: fetch them before the reduction's barriers
-        u32x4 gv[RMS_MAX_CHUNKS];
-        bool whole[RMS_MAX_CHUNKS];          // address checking: gain and output chunk both wholly inside
+        u32x4 gv[CH];
+        bool whole[CH];          // address checking: gain and output chunk both wholly inside
 #pragma unroll
-        for (int c = 0; c < RMS_MAX_CHUNKS; ++c) {
+        for (int c = 0; c < CH; ++c) {
             const uint32_t q = threadIdx.x + c * RMS_WG;
             whole[c] = F.template inside<16>(p.g + 16 * (uint64_t)q) && F.template inside<16>(yrow + 16 * (uint64_t)q);
             if (q < chunks && whole[c]) gv[c] = F.template ld<u32x4>(p.g + 16 * (uint64_t)q);
@@ -291,7 +294,7 @@ __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, Fenc
         const float inv = 1.0f / sqrtf(ss * inv_cols + p.eps);
         uint32_t stopped = 0;
 #pragma unroll
-        for (int c = 0; c < RMS_MAX_CHUNKS; ++c) {
+        for (int c = 0; c < CH; ++c) {
             const uint32_t q = threadIdx.x + c * RMS_WG;
             if (q >= chunks) continue;
             if (whole[c]) {
@@ -441,8 +444,10 @@ int launch_rmsnorm_bf16(const void *args, const FenceArgs &f, int variant, const
     if (shape.grid || shape.block) return GD_EINVAL;
     if (p.cols == 0 || p.rows > 0x7fffffffu) return GD_ESHAPE;
     if (p.rows == 0) return GD_OK;
+    const bool four = p.cols > (uint32_t)(RMS_WG * 8 * 2);          // beyond 16384 columns either kernel reads the row twice
     const int rc = with_variant(variant, [&](auto v) {
-        hipLaunchKernelGGL((k_rmsnorm_bf16<decltype(v)::value>), dim3(p.rows), dim3(RMS_WG), 0, stream, p, f);
+        if (four) hipLaunchKernelGGL((k_rmsnorm_bf16<decltype(v)::value, 4>), dim3(p.rows), dim3(RMS_WG), 0, stream, p, f);
+        else hipLaunchKernelGGL((k_rmsnorm_bf16<decltype(v)::value, 2>), dim3(p.rows), dim3(RMS_WG), 0, stream, p, f);
     });
     if (rc != GD_OK) return rc;
     GD_CHECK_LAUNCH();

@@ -542,7 +542,7 @@ def test_sum_against_fp64(n, shift):
 
 
 @pytest.mark.parametrize("rows,cols,shift", [(5, 8192, 0), (33, 4096, 0), (7, 1000, 0), (3, 9000, 0), (4, 8200, 0),
-                                             (6, 257, 0), (9, 512, 2), (0, 64, 0), (3, 16384, 0), (2, 40008, 0)])
+                                             (6, 257, 0), (9, 512, 2), (0, 64, 0), (3, 16384, 0), (5, 12288, 0), (3, 16392, 0), (2, 40008, 0)])
 def test_rmsnorm_against_oracle(rows, cols, shift):
     r = Rig([4 * MiB, 4 * MiB])
     try:
