@@ -365,6 +365,49 @@ def run_c1(torch, gd, si, args):
         torch.cuda.synchronize()
         return a.elapsed_time(b) * 1e3 / (rounds * replays)
 
+    # One graph per tenant, replayed on the tenant's own stream: each tenant's launches follow one another on the
+    # GPU without the host, and the two tenants' kernels can overlap (they fill a quarter of the chip each).
+    def graphs_per_tenant_us_per_round(mode, rounds=200, replays=5):
+        graphs = []
+        torch.cuda.synchronize()
+        for (t, x, y, off, offs, alpha) in plans[False]:
+            cap, graph = torch.cuda.Stream(), torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=cap):
+                cur = torch.cuda.current_stream()
+                for _ in range(rounds):
+                    gd.gd_launch_fenced(dp.pool, t, gd.GD_K_SAXPY_IDX, gd.gd_args_saxpy_idx(x, y, off, n, alpha * 1e-3, 0), stream=cur.cuda_stream, mode=mode)
+            graphs.append(graph)
+
+        def replay_all():
+            for graph, st in zip(graphs, streams):
+                with torch.cuda.stream(st):
+                    graph.replay()
+        for _ in range(2):
+            replay_all()
+        torch.cuda.synchronize()
+        go = torch.cuda.Event(enable_timing=True)
+        ends = [torch.cuda.Event(enable_timing=True) for _ in streams]
+        go.record()
+        for st in streams:
+            st.wait_event(go)
+        for _ in range(replays):
+            replay_all()
+        for st, e in zip(streams, ends):
+            e.record(st)
+        torch.cuda.synchronize()
+        return max(go.elapsed_time(e) for e in ends) * 1e3 / (rounds * replays)
+
+    try:
+        upload(plans[False])
+        res["graph_per_tenant_fenced_inbounds_us_per_round"] = graphs_per_tenant_us_per_round(gd.GD_FENCE_BITWISE)
+        res["graph_per_tenant_unfenced_inbounds_us_per_round"] = graphs_per_tenant_us_per_round(gd.GD_FENCE_NONE)
+        log(f"[c1] one graph per tenant, replayed on two streams: fenced {res['graph_per_tenant_fenced_inbounds_us_per_round']:.2f} / unfenced "
+            f"{res['graph_per_tenant_unfenced_inbounds_us_per_round']:.2f} us per 2-tenant round")
+    except Exception as ex:                       # informational figure: never lose the run over it
+        res["graph_per_tenant_error"] = repr(ex)
+        log(f"[c1] per-tenant graph replay failed: {ex!r}")
+        torch.cuda.synchronize()
+
     try:
         upload(plans[False])
         res["graph_fenced_inbounds_us_per_round"] = graph_us_per_round(gd.GD_FENCE_BITWISE)
