@@ -133,3 +133,60 @@ def test_every_kind_of_kernel_and_the_allocation_free_sum_replay_from_a_graph():
             r.assert_images_equal(skip=outputs + [(ws, gd.GD_SUM_WORKSPACE)], what=f"replay {replay}")
     finally:
         r.close()
+
+
+def test_one_graph_per_tenant_replayed_on_two_streams_at_once():
+    """Each tenant's chain of indexed saxpys (1 % of the offsets out of range, wrapped by the fence into a scratch
+    region of the tenant's own partition) is recorded into a graph of its own and the graphs are replayed on the
+    tenants' streams at the same time: the tenants' kernels overlap on the chip, and every replay must leave what
+    the oracle computes for the chains run one after the other (the tenants share nothing, so the order between
+    them cannot matter)."""
+    from test_gpu_parity import hazard_free_offsets
+    r = Rig([4 * MiB, 4 * MiB])
+    try:
+        n, rounds, replays = 65536, 20, 3
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        plan, graphs = [], []
+        for t in (0, 1):
+            g = si.rng(1, 70 + t)
+            base, size = r.row(t)
+            x, y, off, scratch = (r.alloc(t, 4 * n) for _ in range(4))
+            offs, where = hazard_free_offsets(g, n, x, y, scratch, 4 * n, base, size)
+            assert len(where) == 655
+            r.upload(t, x, si.uniform_f32(g, n))
+            r.upload(t, y, si.uniform_f32(g, n))
+            r.upload(t, scratch, np.zeros(n, np.float32))
+            r.upload(t, off, offs)
+            plan.append((t, x, y, off, scratch))
+        torch.cuda.synchronize()
+        for (t, x, y, off, scratch) in plan:
+            cap, graph = torch.cuda.Stream(), torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=cap):
+                for _ in range(rounds):
+                    r.launch(t, gd.GD_K_SAXPY_IDX, gd.gd_args_saxpy_idx(x, y, off, n, 0.25, 0), stream=torch.cuda.current_stream().cuda_stream)
+            graphs.append(graph)
+        for replay in range(replays):
+            for graph, st in zip(graphs, streams):
+                with torch.cuda.stream(st):
+                    graph.replay()
+            torch.cuda.synchronize()
+            for (t, x, y, off, scratch) in plan:
+                for _ in range(rounds):
+                    r.oracle("saxpy_idx", t, x, y, off, 0.25, n)
+                assert r.sim.last[2] >= 3 * 655
+            results = [(p, 4 * n) for (t, x, y, off, scratch) in plan for p in (y, scratch)]
+            for (p, nb) in results:
+                # words equal bit for bit, or saxpy results that differ in the last places (fused multiply-add
+                # against fp64 then one rounding, accumulated over the rounds); a wrapped load may have read anything
+                got, want = r.download(p, np.float32, n), r.sim.view(p, np.float32, n)
+                differ = np.flatnonzero(got.view(np.uint32) != want.view(np.uint32))
+                assert np.all(np.isfinite(got[differ])) and np.all(np.isfinite(want[differ])), (replay, hex(p))
+                assert np.all(np.abs(got[differ] - want[differ]) <= 4e-6 * np.maximum(1.0, np.abs(want[differ]))), (replay, hex(p))
+            # everything but the fp32 results (within tolerance above) byte for byte
+            r.assert_images_equal(skip=results, what=f"replay {replay}")
+            # both sides go on from the same bits
+            for (p, nb) in results:
+                r.dview(p, np.uint8, nb).copy_(torch.from_numpy(r.sim.view(p, np.uint8, nb)))
+            torch.cuda.synchronize()
+    finally:
+        r.close()
