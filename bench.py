@@ -39,8 +39,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--configs", default="c3,c4,power,c2,c1,c5,modes",
                     help="comma list out of c1..c5 (c3 is the headline), power (GEMM against the chip's power limit), "
-                         "modes (the paper's three rules side by side) and gatherpolicy (cache-policy bits on random loads; "
-                         "not in the default list)")
+                         "modes (the paper's three rules side by side), gatherpolicy (cache-policy bits on random loads) and shapes "
+                         "(RMSNorm against the shape, gather against the table size); the last two are not in the default list")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--prewarm-ms", type=float, default=250.0,
                     help="untimed launches in front of every measurement until this much GPU time has passed "
@@ -698,6 +698,45 @@ def run_gatherpolicy(torch, gd, si, args):
     return res
 
 
+def run_shapes(torch, gd, si, args):
+    """Not part of the default run: RMSNorm over matrices of several shapes (cache resident and not, rows of up to
+    32768 columns) and the int64 gather against the size of its table, fenced (bitwise) and unfenced."""
+    log("[shapes] RMSNorm against the shape, gather against the table size")
+    dp = DevPool(torch, gd, [4 * GiB])
+    st = torch.cuda.Stream()
+    res = {"workload": "1 tenant, 4 GiB partition, all accesses in bounds", "rmsnorm": {}, "gather_i64_2^26_indices": {}}
+    both = (("fenced", gd.GD_FENCE_BITWISE), ("unfenced", gd.GD_FENCE_NONE))
+    for rows, cols in ((4096, 8192), (16384, 8192), (8192, 4096), (32768, 4096), (2730, 12288), (2048, 16384), (1024, 32768), (4096, 8200), (4096, 8190)):
+        nbytes = 2 * rows * cols
+        x, y, gain = dp.alloc(0, nbytes), dp.alloc(0, nbytes), dp.alloc(0, 2 * cols)
+        dp.view(x, nbytes).view(torch.bfloat16).normal_()
+        dp.view(gain, 2 * cols).view(torch.bfloat16).uniform_(0.5, 1.5)
+        kargs = gd.gd_args_rmsnorm(y, x, gain, rows, cols, 1e-6, 0)
+        row = {}
+        for name, mode in both:
+            sec = solo_avg_seconds(torch, st, lambda: gd.gd_launch_fenced(dp.pool, 0, gd.GD_K_RMSNORM_BF16, kargs, stream=st.cuda_stream, mode=mode), max(10, args.steps))
+            row[name + "_GBps"], row[name + "_us"] = round(2 * nbytes / sec / 1e9, 1), round(sec * 1e6, 2)
+        res["rmsnorm"][f"{rows}x{cols}"] = row
+        log(f"[shapes] rmsnorm {rows} x {cols}: fenced {row['fenced_GBps']} / unfenced {row['unfenced_GBps']} GB/s")
+        for ptr in (x, y, gain):
+            gd.gd_free(dp.pool, 0, ptr)
+    n = 1 << 26
+    tab, idx, out = dp.alloc(0, 4 << 28), dp.alloc(0, 8 * n), dp.alloc(0, 4 * n)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(si.SEED0 + 2000)
+    for lg in (16, 20, 22, 24, 26, 28):
+        dp.view(idx, 8 * n).view(torch.int64).random_(0, 1 << lg, generator=gen)
+        kargs = gd.gd_args_gather(out, tab, idx, n)
+        row = {}
+        for name, mode in both:
+            sec = solo_avg_seconds(torch, st, lambda: gd.gd_launch_fenced(dp.pool, 0, gd.GD_K_GATHER32_I64, kargs, stream=st.cuda_stream, mode=mode), max(3, args.steps // 2))
+            row[name + "_us"], row[name + "_Gloads_per_s"] = round(sec * 1e6, 1), round(n / sec / 1e9, 1)
+        res["gather_i64_2^26_indices"][f"table_{4 << lg >> 20 if lg >= 18 else 0.25}_MiB"] = row
+        log(f"[shapes] gather, table of 2^{lg} elements: fenced {row['fenced_us']} / unfenced {row['unfenced_us']} us ({row['fenced_Gloads_per_s']} G loads/s)")
+    dp.close()
+    return res
+
+
 # ---------------------------------------------------------------------------------
 # the paper's three bounds-checking rules side by side; cache-resident regime; host path
 # ---------------------------------------------------------------------------------
@@ -958,7 +997,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
-    runners = {"c1": run_c1, "c2": run_c2, "c3": run_c3, "c4": run_c4, "c5": run_c5, "modes": run_modes, "power": run_power, "gatherpolicy": run_gatherpolicy}
+    runners = {"c1": run_c1, "c2": run_c2, "c3": run_c3, "c4": run_c4, "c5": run_c5, "modes": run_modes, "power": run_power, "gatherpolicy": run_gatherpolicy, "shapes": run_shapes}
     wanted = [c.strip() for c in args.configs.split(",") if c.strip()]
     per = {}
     for c in wanted:
