@@ -804,16 +804,6 @@ int launch_mfma_probe(uint64_t operands, uint64_t out, uint32_t blocks, uint32_t
 
 // ---- launcher ---------------------------------------------------------------------------
 
-// Host twin of Fence<V>::whole_run for the two rules whose GEMM uses it (mask holds the partition size there).
-static bool whole_run_host(const FenceArgs &f, int variant, uint64_t start, uint64_t bytes)
-{
-    const uint64_t size = f.mask;
-    if (bytes > size) return false;
-    const uint64_t diff = start - f.base;                       // wrap-around, as on the device
-    if (variant == V_CHECK) return diff <= size - bytes;
-    return diff % size <= size - bytes;                          // V_MOD: the image of the first byte has `bytes` bytes behind it
-}
-
 int launch_gemm_bf16(const void *args, const FenceArgs &f, int variant, const Shape &shape,
                      hipStream_t stream)
 {

@@ -190,7 +190,13 @@ constexpr int RMS_WG = 512;
 // then g[j], then stores, and returns at its first refused access.  A row of x that is
 // not wholly inside the partition therefore stops -- and counts -- all `cols` threads of
 // the row; a refused g[j] or y[r,j] stops that one thread.
-template <int V, int CH = 2>
+// TILE: the launcher has found that the fence maps x, g and y each to one contiguous range (Fence::whole_run on the
+// whole matrices; under address checking: all three inside, so that no thread can be refused), the pointers
+// 16-byte aligned and the row at most 8192 columns, a multiple of 8.  That instance holds the per-array path alone
+// (it repeats the test per row): with every path in one kernel a workgroup ran ~100 scalar instructions and ten
+// branches before its first load, which rows of 4096 columns and fewer do not hide (fenced 9-13 % behind
+// unfenced there).  The other instance holds the per-lane paths.
+template <int V, int CH = 2, bool TILE = false>
 __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, FenceArgs fa)
 {
     const Fence<V> F(fa);
@@ -199,27 +205,17 @@ __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, Fenc
     const uint64_t xrow = p.x + 2 * row * p.cols;
     const uint64_t yrow = p.y + 2 * row * p.cols;
     const float inv_cols = 1.0f / (float)p.cols;
-
-    if (F.CHECKED && !F.inside_run(xrow, 2 * (uint64_t)p.cols)) {       // workgroup-uniform
-        if (threadIdx.x == 0) F.fault(p.cols);
-        return;
-    }
-    // one output element under address checking: false = its thread stops (counted by the caller)
-    auto put = [&](uint32_t j, float x, float inv) -> bool {
-        if (!F.template inside<2>(p.g + 2 * (uint64_t)j)) return false;
-        const float g = bf16_lo(F.template ld<uint16_t>(p.g + 2 * (uint64_t)j));
-        if (!F.template inside<2>(yrow + 2 * (uint64_t)j)) return false;
-        F.template st<uint16_t>(yrow + 2 * (uint64_t)j, (uint16_t)f32_to_bf16(x * inv * g));
-        return true;
-    };
-
     const bool vec = ((p.x | p.y | p.g) & 15) == 0 && (p.cols & 7) == 0 &&
                      p.cols <= (uint32_t)(RMS_WG * 8 * CH);
     const uint64_t row_bytes = 2 * (uint64_t)p.cols;
-    // (the per-array form only with two chunks: its loads are waited for by hand, and with four conditional loads
-    // in flight the compiler moves their registers before the wait -- the ISA audit reports it; the wider kernel
-    // fences per lane, with loads the compiler counts)
-    if (CH == 2 && vec && F.whole_run(xrow, row_bytes) && F.whole_run(p.g, row_bytes) && F.whole_run(yrow, row_bytes)) {
+
+    if constexpr (TILE) {
+        // (the per-array form only with two chunks: its loads are waited for by hand, and with four conditional loads
+        // in flight the compiler moves their registers before the wait -- the ISA audit reports it; the wider kernel
+        // fences per lane, with loads the compiler counts)
+        static_assert(CH == 2, "the per-array path holds two chunks per thread");
+        if (!(vec && F.whole_run(xrow, row_bytes) && F.whole_run(p.g, row_bytes) && F.whole_run(yrow, row_bytes)))
+            return;                                                 // never taken: the launcher tested the same for all rows
         // The row, the gains and the output row are each mapped to one contiguous range by the
         // fence (always, unless a pointer wraps at the partition end inside them): their first
         // bytes are fenced once, on the scalar unit, and every wavefront covers 1 KiB tiles at
@@ -264,7 +260,23 @@ __global__ __launch_bounds__(RMS_WG) void k_rmsnorm_bf16(gd_args_rmsnorm p, Fenc
                 F.template st_tile16<u32x4, true>(fy + 16 * (uint64_t)q0, lane16, o);
             }
         }
-    } else if (vec) {
+        return;
+    }
+
+    if (F.CHECKED && !F.inside_run(xrow, 2 * (uint64_t)p.cols)) {       // workgroup-uniform
+        if (threadIdx.x == 0) F.fault(p.cols);
+        return;
+    }
+    // one output element under address checking: false = its thread stops (counted by the caller)
+    auto put = [&](uint32_t j, float x, float inv) -> bool {
+        if (!F.template inside<2>(p.g + 2 * (uint64_t)j)) return false;
+        const float g = bf16_lo(F.template ld<uint16_t>(p.g + 2 * (uint64_t)j));
+        if (!F.template inside<2>(yrow + 2 * (uint64_t)j)) return false;
+        F.template st<uint16_t>(yrow + 2 * (uint64_t)j, (uint16_t)f32_to_bf16(x * inv * g));
+        return true;
+    };
+
+    if (vec) {
         const uint32_t chunks = p.cols >> 3;
         u32x4 xv[CH];
         float ss = 0.0f;
@@ -445,9 +457,15 @@ int launch_rmsnorm_bf16(const void *args, const FenceArgs &f, int variant, const
     if (p.cols == 0 || p.rows > 0x7fffffffu) return GD_ESHAPE;
     if (p.rows == 0) return GD_OK;
     const bool four = p.cols > (uint32_t)(RMS_WG * 8 * 2);          // beyond 16384 columns either kernel reads the row twice
+    const uint64_t row_bytes = 2 * (uint64_t)p.cols;
+    const bool tile = !four && (p.cols & 7) == 0 && ((p.x | p.y | p.g) & 15) == 0 &&
+                      whole_run_host(f, variant, p.x, row_bytes * p.rows) && whole_run_host(f, variant, p.g, row_bytes) &&
+                      whole_run_host(f, variant, p.y, row_bytes * p.rows);
     const int rc = with_variant(variant, [&](auto v) {
-        if (four) hipLaunchKernelGGL((k_rmsnorm_bf16<decltype(v)::value, 4>), dim3(p.rows), dim3(RMS_WG), 0, stream, p, f);
-        else hipLaunchKernelGGL((k_rmsnorm_bf16<decltype(v)::value, 2>), dim3(p.rows), dim3(RMS_WG), 0, stream, p, f);
+        constexpr int V = decltype(v)::value;
+        if (four) hipLaunchKernelGGL((k_rmsnorm_bf16<V, 4, false>), dim3(p.rows), dim3(RMS_WG), 0, stream, p, f);
+        else if (tile) hipLaunchKernelGGL((k_rmsnorm_bf16<V, 2, true>), dim3(p.rows), dim3(RMS_WG), 0, stream, p, f);
+        else hipLaunchKernelGGL((k_rmsnorm_bf16<V, 2, false>), dim3(p.rows), dim3(RMS_WG), 0, stream, p, f);
     });
     if (rc != GD_OK) return rc;
     GD_CHECK_LAUNCH();

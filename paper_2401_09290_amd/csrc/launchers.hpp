@@ -86,6 +86,20 @@ inline int with_variant(int variant, F &&launch)
     }
 }
 
+// Host twin of Fence<V>::whole_run: the fence maps [start, start + bytes) to one contiguous range (under
+// address checking: the range lies inside the partition).  Launchers use it to choose a kernel that fences an
+// array once; such a kernel repeats the test on the device.
+inline bool whole_run_host(const FenceArgs &f, int variant, uint64_t start, uint64_t bytes)
+{
+    if (variant == V_NONE || variant == V_BUF) return true;
+    if (variant == V_BIT32 || variant == V_BIT64) return (((start & f.mask) + (bytes ? bytes - 1 : 0)) & ~f.mask) == 0;
+    const uint64_t size = f.mask;
+    if (bytes > size) return false;
+    const uint64_t diff = start - f.base;                       // wrap-around, as on the device
+    if (variant == V_CHECK) return diff <= size - bytes;
+    return diff % size <= size - bytes;                          // V_MOD: the image of the first byte has `bytes` bytes behind it
+}
+
 // Last HIP error seen by a launcher on this thread (0 = hipSuccess).
 void note_hip_error(hipError_t e);
 #define GD_CHECK_LAUNCH()                                  \

@@ -39,7 +39,7 @@ GiB, MiB = 1 << 30, 1 << 20
 ALGORITHMIC = {
     "k_stream<V, 0, true>": 2 * GiB, "k_stream<V, 1, true>": 3 * GiB,
     "k_gather32<V, 1>": 16 << 26, "k_scatter_f32_i64<V>": 16 << 26, "k_gather32<V, 0>": 12 << 24,
-    "k_sum_partial<V, false>": 4 << 27, "k_rmsnorm_bf16<V, 2>": 4 * 4096 * 8192, "k_gemm_ring<V>": 3 * 128 * MiB, "k_gemm_ring<V, false>": 3 * 128 * MiB, "k_gemm_ring<V, true>": 3 * 128 * MiB,
+    "k_sum_partial<V, false>": 4 << 27, "k_rmsnorm_bf16<V, 2, true>": 4 * 4096 * 8192, "k_gemm_ring<V>": 3 * 128 * MiB, "k_gemm_ring<V, false>": 3 * 128 * MiB, "k_gemm_ring<V, true>": 3 * 128 * MiB,
 }
 
 
