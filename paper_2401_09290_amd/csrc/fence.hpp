@@ -258,7 +258,8 @@ struct Fence {
 
     // THROUGH (with STREAM): the nontemporal store is also written through at device scope ("sc1 nt").  Measured
     // on 1 GiB arrays of random values: copy 316.5 us against 320.4 us for "nt" alone (+1.2 %), triad unchanged
-    // (479 us; a plain store: 512 us).  Used where it was measured, by copy and triad.
+    // (479 us; a plain store: 512 us); on arrays of 64 to 256 MiB the triad is 1.5 to 7 % slower with it.  Used by
+    // the copy.
     template <typename T, bool STREAM = false, bool THROUGH = false>
     __device__ __forceinline__ void st_tile16(uint64_t fenced, uint32_t lane_off, T v) const
     {

@@ -155,7 +155,9 @@ __global__ __launch_bounds__(1024) void k_stream(uint64_t pa, uint64_t pb, uint6
                 } else {
                     F.tile_wait(vb);
                 }
-                F.template st_tile16<f32x4, NT, true>(fa_ + 16 * w0, lane_off, vb);
+                // the copy also writes through at device scope (+1 to 2 % from 2^26 elements up); the triad gains nothing
+                // from that at 2^27 and 2^28 and loses 1.5 to 7 % at 2^24 to 2^26
+                F.template st_tile16<f32x4, NT, OP == 0>(fa_ + 16 * w0, lane_off, vb);
             }
             tail();
         }
