@@ -665,6 +665,21 @@ def run_power(torch, gd, si, args):
     dp.upload(0, B, b_bits)
     for name, mode in (("gemm_fenced_normal_operands", gd.GD_FENCE_BITWISE), ("gemm_unfenced_normal_operands", gd.GD_FENCE_NONE)):
         loop(name, lambda: gd.gd_launch_fenced(dp.pool, 0, gd.GD_K_GEMM_BF16, kargs, stream=st.cuda_stream, mode=mode), flop)
+    # context only, not part of the path: the vendor library's kernel for the same product on the same operands under
+    # the same power cap (torch.matmul of the two bf16 matrices where they lie in the pool; B is stored N x K)
+    try:
+        ta = dp.view(A, 2 * M * K).view(torch.bfloat16).view(M, K)
+        tb = dp.view(B, 2 * M * K).view(torch.bfloat16).view(N, K)
+        tc = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+
+        def vendor():
+            with torch.cuda.stream(st):
+                torch.matmul(ta, tb.t(), out=tc)
+        loop("vendor_library_gemm_normal_operands", vendor, flop)
+        del ta, tb, tc
+    except Exception as ex:                       # context figure: never lose the run over it
+        res["vendor_library_error"] = repr(ex)
+        torch.cuda.synchronize()
     dp.view(A, 2 * M * K).zero_()
     dp.view(B, 2 * M * K).zero_()
     loop("gemm_fenced_zero_operands", lambda: gd.gd_launch_fenced(dp.pool, 0, gd.GD_K_GEMM_BF16, kargs, stream=st.cuda_stream, mode=gd.GD_FENCE_BITWISE), flop)
