@@ -38,7 +38,7 @@ the same guarantee is checked after the fact, on the assembly text produced by
   nor pads those): no instruction names the result registers of a vector-memory load before an
   s_waitcnt vmcnt covers that load; no vector-ALU write to the data registers of a 128-bit store
   within two wait states; five wait states between a vector-ALU write to a scalar register and a
-  vector-memory instruction that reads it;
+  vector-memory instruction that reads it; one wait state between a write of M0 and a global -> LDS copy;
 * per kernel: loads, stores, fence instructions, VGPR/SGPR counts and the
   register delta against the unfenced build of the same kernel.
 
@@ -722,6 +722,24 @@ def sgpr_hazard_problems(flow, pretty):
     return problems
 
 
+LDS_DMA = re.compile(r"^(global_load_lds_|buffer_load_\S+ .*\blds\b)")
+
+
+def m0_hazard_problems(flow, pretty):
+    """A global -> LDS copy takes its LDS address from M0: one wait state between the scalar write of M0 and
+    the copy (the hand-written copies carry an s_nop 0)."""
+    problems = []
+    for i, ln in enumerate(flow.body):
+        text = ln.strip()
+        if not LDS_DMA.match(text):
+            continue
+        for j in flow.preds[i]:
+            t = flow.body[j].strip()
+            if re.match(r"^s_\w+\s+m0\b", t):
+                problems.append(f"{pretty}: `{text}` directly behind `{t}`: M0 needs one wait state")
+    return problems
+
+
 def lint_kernel(name, pretty, body, variant, fence_offset=None, explicit_end=None):
     """fence_offset / explicit_end: byte offset of the fence's parameter block among the kernel arguments and
     the end of the explicit arguments (from the code object's metadata); the dependency rules need them."""
@@ -805,6 +823,7 @@ def lint_kernel(name, pretty, body, variant, fence_offset=None, explicit_end=Non
     problems += pending_load_problems(flow, pretty)
     problems += store_data_problems(flow, pretty)
     problems += sgpr_hazard_problems(flow, pretty)
+    problems += m0_hazard_problems(flow, pretty)
     return problems, loads, stores, fences
 
 

@@ -206,6 +206,23 @@ def test_scalar_registers_written_by_the_vector_alu_rest_five_wait_states_before
     assert hazard(branch) and not hazard(branch.replace("    s_cbranch_scc1 .LBB0_2\n", ""))
 
 
+def test_m0_rests_one_wait_state_before_a_copy_to_the_lds():
+    text = """
+    s_and_b64 s[8:9], s[4:5], s[6:7]
+    s_or_b64 s[8:9], s[8:9], s[10:11]
+    v_and_b32 v1, 0x3ff, v0
+    s_mov_b32 m0, s12
+    s_nop 0
+    global_load_lds_dwordx4 v1, s[8:9]
+    s_waitcnt vmcnt(0)
+    s_endpgm
+"""
+    hazard = lambda t: [p for p in lint_text(t, 2) if "M0 needs one wait state" in p]
+    assert lint_text(text, 2) == []
+    assert hazard(text.replace("    s_nop 0\n", ""))
+    assert hazard(text.replace("    s_nop 0\n", "").replace("s_mov_b32 m0, s12", "s_add_u32 m0, s12, 16"))
+
+
 # ---- dependency rules (all five rules), on real compiler output with planted mistakes -------
 
 @pytest.mark.skipif(shutil.which("hipcc") is None, reason="needs hipcc")
